@@ -1,0 +1,55 @@
+"""One model update w <- w + Delta_1 + Delta_2 of the hybrid-order optimiser
+(Eq. 4 and Eq. 12; with a dual variable pi, Eq. 14), float64.  The base
+first-order optimiser is heavy-ball momentum.  Test infrastructure only.
+
+Readings of points the paper leaves open:
+  * The base optimiser returns a descent vector (its sign and learning rate
+    are inside it, since the update is w + Delta_1 + Delta_2): the buffer is
+    b <- momentum * b + x and the returned vector is -lr * b.
+  * Eq. 14 names "g_1" inside Delta_2 without saying whether it is the
+    projection of g_t or of g_t + pi.  `g1_reading="projected"` (default)
+    removes the projection of g_t + pi, mirroring Eq. 12; "literal" removes the
+    projection of g_t only.  With V-hat fixed and a linear base optimiser both
+    give the same Delta_2.
+  * Eq. 4 and Eq. 14 write a plain inverse of A_1 (+ sigma I): `curv_mode =
+    "signed"` is that; "abs" divides by |a-hat| + sigma instead.
+  * The term sigma (w_a - w) of the gradient of the augmented Lagrangian does
+    not appear in Eq. 14 and is not added.
+"""
+from __future__ import annotations
+
+from typing import Optional, Tuple
+
+import numpy as np
+
+
+def fosi_step(w: np.ndarray, g: np.ndarray, V: np.ndarray, evals: np.ndarray, mom: np.ndarray,
+              alpha: float, lr: float, momentum: float, sigma: float = 0.0,
+              pi: Optional[np.ndarray] = None, curv_mode: str = "signed",
+              g1_reading: str = "projected") -> Tuple[np.ndarray, np.ndarray]:
+    """Returns (w_new, mom_new).  V is n x (k+l) with orthonormal columns (may
+    have zero columns), evals the matching Ritz values.  Without `pi` this is
+    the plain update (sigma is ignored)."""
+    w = np.asarray(w, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    a_hat = np.asarray(evals, dtype=np.float64)
+    b = np.asarray(mom, dtype=np.float64)
+    if pi is None:
+        g_tilde, sig = g, 0.0
+    else:
+        g_tilde, sig = g + np.asarray(pi, dtype=np.float64), float(sigma)
+
+    # Delta_1: alpha-scaled Newton step inside span(V-hat)
+    c = V.T @ g_tilde
+    denom = a_hat + sig if curv_mode == "signed" else np.abs(a_hat) + sig
+    delta1 = -alpha * (V @ (c / denom))
+
+    # Delta_2: base optimiser on the complement, re-projected
+    g1 = V @ c if g1_reading == "projected" else V @ (V.T @ g)
+    x = g_tilde - g1
+    b_new = momentum * b + x
+    o = -lr * b_new
+    delta2 = o - V @ (V.T @ o)
+
+    return w + delta1 + delta2, b_new

@@ -1,0 +1,44 @@
+"""Comparison helpers for the tests (no method arithmetic; plain linear algebra
+on results)."""
+import numpy as np
+
+
+def sin_principal_angles(V_ref: np.ndarray, V_test: np.ndarray) -> np.ndarray:
+    """Sines of the principal angles between the column spaces, computed as the
+    singular values of (I - P_ref) V_test with both bases orthonormalised
+    (accurate for small angles, unlike the arccos of the cosines)."""
+    A = np.linalg.qr(np.asarray(V_ref, dtype=np.float64))[0]
+    B = np.linalg.qr(np.asarray(V_test, dtype=np.float64))[0]
+    R = B - A @ (A.T @ B)
+    return np.linalg.svd(R, compute_uv=False)
+
+
+def rel_l2(a: np.ndarray, b: np.ndarray) -> float:
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def reduced_tridiagonal(U: np.ndarray, lam: np.ndarray, shift: float, v1: np.ndarray):
+    """Independent route to the Lanczos tridiagonal of H = U diag(lam) U^T + shift I
+    started from v1: the Krylov space lives in span([U, v1]), so H restricted to
+    an orthonormal basis of that (r+1)-dimensional space is a small dense matrix
+    M; a Householder reflector moves the start vector to e_1 and LAPACK's
+    Householder reduction to Hessenberg form (tridiagonal, M being symmetric)
+    yields the same matrix the Lanczos recurrence builds, up to the signs of the
+    off-diagonal.  Returns (diag, |offdiag|)."""
+    import scipy.linalg as sla
+    U64 = np.asarray(U, dtype=np.float64)
+    v = np.asarray(v1, dtype=np.float64)
+    v = v / np.linalg.norm(v)
+    Bs = np.linalg.qr(np.column_stack([U64, v]))[0]
+    G = Bs.T @ U64
+    M = G @ np.diag(np.asarray(lam, dtype=np.float64)) @ G.T + float(shift) * np.eye(Bs.shape[1])
+    z = Bs.T @ v
+    z /= np.linalg.norm(z)
+    e1 = np.zeros_like(z)
+    e1[0] = 1.0
+    u = z - e1
+    P = np.eye(len(z)) - 2.0 * np.outer(u, u) / (u @ u) if np.linalg.norm(u) > 0 else np.eye(len(z))
+    Hh = sla.hessenberg(P.T @ M @ P)
+    return np.diag(Hh).copy(), np.abs(np.diag(Hh, -1))
