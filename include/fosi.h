@@ -1,0 +1,189 @@
+/*
+ * fosi.h -- C boundary of the MI355X (gfx950) hot path of the hybrid-order
+ * optimiser: Lanczos on Hessian-vector products with full reorthogonalisation
+ * (Algorithm 1), Ritz extraction of the k largest / l smallest pairs (Eq. 8),
+ * the two-subspace update (Eq. 4, Eq. 12; Eq. 14 with a dual variable) and the
+ * outer multiplier rule (Eq. 11, Algorithm 3).
+ *
+ * Conventions that hold for every call
+ *   - "dev" pointers are device (HBM) addresses on the context's GPU, "host"
+ *     pointers are ordinary host memory.  The caller owns every buffer it
+ *     passes; the library only allocates its own scratch (a few MiB per
+ *     context, plus per-operator caches stated below).
+ *   - Vectors are fp32 of length n.  Matrices are fp32 column-major with a
+ *     leading dimension ld >= n that is a multiple of 4 floats; matrix and
+ *     vector base pointers are 16-byte aligned.  Violations return
+ *     FOSI_ERR_BAD_LAYOUT.
+ *   - Work is enqueued on the context's HIP stream.  fosi_lanczos blocks until
+ *     its tridiagonal has been copied to the host; fosi_ritz is asynchronous
+ *     after its (host-side) eigen-solve; everything else is asynchronous.
+ *   - No call aborts, throws or prints.  A negative status is an error and
+ *     fosi_last_error(ctx) describes it.
+ *   - Reductions are two-stage with a fixed order: a repeated call on the same
+ *     inputs returns the same bits.
+ */
+#ifndef FOSI_H
+#define FOSI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t fosi_status;
+#define FOSI_OK                0
+#define FOSI_ERR_INVALID_ARG  (-1)  /* null pointer, non-positive size, unknown enum            */
+#define FOSI_ERR_BAD_LAYOUT   (-2)  /* ld < n, ld not a multiple of 4, misaligned pointer       */
+#define FOSI_ERR_RANK         (-3)  /* more Ritz pairs requested than Lanczos steps available   */
+#define FOSI_ERR_NONFINITE    (-4)  /* NaN/Inf met in the recurrence, or a zero Newton divisor  */
+#define FOSI_ERR_HIP          (-5)  /* a HIP runtime call failed                                */
+#define FOSI_ERR_NOMEM        (-6)  /* scratch allocation failed                                */
+#define FOSI_ERR_CALLBACK     (-7)  /* a user hvp callback returned non-zero                    */
+#define FOSI_ERR_LIMIT        (-8)  /* a size exceeds a built-in limit (see FOSI_MAX_COLS)      */
+
+/* Largest number of matrix columns any kernel handles (Lanczos steps + 1,
+ * planted rank, k + l). */
+#define FOSI_MAX_COLS 256
+
+typedef struct fosi_ctx fosi_ctx;   /* one GPU + one stream + scratch; not thread-safe */
+typedef struct fosi_hvp fosi_hvp;   /* a curvature operator v -> H v bound to a context */
+
+/* ---- context ---------------------------------------------------------- */
+
+/* Creates a context on GPU `device`.  `hip_stream` is a hipStream_t passed as
+ * a pointer (NULL = the default stream); the caller keeps the stream alive. */
+fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream);
+fosi_status fosi_ctx_destroy(fosi_ctx* ctx);
+/* Blocks until all work enqueued through this context has finished. */
+fosi_status fosi_ctx_synchronize(fosi_ctx* ctx);
+/* Text of the last error on this context ("" if none).  Owned by the context. */
+const char* fosi_last_error(const fosi_ctx* ctx);
+const char* fosi_status_string(fosi_status s);
+
+/* ---- curvature operators: the input hvp_t of Algorithm 1 ------------------
+ * The paper obtains H v from a network by automatic differentiation; these
+ * operators take its place.  All of them read v_dev and write hv_dev (both fp32,
+ * length n, distinct buffers) on the context's stream. */
+
+/* H = U diag(lam) U^T + shift I.  U_dev: n x r column-major (ldu), lam_dev: r
+ * fp32.  Both are read at every apply and stay owned by the caller. */
+fosi_status hvp_planted_create(fosi_ctx* ctx, int64_t n, int r, const float* U_dev, int64_t ldu,
+                               const float* lam_dev, float shift, fosi_hvp** out);
+/* H = diag(d).  d_dev: n fp32. */
+fosi_status hvp_diag_create(fosi_ctx* ctx, int64_t n, const float* d_dev, fosi_hvp** out);
+/* Generalised Gauss-Newton matrix of the mean softmax cross-entropy of a linear
+ * classifier, logits = X W:  H v = X^T[(diag(p_b) - p_b p_b^T)(X V)_b]_b / B with
+ * V = v viewed as d x C row-major, n = d*C.  X_dev: B x d row-major, W_dev:
+ * d x C row-major.  The operator caches P = softmax(X W) and two B x C work
+ * matrices in device memory it allocates (freed by hvp_destroy). */
+fosi_status hvp_softmax_ggn_create(fosi_ctx* ctx, int B, int d, int C, const float* X_dev,
+                                   const float* W_dev, fosi_hvp** out);
+/* User operator (for instance a double-backward pass).  fn must enqueue its
+ * work on `stream` (a hipStream_t) and return 0 on success. */
+typedef int (*fosi_hvp_fn)(void* user, const float* v_dev, float* hv_dev, void* stream);
+fosi_status hvp_callback_create(fosi_ctx* ctx, int64_t n, fosi_hvp_fn fn, void* user, fosi_hvp** out);
+fosi_status hvp_apply(fosi_hvp* op, const float* v_dev, float* hv_dev);
+fosi_status hvp_destroy(fosi_hvp* op);
+
+/* ---- Algorithm 1: Lanczos with full reorthogonalisation ------------------- */
+
+typedef struct {
+    /* Gram-Schmidt passes per step.  1 is the paper's single pass; 2 (default)
+     * repeats it once, which fp32 storage needs to keep Q orthonormal.  With 2
+     * passes the diagonal entry is the sum of the two coefficients removed
+     * along the current vector. */
+    int32_t reorth_passes;
+    /* The step count stops early (m_eff < m) when ||h after orthogonalisation||
+     * <= breakdown_tol * ||H q_i||: the Krylov space is exhausted.  Default 1e-6. */
+    double breakdown_tol;
+} fosi_lanczos_opts;
+
+/* Q_dev: n x (m+1) column-major (ldq).  On entry column 0 holds the start
+ * vector (any non-zero vector: it is normalised in place); on exit columns
+ * 0..m_eff-1 are the orthonormal Lanczos vectors and column m_eff (if
+ * m_eff == m: the residual direction) is scratch.
+ * alpha_host, beta_host: m doubles each, first m_eff valid.  beta[i] couples
+ * columns i and i+1; beta[m_eff-1] is the norm of the final residual.
+ * opts may be NULL (defaults).  Breakdown is not an error. */
+fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q_dev, int64_t ldq,
+                         double* alpha_host, double* beta_host, int32_t* m_eff,
+                         const fosi_lanczos_opts* opts);
+
+/* ---- Eq. 8: Ritz extraction ------------------------------------------------ */
+
+/* Host-only helper: eigen-decomposition of the symmetric tridiagonal matrix
+ * with diagonal alpha[0..m-1] and off-diagonal beta[0..m-2].  evals: m doubles,
+ * ascending.  evecs: m x m doubles, column-major, column j belongs to evals[j]
+ * (may be NULL).  Touches no GPU. */
+fosi_status fosi_tridiag_eigh(int m, const double* alpha, const double* beta, double* evals, double* evecs);
+
+/* Solves the m_eff x m_eff tridiagonal problem on the host, keeps the k largest
+ * (descending) then the l smallest (ascending) Ritz values and forms their Ritz
+ * vectors V = Q[:, :m_eff] S on the GPU.  V_dev: n x (k+l) column-major (ldv).
+ * evals_host: k+l doubles.  resid_host: k+l residual estimates
+ * beta[m_eff-1] * |last component of the eigenvector| (may be NULL).
+ * Needs 1 <= k+l <= m_eff, else FOSI_ERR_RANK. */
+fosi_status fosi_ritz(fosi_ctx* ctx, int64_t n, int m_eff, const float* Q_dev, int64_t ldq,
+                      const double* alpha_host, const double* beta_host, int k, int l,
+                      float* V_dev, int64_t ldv, double* evals_host, double* resid_host);
+
+/* ---- Eq. 4 + Eq. 12 (Eq. 14 with a dual variable): one model update --------- */
+
+#define FOSI_CURV_SIGNED 0   /* divide by (a_j + sigma) as the equations are written */
+#define FOSI_CURV_ABS    1   /* divide by (|a_j| + sigma)                            */
+
+typedef struct {
+    float alpha;      /* Newton scale                                        */
+    float lr;         /* learning rate of the base optimiser (heavy ball)    */
+    float momentum;   /* heavy-ball coefficient                              */
+    float sigma;      /* ADMM penalty; ignored when pi_dev is NULL            */
+    int32_t curv_mode;
+} fosi_step_params;
+
+/* w <- w + Delta_1 + Delta_2 with
+ *   g~ = g + pi (pi = 0 if pi_dev is NULL),  c = V^T g~,
+ *   Delta_1 = -alpha V (c / (a + sigma)),
+ *   b <- momentum b + (g~ - V c),  o = -lr b,  Delta_2 = o - V (V^T o).
+ * V_dev: n x r_v column-major (ldv), r_v = k+l >= 0 (0: plain heavy ball);
+ * evals_host: r_v doubles; g_dev, pi_dev: n fp32 read-only; mom_dev (b) and
+ * w_dev: n fp32, updated in place. */
+fosi_status fosi_step(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int64_t ldv,
+                      const double* evals_host, const float* g_dev, const float* pi_dev,
+                      float* mom_dev, float* w_dev, const fosi_step_params* p);
+
+/* ---- Algorithm 3 / Eq. 11: outer multiplier rule ---------------------------- */
+
+/* Start of an outer iteration: w_anchor = w_a + pi / sigma; w_a = w_anchor. */
+fosi_status fosi_admm_begin(fosi_ctx* ctx, int64_t n, float sigma, const float* pi_dev,
+                            float* w_anchor_dev, float* wa_dev);
+/* End of an outer iteration: pi <- pi + sigma (w_a - w_anchor). */
+fosi_status fosi_admm_end(fosi_ctx* ctx, int64_t n, float sigma, const float* w_anchor_dev,
+                          const float* wa_dev, float* pi_dev);
+
+/* ---- per-kernel timing (opt-in) --------------------------------------------
+ * When enabled, every launch of the kernels listed below is bracketed by HIP
+ * events on the context's stream.  fosi_profile_read synchronises and returns
+ * the launch count, the summed duration and the summed algorithmic bytes of
+ * one kernel class since the last reset. */
+#define FOSI_PROF_HVP_PROJECT   0   /* planted operator: coefficients U^T v            */
+#define FOSI_PROF_HVP_EXPAND    1   /* planted operator: shift v + U (lam . coeff)     */
+#define FOSI_PROF_REORTH_DOT    2   /* Gram-Schmidt: Q^T h                             */
+#define FOSI_PROF_REORTH_SUB    3   /* Gram-Schmidt: h - Q c, ||.||^2                  */
+#define FOSI_PROF_NORMALISE     4   /* q = h / beta                                    */
+#define FOSI_PROF_RITZ_VECTORS  5   /* V = Q S                                         */
+#define FOSI_PROF_STEP          6   /* all kernels of one fosi_step                    */
+#define FOSI_PROF_ADMM          7   /* multiplier rule kernels                         */
+#define FOSI_PROF_HVP_GGN       8   /* softmax-GGN operator, whole apply               */
+#define FOSI_PROF_HVP_OTHER     9   /* diagonal / callback operators                   */
+#define FOSI_PROF_NUM          10
+fosi_status fosi_profile_enable(fosi_ctx* ctx, int on);
+fosi_status fosi_profile_reset(fosi_ctx* ctx);
+fosi_status fosi_profile_read(fosi_ctx* ctx, int kernel_class, int64_t* launches, double* total_ms,
+                              double* algorithmic_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FOSI_H */

@@ -1,0 +1,23 @@
+"""MI355X-native hot path of the DHO2 / FOSI hybrid-order optimiser.
+
+The arithmetic lives in libfosi_hip.so (hand-written HIP for gfx950, built by
+`python -m paper_2505_00982_amd.build`); this package is a thin ctypes binding
+with the same names as the C functions declared in include/fosi.h.
+"""
+from .binding import (  # noqa: F401
+    FosiError,
+    Context,
+    Hvp,
+    ColMajor,
+    StepParams,
+    fosi_lanczos,
+    fosi_ritz,
+    fosi_step,
+    fosi_admm_begin,
+    fosi_admm_end,
+    fosi_tridiag_eigh,
+    library_path,
+    load_library,
+    PROF,
+    STATUS,
+)

@@ -1,0 +1,36 @@
+"""Builds libfosi_hip.so (the C-ABI library) in-tree with hipcc for gfx950.
+
+Usage: python -m paper_2505_00982_amd.build
+"""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+SOURCES = ["fosi_api.hip", "fosi_kernels.hip", "hvp_ggn.hip", "tridiag_eigh.cpp"]
+LIB = os.path.join(HERE, "libfosi_hip.so")
+
+
+def build_library(verbose: bool = True) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [
+        hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+        # packed-fp32 instructions are switched off for all device code
+        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+        "-Wall", "-Wno-unused-result",
+        "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
+        "-o", LIB,
+    ] + [os.path.join(HERE, "csrc", s) for s in SOURCES]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    build_library()
+    print("built", LIB)
+    sys.exit(0)

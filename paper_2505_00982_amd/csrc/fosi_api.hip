@@ -1,0 +1,536 @@
+// The exported C functions: argument checks, the Lanczos driver loop, the host
+// part of the Ritz extraction, the sequencing of the update-rule kernels, and
+// the opt-in per-kernel timers.  All arithmetic on vectors of length n happens
+// in the kernels of fosi_kernels.hip / hvp_ggn.hip.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "fosi_internal.h"
+
+namespace fosi {
+
+fosi_status fail(fosi_ctx* ctx, fosi_status code, const std::string& msg) {
+    if (ctx != nullptr) ctx->last_error = msg;
+    return code;
+}
+
+fosi_status check_hip(fosi_ctx* ctx, hipError_t e, const char* what) {
+    if (e == hipSuccess) return FOSI_OK;
+    return fail(ctx, FOSI_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+void prof_begin(fosi_ctx* ctx, int cls, double bytes) {
+    if (!ctx->prof_on) return;
+    ProfRecord r{};
+    r.cls = cls;
+    r.bytes = bytes;
+    for (hipEvent_t* ev : {&r.start, &r.stop}) {
+        if (!ctx->event_pool.empty()) {
+            *ev = ctx->event_pool.back();
+            ctx->event_pool.pop_back();
+        } else if (hipEventCreate(ev) != hipSuccess) {
+            return;
+        }
+    }
+    (void)hipEventRecord(r.start, ctx->stream);
+    ctx->prof.push_back(r);
+}
+
+void prof_end(fosi_ctx* ctx) {
+    if (!ctx->prof_on || ctx->prof.empty()) return;
+    (void)hipEventRecord(ctx->prof.back().stop, ctx->stream);
+}
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+fosi_status check_matrix(fosi_ctx* ctx, const char* name, const void* p, int64_t n, int64_t ld, int cols) {
+    if (cols == 0) return FOSI_OK;
+    if (p == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, std::string(name) + " is null");
+    if (ld < n || (ld & 3) != 0)
+        return fail(ctx, FOSI_ERR_BAD_LAYOUT, std::string(name) + ": leading dimension must be >= n and a multiple of 4");
+    if (!aligned16(p)) return fail(ctx, FOSI_ERR_BAD_LAYOUT, std::string(name) + " is not 16-byte aligned");
+    return FOSI_OK;
+}
+
+fosi_status check_vector(fosi_ctx* ctx, const char* name, const void* p, bool nullable = false) {
+    if (p == nullptr) return nullable ? FOSI_OK : fail(ctx, FOSI_ERR_INVALID_ARG, std::string(name) + " is null");
+    if (!aligned16(p)) return fail(ctx, FOSI_ERR_BAD_LAYOUT, std::string(name) + " is not 16-byte aligned");
+    return FOSI_OK;
+}
+
+int env_int(const char* name, int dflt) {
+    const char* v = std::getenv(name);
+    if (v == nullptr || *v == 0) return dflt;
+    return std::atoi(v);
+}
+
+size_t round256(size_t b) { return (b + 255) / 256 * 256; }
+
+fosi_status launch_status(fosi_ctx* ctx, const char* what) { return check_hip(ctx, hipGetLastError(), what); }
+
+const double kVec = 4.0;   // bytes per element of an fp32 vector
+
+}  // namespace
+}  // namespace fosi
+
+using namespace fosi;
+
+extern "C" {
+
+const char* fosi_status_string(fosi_status s) {
+    switch (s) {
+        case FOSI_OK: return "ok";
+        case FOSI_ERR_INVALID_ARG: return "invalid argument";
+        case FOSI_ERR_BAD_LAYOUT: return "bad layout";
+        case FOSI_ERR_RANK: return "not enough Lanczos steps for the requested Ritz pairs";
+        case FOSI_ERR_NONFINITE: return "non-finite value";
+        case FOSI_ERR_HIP: return "HIP runtime error";
+        case FOSI_ERR_NOMEM: return "out of memory";
+        case FOSI_ERR_CALLBACK: return "hvp callback failed";
+        case FOSI_ERR_LIMIT: return "size exceeds a built-in limit";
+        default: return "unknown status";
+    }
+}
+
+fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
+    if (out == nullptr) return FOSI_ERR_INVALID_ARG;
+    *out = nullptr;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return FOSI_ERR_HIP;
+    if (device < 0 || device >= ndev) return FOSI_ERR_INVALID_ARG;
+    if (hipSetDevice(device) != hipSuccess) return FOSI_ERR_HIP;
+    fosi_ctx* ctx = new (std::nothrow) fosi_ctx();
+    if (ctx == nullptr) return FOSI_ERR_NOMEM;
+    ctx->device = device;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) == hipSuccess) ctx->sm_count = prop.multiProcessorCount;
+    ctx->tun.dot_cols_per_block = env_int("FOSI_DOT_COLS", 16);
+    ctx->tun.dot_target_blocks = env_int("FOSI_DOT_BLOCKS", 8 * ctx->sm_count);
+    ctx->tun.comb_rows_per_thread = env_int("FOSI_COMB_ROWS", 1);
+
+    const size_t cols1 = kMaxCols + 1;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += round256(bytes); return o; };
+    const size_t o_part = take(sizeof(double) * kMaxDotSlots * cols1);
+    const size_t o_norm = take(sizeof(double) * kMaxNormSlots);
+    const size_t o_ca = take(sizeof(double) * cols1), o_cb = take(sizeof(double) * cols1);
+    const size_t o_cc = take(sizeof(double) * cols1), o_ch = take(sizeof(double) * cols1);
+    const size_t o_scal = take(sizeof(double) * 8);
+    const size_t o_al = take(sizeof(double) * kMaxCols), o_be = take(sizeof(double) * kMaxCols);
+    const size_t o_hn = take(sizeof(double) * kMaxCols), o_nw = take(sizeof(double) * kMaxCols);
+    const size_t o_S = take(sizeof(float) * kMaxCols * kMaxCols);
+    const size_t o_fl = take(sizeof(int) * 8);
+    if (hipMalloc(&ctx->scratch_base, off) != hipSuccess) {
+        delete ctx;
+        return FOSI_ERR_NOMEM;
+    }
+    char* b = static_cast<char*>(ctx->scratch_base);
+    ctx->s.partials = reinterpret_cast<double*>(b + o_part);
+    ctx->s.norm_partials = reinterpret_cast<double*>(b + o_norm);
+    ctx->s.coef_a = reinterpret_cast<double*>(b + o_ca);
+    ctx->s.coef_b = reinterpret_cast<double*>(b + o_cb);
+    ctx->s.coef_c = reinterpret_cast<double*>(b + o_cc);
+    ctx->s.coef_h = reinterpret_cast<double*>(b + o_ch);
+    ctx->s.scal = reinterpret_cast<double*>(b + o_scal);
+    ctx->s.alpha = reinterpret_cast<double*>(b + o_al);
+    ctx->s.beta = reinterpret_cast<double*>(b + o_be);
+    ctx->s.hnorm = reinterpret_cast<double*>(b + o_hn);
+    ctx->s.newton = reinterpret_cast<double*>(b + o_nw);
+    ctx->s.S = reinterpret_cast<float*>(b + o_S);
+    ctx->s.flags = reinterpret_cast<int*>(b + o_fl);
+    if (hipMemsetAsync(ctx->scratch_base, 0, off, ctx->stream) != hipSuccess) {
+        (void)hipFree(ctx->scratch_base);
+        delete ctx;
+        return FOSI_ERR_HIP;
+    }
+    *out = ctx;
+    return FOSI_OK;
+}
+
+fosi_status fosi_ctx_destroy(fosi_ctx* ctx) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    (void)hipStreamSynchronize(ctx->stream);
+    for (auto& r : ctx->prof) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    for (auto& e : ctx->event_pool) (void)hipEventDestroy(e);
+    (void)hipFree(ctx->scratch_base);
+    delete ctx;
+    return FOSI_OK;
+}
+
+fosi_status fosi_ctx_synchronize(fosi_ctx* ctx) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    return check_hip(ctx, hipStreamSynchronize(ctx->stream), "hipStreamSynchronize");
+}
+
+const char* fosi_last_error(const fosi_ctx* ctx) { return ctx == nullptr ? "null context" : ctx->last_error.c_str(); }
+
+/* ------------------------------------------------------------- operators */
+
+static fosi_status new_op(fosi_ctx* ctx, fosi_hvp::Kind kind, int64_t n, fosi_hvp** out) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (out == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "out is null");
+    *out = nullptr;
+    if (n < 1) return fail(ctx, FOSI_ERR_INVALID_ARG, "n must be positive");
+    fosi_hvp* op = new (std::nothrow) fosi_hvp();
+    if (op == nullptr) return fail(ctx, FOSI_ERR_NOMEM, "operator allocation failed");
+    op->kind = kind;
+    op->ctx = ctx;
+    op->n = n;
+    *out = op;
+    return FOSI_OK;
+}
+
+fosi_status hvp_planted_create(fosi_ctx* ctx, int64_t n, int r, const float* U_dev, int64_t ldu,
+                               const float* lam_dev, float shift, fosi_hvp** out) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (out != nullptr) *out = nullptr;
+    if (n < 1 || r < 0) return fail(ctx, FOSI_ERR_INVALID_ARG, "n must be positive and r non-negative");
+    if (r > kMaxCols) return fail(ctx, FOSI_ERR_LIMIT, "planted rank exceeds FOSI_MAX_COLS");
+    if (fosi_status s = check_matrix(ctx, "U_dev", U_dev, n, ldu, r)) return s;
+    if (r > 0 && lam_dev == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "lam_dev is null");
+    if (fosi_status s = new_op(ctx, fosi_hvp::PLANTED, n, out)) return s;
+    (*out)->r = r;
+    (*out)->U = U_dev;
+    (*out)->ldu = ldu;
+    (*out)->lam = lam_dev;
+    (*out)->shift = shift;
+    return FOSI_OK;
+}
+
+fosi_status hvp_diag_create(fosi_ctx* ctx, int64_t n, const float* d_dev, fosi_hvp** out) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (out != nullptr) *out = nullptr;
+    if (d_dev == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "d_dev is null");
+    if (fosi_status s = new_op(ctx, fosi_hvp::DIAG, n, out)) return s;
+    (*out)->d = d_dev;
+    return FOSI_OK;
+}
+
+fosi_status hvp_softmax_ggn_create(fosi_ctx* ctx, int B, int d, int C, const float* X_dev, const float* W_dev,
+                                   fosi_hvp** out) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (out != nullptr) *out = nullptr;
+    if (B < 1 || d < 1 || C < 1) return fail(ctx, FOSI_ERR_INVALID_ARG, "B, d, C must be positive");
+    if (X_dev == nullptr || W_dev == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "X_dev or W_dev is null");
+    if (!aligned16(X_dev) || !aligned16(W_dev)) return fail(ctx, FOSI_ERR_BAD_LAYOUT, "X_dev/W_dev not 16-byte aligned");
+    if (fosi_status s = new_op(ctx, fosi_hvp::GGN, (int64_t)d * C, out)) return s;
+    fosi_hvp* op = *out;
+    op->B = B;
+    op->dim = d;
+    op->C = C;
+    op->X = X_dev;
+    op->W = W_dev;
+    if (fosi_status s = ggn_prepare(op)) {
+        ggn_release(op);
+        delete op;
+        *out = nullptr;
+        return s;
+    }
+    return FOSI_OK;
+}
+
+fosi_status hvp_callback_create(fosi_ctx* ctx, int64_t n, fosi_hvp_fn fn, void* user, fosi_hvp** out) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (out != nullptr) *out = nullptr;
+    if (fn == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "fn is null");
+    if (fosi_status s = new_op(ctx, fosi_hvp::CALLBACK, n, out)) return s;
+    (*out)->fn = fn;
+    (*out)->user = user;
+    return FOSI_OK;
+}
+
+fosi_status hvp_apply(fosi_hvp* op, const float* v_dev, float* hv_dev) {
+    if (op == nullptr) return FOSI_ERR_INVALID_ARG;
+    fosi_ctx* ctx = op->ctx;
+    if (fosi_status s = check_vector(ctx, "v_dev", v_dev)) return s;
+    if (fosi_status s = check_vector(ctx, "hv_dev", hv_dev)) return s;
+    if (v_dev == hv_dev) return fail(ctx, FOSI_ERR_INVALID_ARG, "v_dev and hv_dev must be distinct");
+    const int64_t n = op->n;
+    const int* stop = ctx->s.flags;   // zero outside a Lanczos run
+    switch (op->kind) {
+        case fosi_hvp::PLANTED: {
+            const double vec = kVec * (double)n;
+            // coefficients lam_j * (u_j . v), then shift v + U (coefficients)
+            launch_dot_columns(ctx, op->U, op->ldu, op->r, v_dev, nullptr, n, ctx->s.coef_h, op->lam, op->r, 1.0, stop,
+                               FOSI_PROF_HVP_PROJECT, (op->r + 1) * vec);
+            launch_combine_columns(ctx, op->U, op->ldu, op->r, ctx->s.coef_h, nullptr, 0.0, v_dev, (double)op->shift,
+                                   nullptr, 0.0, 1.0, hv_dev, n, false, stop, FOSI_PROF_HVP_EXPAND, (op->r + 2) * vec);
+            break;
+        }
+        case fosi_hvp::DIAG: {
+            ProfScope p(ctx, FOSI_PROF_HVP_OTHER, 3 * kVec * (double)n);
+            launch_diag_apply(ctx, op->d, v_dev, hv_dev, n);
+            break;
+        }
+        case fosi_hvp::GGN: {
+            ProfScope p(ctx, FOSI_PROF_HVP_GGN, 0.0);
+            if (fosi_status s = ggn_apply(op, v_dev, hv_dev)) return s;
+            break;
+        }
+        case fosi_hvp::CALLBACK: {
+            ProfScope p(ctx, FOSI_PROF_HVP_OTHER, 0.0);
+            if (op->fn(op->user, v_dev, hv_dev, ctx->stream) != 0)
+                return fail(ctx, FOSI_ERR_CALLBACK, "hvp callback returned non-zero");
+            break;
+        }
+    }
+    return launch_status(ctx, "hvp_apply");
+}
+
+fosi_status hvp_destroy(fosi_hvp* op) {
+    if (op == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (op->kind == fosi_hvp::GGN) {
+        (void)hipStreamSynchronize(op->ctx->stream);
+        ggn_release(op);
+    }
+    delete op;
+    return FOSI_OK;
+}
+
+/* ------------------------------------------------------------- Algorithm 1 */
+
+fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q_dev, int64_t ldq,
+                         double* alpha_host, double* beta_host, int32_t* m_eff, const fosi_lanczos_opts* opts) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (op == nullptr || alpha_host == nullptr || beta_host == nullptr || m_eff == nullptr)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "null argument");
+    if (op->ctx != ctx) return fail(ctx, FOSI_ERR_INVALID_ARG, "operator belongs to another context");
+    if (n < 1 || m < 1) return fail(ctx, FOSI_ERR_INVALID_ARG, "n and m must be positive");
+    if (op->n != n) return fail(ctx, FOSI_ERR_INVALID_ARG, "operator size differs from n");
+    if (m + 1 > kMaxCols) return fail(ctx, FOSI_ERR_LIMIT, "m + 1 exceeds FOSI_MAX_COLS");
+    if (fosi_status s = check_matrix(ctx, "Q_dev", Q_dev, n, ldq, m + 1)) return s;
+    int passes = 2;
+    double tol = 1e-6;
+    if (opts != nullptr) {
+        if (opts->reorth_passes != 0) passes = opts->reorth_passes;
+        if (opts->breakdown_tol > 0.0) tol = opts->breakdown_tol;
+    }
+    if (passes != 1 && passes != 2) return fail(ctx, FOSI_ERR_INVALID_ARG, "reorth_passes must be 1 or 2");
+    *m_eff = 0;
+
+    const double vec = kVec * (double)n;
+    int* flags = ctx->s.flags;
+    if (fosi_status s = check_hip(ctx, hipMemsetAsync(flags, 0, 8 * sizeof(int), ctx->stream), "clear flags")) return s;
+
+    // first column: the caller's vector, normalised in place
+    launch_dot_columns(ctx, nullptr, 0, 0, Q_dev, nullptr, n, ctx->s.coef_a, nullptr, 0, 1.0, nullptr, -1, 0.0);
+    launch_inv_sqrt(ctx, ctx->s.coef_a, ctx->s.scal + 1);
+    launch_scale(ctx, Q_dev, ctx->s.scal + 1, n, nullptr);
+
+    for (int i = 0; i < m; ++i) {
+        const float* q = Q_dev + (int64_t)i * ldq;
+        float* h = Q_dev + (int64_t)(i + 1) * ldq;     // the new direction is built in place in the next column
+        if (fosi_status s = hvp_apply(op, q, h)) return s;
+        const int ncols = i + 1;
+        double* coef[2] = {ctx->s.coef_a, ctx->s.coef_b};
+        int norm_slots = 0;
+        for (int p = 0; p < passes; ++p) {
+            // Gram-Schmidt against every column built so far; the coefficient along q_i is the diagonal entry
+            launch_dot_columns(ctx, Q_dev, ldq, ncols, h, nullptr, n, coef[p], nullptr, 0, 1.0, flags,
+                               FOSI_PROF_REORTH_DOT, (ncols + 1) * vec);
+            norm_slots = launch_combine_columns(ctx, Q_dev, ldq, ncols, coef[p], h, 1.0, nullptr, 0.0, nullptr, 0.0,
+                                                -1.0, h, n, true, flags, FOSI_PROF_REORTH_SUB, (ncols + 2) * vec);
+        }
+        launch_lanczos_finalize(ctx, i, norm_slots, passes == 2, tol);
+        {
+            ProfScope ps(ctx, FOSI_PROF_NORMALISE, 2 * vec);
+            launch_scale(ctx, h, ctx->s.scal, n, flags);
+        }
+        if (fosi_status s = launch_status(ctx, "lanczos step")) return s;
+    }
+
+    int hflags[2] = {0, 0};
+    if (fosi_status s = check_hip(ctx, hipMemcpyAsync(alpha_host, ctx->s.alpha, sizeof(double) * m, hipMemcpyDeviceToHost,
+                                                      ctx->stream), "copy alpha")) return s;
+    if (fosi_status s = check_hip(ctx, hipMemcpyAsync(beta_host, ctx->s.beta, sizeof(double) * m, hipMemcpyDeviceToHost,
+                                                      ctx->stream), "copy beta")) return s;
+    if (fosi_status s = check_hip(ctx, hipMemcpyAsync(hflags, flags, sizeof(hflags), hipMemcpyDeviceToHost, ctx->stream),
+                                  "copy flags")) return s;
+    if (fosi_status s = check_hip(ctx, hipStreamSynchronize(ctx->stream), "lanczos synchronize")) return s;
+    // leave the stop flag clear so that later operator applications run
+    if (fosi_status s = check_hip(ctx, hipMemsetAsync(flags, 0, 8 * sizeof(int), ctx->stream), "clear flags")) return s;
+    *m_eff = hflags[1];
+    if (hflags[0] == 2) return fail(ctx, FOSI_ERR_NONFINITE, "non-finite value in the Lanczos recurrence");
+    return FOSI_OK;
+}
+
+/* ------------------------------------------------------------------- Eq. 8 */
+
+fosi_status fosi_tridiag_eigh(int m, const double* alpha, const double* beta, double* evals, double* evecs) {
+    if (m < 1 || alpha == nullptr || evals == nullptr || (m > 1 && beta == nullptr)) return FOSI_ERR_INVALID_ARG;
+    for (int i = 0; i < m; ++i)
+        if (!std::isfinite(alpha[i]) || (i + 1 < m && !std::isfinite(beta[i]))) return FOSI_ERR_NONFINITE;
+    return tridiag_eigh(m, alpha, beta, evals, evecs) == 0 ? FOSI_OK : FOSI_ERR_NONFINITE;
+}
+
+fosi_status fosi_ritz(fosi_ctx* ctx, int64_t n, int m_eff, const float* Q_dev, int64_t ldq, const double* alpha_host,
+                      const double* beta_host, int k, int l, float* V_dev, int64_t ldv, double* evals_host,
+                      double* resid_host) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (alpha_host == nullptr || beta_host == nullptr || evals_host == nullptr)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "null argument");
+    if (n < 1 || m_eff < 1 || k < 0 || l < 0) return fail(ctx, FOSI_ERR_INVALID_ARG, "bad sizes");
+    if (m_eff > kMaxCols) return fail(ctx, FOSI_ERR_LIMIT, "m_eff exceeds FOSI_MAX_COLS");
+    const int rv = k + l;
+    if (rv < 1 || rv > m_eff) return fail(ctx, FOSI_ERR_RANK, "need 1 <= k + l <= m_eff");
+    if (fosi_status s = check_matrix(ctx, "Q_dev", Q_dev, n, ldq, m_eff)) return s;
+    if (fosi_status s = check_matrix(ctx, "V_dev", V_dev, n, ldv, rv)) return s;
+
+    std::vector<double> u(m_eff), Z((size_t)m_eff * m_eff);
+    if (fosi_status s = fosi_tridiag_eigh(m_eff, alpha_host, beta_host, u.data(), Z.data()))
+        return fail(ctx, s, "tridiagonal eigen-solve failed");
+    std::vector<int> sel(rv);
+    for (int j = 0; j < k; ++j) sel[j] = m_eff - 1 - j;   // k largest, descending
+    for (int j = 0; j < l; ++j) sel[k + j] = j;           // l smallest, ascending
+    const double blast = std::fabs(beta_host[m_eff - 1]);
+    for (int j = 0; j < rv; ++j) {
+        evals_host[j] = u[sel[j]];
+        if (resid_host != nullptr) resid_host[j] = blast * std::fabs(Z[(size_t)sel[j] * m_eff + (m_eff - 1)]);
+    }
+    // Ritz vectors in chunks of at most 40 output columns (register budget of the kernel)
+    const double vec = kVec * (double)n;
+    for (int c0 = 0; c0 < rv; c0 += 40) {
+        const int cw = std::min(40, rv - c0);
+        const int pad = cw <= 8 ? 8 : cw <= 16 ? 16 : cw <= 24 ? 24 : cw <= 32 ? 32 : 40;
+        std::vector<float> S((size_t)m_eff * pad, 0.f);
+        for (int j = 0; j < m_eff; ++j)
+            for (int t = 0; t < cw; ++t) S[(size_t)j * pad + t] = (float)Z[(size_t)sel[c0 + t] * m_eff + j];
+        // pageable source: the runtime stages the copy before returning, so S may go out of scope
+        if (fosi_status s = check_hip(ctx, hipMemcpyAsync(ctx->s.S, S.data(), S.size() * sizeof(float),
+                                                          hipMemcpyHostToDevice, ctx->stream), "upload S")) return s;
+        if (fosi_status s = check_hip(ctx, hipStreamSynchronize(ctx->stream), "upload S sync")) return s;
+        ProfScope ps(ctx, FOSI_PROF_RITZ_VECTORS, (m_eff + cw) * vec);
+        launch_ritz_vectors(ctx, Q_dev, ldq, m_eff, ctx->s.S, pad, cw, V_dev + (int64_t)c0 * ldv, ldv, n);
+    }
+    return launch_status(ctx, "ritz vectors");
+}
+
+/* ------------------------------------------------- Eq. 4 / Eq. 12 / Eq. 14 */
+
+fosi_status fosi_step(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int64_t ldv, const double* evals_host,
+                      const float* g_dev, const float* pi_dev, float* mom_dev, float* w_dev, const fosi_step_params* p) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (p == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "params is null");
+    if (n < 1 || r_v < 0) return fail(ctx, FOSI_ERR_INVALID_ARG, "bad sizes");
+    if (r_v > kMaxCols) return fail(ctx, FOSI_ERR_LIMIT, "k + l exceeds FOSI_MAX_COLS");
+    if (p->curv_mode != FOSI_CURV_SIGNED && p->curv_mode != FOSI_CURV_ABS)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "unknown curv_mode");
+    if (fosi_status s = check_matrix(ctx, "V_dev", V_dev, n, ldv, r_v)) return s;
+    if (r_v > 0 && evals_host == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "evals_host is null");
+    if (fosi_status s = check_vector(ctx, "g_dev", g_dev)) return s;
+    if (fosi_status s = check_vector(ctx, "pi_dev", pi_dev, true)) return s;
+    if (fosi_status s = check_vector(ctx, "mom_dev", mom_dev)) return s;
+    if (fosi_status s = check_vector(ctx, "w_dev", w_dev)) return s;
+
+    const double sigma = pi_dev != nullptr ? (double)p->sigma : 0.0;
+    const double alpha = p->alpha, lr = p->lr, mu = p->momentum;
+    if (r_v > 0) {
+        std::vector<double> newton(r_v);
+        for (int j = 0; j < r_v; ++j) {
+            const double a = p->curv_mode == FOSI_CURV_ABS ? std::fabs(evals_host[j]) : evals_host[j];
+            const double den = a + sigma;
+            if (!(std::fabs(den) >= 1e-30) || !std::isfinite(den))
+                return fail(ctx, FOSI_ERR_NONFINITE, "Newton divisor a_j + sigma is zero or non-finite");
+            newton[j] = alpha / den;
+        }
+        if (newton != ctx->newton_cache) {   // unchanged between curvature refreshes: upload once
+            if (fosi_status s = check_hip(ctx, hipMemcpyAsync(ctx->s.newton, newton.data(), sizeof(double) * r_v,
+                                                              hipMemcpyHostToDevice, ctx->stream), "upload divisors"))
+                return s;
+            if (fosi_status s = check_hip(ctx, hipStreamSynchronize(ctx->stream), "upload divisors sync")) return s;
+            ctx->newton_cache = newton;
+        }
+    }
+    const double vec = kVec * (double)n;
+    const int extra = pi_dev != nullptr ? 1 : 0;
+    ProfScope ps(ctx, FOSI_PROF_STEP, r_v > 0 ? (4.0 * r_v + 8 + 2 * extra) * vec : (6.0 + extra) * vec);
+    if (r_v > 0)   // c = V^T (g + pi)
+        launch_dot_columns(ctx, V_dev, ldv, r_v, g_dev, pi_dev, n, ctx->s.coef_a, nullptr, 0, 1.0, nullptr, -1, 0.0);
+    // b <- momentum b + (g + pi) - V c
+    launch_combine_columns(ctx, V_dev, ldv, r_v, ctx->s.coef_a, mom_dev, mu, g_dev, 1.0, pi_dev, 1.0, -1.0, mom_dev, n,
+                           false, nullptr, -1, 0.0);
+    if (r_v > 0) {   // e = V^T b ;  d = newton . c - lr e
+        launch_dot_columns(ctx, V_dev, ldv, r_v, mom_dev, nullptr, n, ctx->s.coef_b, nullptr, 0, 1.0, nullptr, -1, 0.0);
+        launch_step_coefficients(ctx, r_v, lr);
+    }
+    // w <- w - lr b - V d   ( = w + Delta_1 + Delta_2 )
+    launch_combine_columns(ctx, V_dev, ldv, r_v, ctx->s.coef_c, w_dev, 1.0, mom_dev, -lr, nullptr, 0.0, -1.0, w_dev, n,
+                           false, nullptr, -1, 0.0);
+    return launch_status(ctx, "fosi_step");
+}
+
+/* ------------------------------------------------------ Algorithm 3 / Eq. 11 */
+
+fosi_status fosi_admm_begin(fosi_ctx* ctx, int64_t n, float sigma, const float* pi_dev, float* w_anchor_dev,
+                            float* wa_dev) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (n < 1 || !(sigma > 0.f)) return fail(ctx, FOSI_ERR_INVALID_ARG, "n and sigma must be positive");
+    if (pi_dev == nullptr || w_anchor_dev == nullptr || wa_dev == nullptr)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "null argument");
+    ProfScope ps(ctx, FOSI_PROF_ADMM, 4 * kVec * (double)n);
+    launch_admm_begin(ctx, n, 1.0 / (double)sigma, pi_dev, w_anchor_dev, wa_dev);
+    return launch_status(ctx, "admm_begin");
+}
+
+fosi_status fosi_admm_end(fosi_ctx* ctx, int64_t n, float sigma, const float* w_anchor_dev, const float* wa_dev,
+                          float* pi_dev) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (n < 1 || !(sigma > 0.f)) return fail(ctx, FOSI_ERR_INVALID_ARG, "n and sigma must be positive");
+    if (pi_dev == nullptr || w_anchor_dev == nullptr || wa_dev == nullptr)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "null argument");
+    ProfScope ps(ctx, FOSI_PROF_ADMM, 4 * kVec * (double)n);
+    launch_admm_end(ctx, n, (double)sigma, w_anchor_dev, wa_dev, pi_dev);
+    return launch_status(ctx, "admm_end");
+}
+
+/* ------------------------------------------------------------------ timers */
+
+fosi_status fosi_profile_enable(fosi_ctx* ctx, int on) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    ctx->prof_on = on != 0;
+    return FOSI_OK;
+}
+
+fosi_status fosi_profile_reset(fosi_ctx* ctx) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (fosi_status s = check_hip(ctx, hipStreamSynchronize(ctx->stream), "profile reset")) return s;
+    for (auto& r : ctx->prof) {
+        ctx->event_pool.push_back(r.start);
+        ctx->event_pool.push_back(r.stop);
+    }
+    ctx->prof.clear();
+    return FOSI_OK;
+}
+
+fosi_status fosi_profile_read(fosi_ctx* ctx, int kernel_class, int64_t* launches, double* total_ms,
+                              double* algorithmic_bytes) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (kernel_class < 0 || kernel_class >= FOSI_PROF_NUM || launches == nullptr || total_ms == nullptr ||
+        algorithmic_bytes == nullptr)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "bad profile query");
+    if (fosi_status s = check_hip(ctx, hipStreamSynchronize(ctx->stream), "profile read")) return s;
+    int64_t cnt = 0;
+    double ms = 0.0, bytes = 0.0;
+    for (auto& r : ctx->prof) {
+        if (r.cls != kernel_class) continue;
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, r.start, r.stop) != hipSuccess) continue;
+        ++cnt;
+        ms += t;
+        bytes += r.bytes;
+    }
+    *launches = cnt;
+    *total_ms = ms;
+    *algorithmic_bytes = bytes;
+    return FOSI_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,136 @@
+// Internal declarations shared by the translation units of libfosi_hip.
+// Nothing here is part of the public boundary (see include/fosi.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "fosi.h"
+
+namespace fosi {
+
+constexpr int kThreads = 256;          // every streaming kernel uses 4 wavefronts of 64 lanes
+constexpr int kMaxCols = FOSI_MAX_COLS;
+constexpr int kMaxDotSlots = 4096;     // row slots (gridDim.x) of the transposed product
+constexpr int kMaxNormSlots = 32768;   // blocks of the column-combination kernel that emit ||.||^2 partials
+
+struct ProfRecord {
+    int cls;
+    double bytes;
+    hipEvent_t start, stop;
+};
+
+struct Tunables {
+    int dot_cols_per_block;   // JB: columns a block of the transposed product accumulates (8, 16 or 32)
+    int dot_target_blocks;    // total resident blocks aimed at by the transposed product
+    int comb_rows_per_thread; // float4 row groups per thread in the column-combination kernel (1 or 2)
+};
+
+// Device scratch layout (one allocation per context).
+struct Scratch {
+    double* partials;      // kMaxDotSlots x (kMaxCols + 1)
+    double* norm_partials; // kMaxNormSlots
+    double* coef_a;        // kMaxCols + 1  (first Gram-Schmidt pass / operator coefficients)
+    double* coef_b;        // kMaxCols + 1  (second pass)
+    double* coef_c;        // kMaxCols + 1  (update-rule coefficients)
+    double* coef_h;        // kMaxCols + 1  (planted operator)
+    double* scal;          // 8 scalars: [0] = 1/beta, [1] = 1/||v||
+    double* alpha;         // kMaxCols
+    double* beta;          // kMaxCols
+    double* hnorm;         // kMaxCols
+    double* newton;        // kMaxCols: alpha / (a_j + sigma)
+    float* S;              // kMaxCols x kMaxCols Ritz coefficient block
+    int* flags;            // [0] stop flag (1 = breakdown, 2 = non-finite), [1] completed steps
+};
+
+}  // namespace fosi
+
+struct fosi_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    void* scratch_base = nullptr;
+    fosi::Scratch s{};
+    fosi::Tunables tun{};
+    std::string last_error;
+    bool prof_on = false;
+    std::vector<fosi::ProfRecord> prof;
+    std::vector<hipEvent_t> event_pool;
+    std::vector<double> newton_cache;   // host copy of what `s.newton` holds
+    int sm_count = 256;
+};
+
+struct fosi_hvp {
+    enum Kind { PLANTED, DIAG, GGN, CALLBACK } kind;
+    fosi_ctx* ctx;
+    int64_t n;
+    // planted
+    int r = 0;
+    const float* U = nullptr;
+    int64_t ldu = 0;
+    const float* lam = nullptr;
+    float shift = 0.f;
+    // diag
+    const float* d = nullptr;
+    // ggn
+    int B = 0, dim = 0, C = 0;
+    const float* X = nullptr;
+    const float* W = nullptr;
+    float* P = nullptr;     // B x C softmax probabilities
+    float* Z = nullptr;     // B x C work
+    // callback
+    fosi_hvp_fn fn = nullptr;
+    void* user = nullptr;
+};
+
+namespace fosi {
+
+// ---- error / profiling helpers (fosi_api.hip) ----
+fosi_status fail(fosi_ctx* ctx, fosi_status code, const std::string& msg);
+fosi_status check_hip(fosi_ctx* ctx, hipError_t e, const char* what);
+void prof_begin(fosi_ctx* ctx, int cls, double bytes);
+void prof_end(fosi_ctx* ctx);
+
+struct ProfScope {
+    fosi_ctx* c;
+    ProfScope(fosi_ctx* ctx, int cls, double bytes) : c(ctx) { prof_begin(c, cls, bytes); }
+    ~ProfScope() { prof_end(c); }
+};
+
+// ---- kernel launchers (fosi_kernels.hip); all enqueue on ctx->stream ----
+
+// coef[j] = (sum_rows A[row,j] * (x[row] + x2[row])) * (scale ? scale[j] : 1) * gscale  for j < ncols,
+// coef[ncols] = sum_rows (x + x2)^2.   x2 and scale may be null.  stop may be null.
+void launch_dot_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const float* x,
+                        const float* x2, int64_t n, double* coef, const float* scale, int nscale,
+                        double gscale, const int* stop, int prof_cls, double prof_bytes);
+
+// out = a0*y + a1*x1 + a2*x2 + sa * A[:, :ncols] d   (null pointers drop their term; out may alias y).
+// With want_norm the per-block partial sums of out^2 are left in ctx->s.norm_partials; their count is
+// returned.  Only the main kernel of each launcher is bracketed by the profiling events (prof_cls < 0: none).
+int launch_combine_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const double* d,
+                           const float* y, double a0, const float* x1, double a1, const float* x2,
+                           double a2, double sa, float* out, int64_t n, bool want_norm, const int* stop,
+                           int prof_cls, double prof_bytes);
+
+void launch_lanczos_finalize(fosi_ctx* ctx, int step, int norm_slots, bool two_pass, double tol);
+void launch_inv_sqrt(fosi_ctx* ctx, const double* in, double* out);
+void launch_scale(fosi_ctx* ctx, float* x, const double* factor, int64_t n, const int* stop);
+void launch_diag_apply(fosi_ctx* ctx, const float* d, const float* v, float* out, int64_t n);
+void launch_ritz_vectors(fosi_ctx* ctx, const float* Q, int64_t ldq, int m, const float* S_dev, int rv_pad,
+                         int rv, float* V, int64_t ldv, int64_t n);
+void launch_step_coefficients(fosi_ctx* ctx, int rv, double lr);
+void launch_admm_begin(fosi_ctx* ctx, int64_t n, double inv_sigma, const float* pi, float* anchor, float* wa);
+void launch_admm_end(fosi_ctx* ctx, int64_t n, double sigma, const float* anchor, const float* wa, float* pi);
+
+// softmax-GGN operator (hvp_ggn.hip)
+fosi_status ggn_prepare(fosi_hvp* op);
+fosi_status ggn_apply(fosi_hvp* op, const float* v, float* hv);
+void ggn_release(fosi_hvp* op);
+
+// host tridiagonal eigen-solver (tridiag_eigh.cpp); returns 0 on success
+int tridiag_eigh(int m, const double* alpha, const double* beta, double* evals, double* evecs);
+
+}  // namespace fosi

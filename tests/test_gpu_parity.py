@@ -1,0 +1,343 @@
+"""GPU parity: the HIP path (called through the C-ABI binding) against the CPU
+oracle on the same seeded inputs.
+
+Tolerances (fp32 storage, fp64 accumulation on the GPU; fp64 oracle):
+  * Ritz values: relative error <= 1e-4; Ritz subspaces: principal angles < 1e-3 rad
+    (compared as sin of the angle, for the k-block and the l-block separately);
+  * one update step: relative L2 error <= 1e-5, the oracle evaluating the update
+    on the GPU's own (V-hat, a-hat);
+  * operator applications and single kernels: relative L2 error <= 1e-6.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from oracle.lanczos import tridiagonal
+from tests.helpers import reduced_tridiagonal, rel_l2, sin_principal_angles
+
+pytestmark = pytest.mark.gpu
+
+EVAL_RTOL = 1e-4
+ANGLE_TOL = 1e-3
+STEP_RTOL = 1e-5
+KERNEL_RTOL = 1e-6
+
+
+@pytest.fixture(scope="module")
+def fo():
+    import paper_2505_00982_amd as fo
+    return fo
+
+
+@pytest.fixture(scope="module")
+def ctx(fo):
+    c = fo.Context(0)
+    yield c
+    c.close()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def planted_op(w):
+    return lambda v: oracle.hvp_planted(w.U, w.lam, float(w.shift), v)
+
+
+def gpu_curvature(fo, ctx, w, m=None, k=None, l=None, passes=2):
+    """Lanczos + Ritz on the GPU for a planted workload; returns a dict of host results."""
+    m = m or w.m
+    k = w.k if k is None else k
+    l = w.l if l is None else l
+    ld = wl.padded_ld(w.n)
+    U = fo.ColMajor.from_numpy(w.U, ld)
+    op = ctx.hvp_planted(U, dev(w.lam), float(w.shift))
+    Q = fo.ColMajor(w.n, m + 1, ld)
+    Q.col(0).copy_(dev(w.v1))
+    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, m, reorth_passes=passes)
+    V = fo.ColMajor(w.n, k + l, ld)
+    evals, resid = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, k, l, V)
+    ctx.synchronize()
+    return dict(op=op, U=U, Q=Q, V=V, alpha=alpha, beta=beta, m_eff=m_eff, evals=evals, resid=resid, k=k, l=l)
+
+
+def check_ritz_parity(w, g, res_or, converged_only=False):
+    k, l = g["k"], g["l"]
+    me = min(res_or.m_eff, g["m_eff"])
+    rz = oracle.ritz(res_or.Q, res_or.alpha, res_or.beta, res_or.m_eff, k, l)
+    rel = np.abs(g["evals"] - rz.evals) / np.abs(rz.evals)
+    Vg = g["V"].to_numpy().astype(np.float64)
+    mask = np.ones(k + l, dtype=bool)
+    if converged_only:
+        mask = rz.resid <= 1e-6 * np.abs(rz.evals)
+    assert rel[mask].max() <= EVAL_RTOL, rel
+    top = np.arange(k)[mask[:k]]
+    if len(top):
+        assert sin_principal_angles(rz.V[:, top], Vg[:, top]).max() < ANGLE_TOL
+    bot = k + np.arange(l)[mask[k:]]
+    if len(bot):
+        assert sin_principal_angles(rz.V[:, bot], Vg[:, bot]).max() < ANGLE_TOL
+    return rz, me
+
+
+# ------------------------------------------------------------------ single operators / kernels
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 63, 64, 257, 4096, 70001])
+def test_planted_operator_matches_oracle(fo, ctx, n):
+    w = wl.planted_workload(1, n=max(n, 40))   # the generator needs n >= r for an orthonormal block
+    if n < 40:
+        # tiny vectors: keep the first n rows of U (no longer orthonormal, still a valid operator)
+        U, v = w.U[:n].copy(), w.v1[:n].copy()
+    else:
+        U, v = w.U, w.v1
+    ld = wl.padded_ld(n)
+    Ud = fo.ColMajor.from_numpy(U, ld)
+    op = ctx.hvp_planted(Ud, dev(w.lam), float(w.shift))
+    vd, out = dev(v), torch.zeros(n, device="cuda")
+    op.apply(vd, out)
+    ctx.synchronize()
+    ref = oracle.hvp_planted(U, w.lam, float(w.shift), v)
+    assert rel_l2(out.cpu().numpy(), ref) <= KERNEL_RTOL
+    op.close()
+
+
+def test_diag_operator_and_full_spectrum(fo, ctx):
+    n = 48
+    d = (np.linspace(-3.0, 7.0, n) + 0.01 * np.arange(n) ** 1.5).astype(np.float32)
+    v1 = wl.normal_vector(1, 99, n)
+    op = ctx.hvp_diag(dev(d))
+    Q = fo.ColMajor(n, n + 1)
+    Q.col(0).copy_(dev(v1))
+    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, n, breakdown_tol=1e-9)
+    assert m_eff == n
+    u = np.linalg.eigvalsh(tridiagonal(alpha, beta, n))
+    assert np.max(np.abs(u - np.sort(d.astype(np.float64)))) < 2e-5
+    op.close()
+
+
+# ------------------------------------------------------------------ config 1 end to end
+@pytest.fixture(scope="module")
+def cfg1(fo, ctx):
+    w = wl.planted_workload(1)
+    g = gpu_curvature(fo, ctx, w)
+    res_or = oracle.lanczos(planted_op(w), w.v1, w.m)
+    return w, g, res_or
+
+
+def test_cfg1_tridiagonal_and_breakdown(cfg1):
+    w, g, res_or = cfg1
+    # the Krylov space has dimension 33; in fp32 the exhausted direction is found one step later at the latest
+    assert g["m_eff"] in (33, 34)
+    # the leading part of the recurrence is well conditioned: entry-by-entry agreement
+    assert np.max(np.abs(g["alpha"][:16] - res_or.alpha[:16])) < 2e-4 * 1e3
+    assert np.max(np.abs(g["beta"][:16] - res_or.beta[:16])) < 2e-4 * 1e3
+    a_h, b_h = reduced_tridiagonal(w.U, w.lam, w.shift, w.v1)
+    assert np.max(np.abs(g["alpha"][:16] - a_h[:16])) < 2e-4 * 1e3
+
+
+def test_cfg1_orthonormal_basis(cfg1):
+    w, g, _ = cfg1
+    Q = g["Q"].to_numpy(g["m_eff"]).astype(np.float64)
+    assert np.abs(Q.T @ Q - np.eye(g["m_eff"])).max() < 1e-5
+
+
+def test_cfg1_ritz_pairs(cfg1):
+    w, g, res_or = cfg1
+    rz, _ = check_ritz_parity(w, g, res_or)
+    truth = np.sort(w.lam.astype(np.float64))[::-1][: w.k] + float(w.shift)
+    assert np.max(np.abs(g["evals"] - truth) / truth) < EVAL_RTOL
+
+
+def test_cfg1_update_step(fo, ctx, cfg1):
+    w, g, _ = cfg1
+    p = w.params
+    grad = w.grad(0)
+    wd, md = dev(w.w0), torch.zeros(w.n, device="cuda")
+    sp = fo.StepParams(float(p.alpha), float(p.lr), float(p.momentum), float(p.sigma), 0)
+    fo.fosi_step(ctx, g["V"], w.k + w.l, g["evals"], dev(grad), None, md, wd, sp)
+    ctx.synchronize()
+    Vg = g["V"].to_numpy().astype(np.float64)
+    w_ref, b_ref = oracle.fosi_step(w.w0, grad, Vg, g["evals"], np.zeros(w.n), float(p.alpha), float(p.lr),
+                                    float(p.momentum))
+    upd_gpu = wd.cpu().numpy().astype(np.float64) - w.w0
+    assert rel_l2(upd_gpu, w_ref - w.w0) <= 5e-5          # the update alone (w0 is O(1), so fp32 storage of w limits this)
+    assert rel_l2(wd.cpu().numpy(), w_ref) <= STEP_RTOL
+    assert rel_l2(md.cpu().numpy(), b_ref) <= STEP_RTOL
+
+
+def test_repeat_is_bit_identical(fo, ctx, cfg1):
+    w, g, _ = cfg1
+    g2 = gpu_curvature(fo, ctx, w)
+    assert np.array_equal(g["alpha"], g2["alpha"]) and np.array_equal(g["beta"], g2["beta"])
+    assert torch.equal(g["V"].buf, g2["V"].buf)
+
+
+# ------------------------------------------------------------------ ragged sizes, single pass, small k+l
+@pytest.mark.parametrize("n,m,k,l", [(1000 + 3, 12, 1, 0), (4096 + 61, 20, 3, 2), (70001, 24, 4, 3)])
+def test_ragged_sizes(fo, ctx, n, m, k, l):
+    w = wl.planted_workload(2, n=n)
+    g = gpu_curvature(fo, ctx, w, m=m, k=k, l=l)
+    res_or = oracle.lanczos(planted_op(w), w.v1, m)
+    assert g["m_eff"] == res_or.m_eff == m
+    scale = np.abs(w.lam).max()
+    assert np.max(np.abs(g["alpha"] - res_or.alpha)) < 1e-5 * scale
+    assert np.max(np.abs(g["beta"] - res_or.beta)) < 1e-5 * scale
+    Q = g["Q"].to_numpy(m).astype(np.float64)
+    assert np.abs(Q.T @ Q - np.eye(m)).max() < 1e-5
+    check_ritz_parity(w, g, res_or)
+
+
+def test_single_pass_option(fo, ctx):
+    # one Gram-Schmidt pass: the paper's literal line
+    n = 5000
+    d = np.linspace(1.0, 2.0, n).astype(np.float32)
+    v1 = wl.normal_vector(1, 98, n)
+    op = ctx.hvp_diag(dev(d))
+    Q = fo.ColMajor(n, 11)
+    Q.col(0).copy_(dev(v1))
+    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, 10, reorth_passes=1)
+    res = oracle.lanczos(lambda v: oracle.hvp_diag(d, v), v1, 10)
+    assert m_eff == 10
+    # a single classical Gram-Schmidt pass in fp32 loses orthogonality quickly (the error grows ~30x per
+    # step on this operator), which is why two passes are the default: only the early entries are compared
+    assert np.max(np.abs(alpha[:6] - res.alpha[:6])) < 1e-6 and np.max(np.abs(beta[:6] - res.beta[:6])) < 1e-6
+    op.close()
+
+
+# ------------------------------------------------------------------ update rule and multiplier rule
+def _random_basis(n, r, seed):
+    return np.linalg.qr(np.random.default_rng(seed).standard_normal((n, r)))[0].astype(np.float32)
+
+
+@pytest.mark.parametrize("n,r", [(7, 2), (1025, 0), (1025, 1), (50003, 15), (50003, 40)])
+@pytest.mark.parametrize("with_pi", [False, True])
+def test_update_step_against_oracle(fo, ctx, n, r, with_pi):
+    rng = np.random.default_rng(n + r)
+    Vh = _random_basis(n, r, 5) if r else np.zeros((n, 0), dtype=np.float32)
+    ev = np.concatenate([rng.uniform(1, 50, r - r // 3), -rng.uniform(0.5, 5, r // 3)]) if r else np.zeros(0)
+    w0, g, b0 = (rng.standard_normal(n).astype(np.float32) for _ in range(3))
+    pi = (0.1 * rng.standard_normal(n)).astype(np.float32) if with_pi else None
+    V = fo.ColMajor.from_numpy(Vh, wl.padded_ld(n)) if r else None
+    wd, md = dev(w0), dev(b0)
+    sp = fo.StepParams(0.1, 0.01, 0.9, 5e-4, 0)
+    for _ in range(2):   # two steps so that the momentum buffer is exercised
+        fo.fosi_step(ctx, V, r, ev, dev(g), dev(pi) if with_pi else None, md, wd, sp)
+    ctx.synchronize()
+    w_ref, b_ref = w0, b0
+    f32 = lambda x: float(np.float32(x))
+    for _ in range(2):
+        w_ref, b_ref = oracle.fosi_step(w_ref, g, Vh, ev, b_ref, f32(0.1), f32(0.01), f32(0.9), f32(5e-4), pi=pi)
+    assert rel_l2(wd.cpu().numpy(), w_ref) <= STEP_RTOL
+    assert rel_l2(md.cpu().numpy(), b_ref) <= STEP_RTOL
+
+
+def test_abs_curvature_mode(fo, ctx):
+    n, r = 3001, 6
+    rng = np.random.default_rng(3)
+    Vh = _random_basis(n, r, 6)
+    ev = np.array([9.0, 4.0, 2.0, -1.0, -3.0, 0.5])
+    w0, g = rng.standard_normal(n).astype(np.float32), rng.standard_normal(n).astype(np.float32)
+    V = fo.ColMajor.from_numpy(Vh, wl.padded_ld(n))
+    wd, md = dev(w0), torch.zeros(n, device="cuda")
+    fo.fosi_step(ctx, V, r, ev, dev(g), None, md, wd, fo.StepParams(0.1, 0.01, 0.9, 0.0, 1))
+    ctx.synchronize()
+    f32 = lambda x: float(np.float32(x))
+    w_ref, _ = oracle.fosi_step(w0, g, Vh, ev, np.zeros(n), f32(0.1), f32(0.01), f32(0.9), curv_mode="abs")
+    assert rel_l2(wd.cpu().numpy(), w_ref) <= STEP_RTOL
+
+
+def test_admm_outer_iteration_cfg2_reduced(fo, ctx):
+    """One outer iteration of Algorithm 3 on a reduced config-2 workload: curvature,
+    anchor, ten inner updates with fresh gradients, multiplier update."""
+    w = wl.planted_workload(2, n=(1 << 16) + 7)
+    g = gpu_curvature(fo, ctx, w)
+    p = w.params
+    sig = float(p.sigma)
+    sp = fo.StepParams(float(p.alpha), float(p.lr), float(p.momentum), sig, 0)
+    rng = np.random.default_rng(0)
+    pi0 = (1e-3 * rng.standard_normal(w.n)).astype(np.float32)
+    wa, pi, mom, anchor = dev(w.w0), dev(pi0), torch.zeros(w.n, device="cuda"), torch.zeros(w.n, device="cuda")
+    fo.fosi_admm_begin(ctx, sig, pi, anchor, wa)
+    for t in range(w.steps):
+        fo.fosi_step(ctx, g["V"], w.k + w.l, g["evals"], dev(w.grad(t)), pi, mom, wa, sp)
+    fo.fosi_admm_end(ctx, sig, anchor, wa, pi)
+    ctx.synchronize()
+    Vg = g["V"].to_numpy().astype(np.float64)
+    # the oracle mirrors the fp32 storage of the anchor (pi / sigma is ~1e3 times larger than pi)
+    a_ref, wa_ref = oracle.admm_begin(w.w0, pi0, sig)
+    assert rel_l2(anchor.cpu().numpy(), a_ref) <= 1e-6
+    b_ref = np.zeros(w.n)
+    for t in range(w.steps):
+        wa_ref, b_ref = oracle.fosi_step(wa_ref, w.grad(t), Vg, g["evals"], b_ref, float(p.alpha), float(p.lr),
+                                         float(p.momentum), sig, pi=pi0)
+    assert rel_l2(wa.cpu().numpy(), wa_ref) <= STEP_RTOL
+    assert rel_l2(mom.cpu().numpy(), b_ref) <= STEP_RTOL
+    # multiplier: compare the increment computed from the GPU's own (stored) vectors
+    pi_ref = oracle.admm_end(anchor.cpu().numpy(), wa.cpu().numpy(), pi0, sig)
+    assert rel_l2(pi.cpu().numpy(), pi_ref) <= 1e-6
+
+
+# ------------------------------------------------------------------ error paths (host checks; every kernel exits normally)
+def test_argument_errors(fo, ctx):
+    w = wl.planted_workload(1, n=256)
+    U = fo.ColMajor.from_numpy(w.U, 256)
+    op = ctx.hvp_planted(U, dev(w.lam), 0.1)
+    Q = fo.ColMajor(256, 9, 256)
+    Q.col(0).copy_(dev(w.v1))
+    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, 8)
+    V = fo.ColMajor(256, 9, 256)
+    with pytest.raises(fo.FosiError) as e:
+        fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, 6, 3, V)          # k + l > m_eff
+    assert e.value.status == -3
+    bad = fo.ColMajor(256, 9, 258)                                   # ld not a multiple of 4
+    with pytest.raises(fo.FosiError) as e:
+        fo.fosi_lanczos(ctx, op, bad, 8)
+    assert e.value.status == -2
+    with pytest.raises(fo.FosiError) as e:
+        fo.fosi_lanczos(ctx, op, Q, 300)                             # beyond FOSI_MAX_COLS
+    assert e.value.status == -8
+    with pytest.raises(fo.FosiError) as e:                           # zero Newton divisor
+        fo.fosi_step(ctx, V, 2, np.array([1.0, 0.0]), dev(w.v1), None, torch.zeros(256, device="cuda"),
+                     torch.zeros(256, device="cuda"), fo.StepParams())
+    assert e.value.status == -4
+    op.close()
+
+
+def test_nonfinite_operator_is_reported(fo, ctx):
+    n = 512
+    Q = fo.ColMajor(n, 6, 512)
+    Q.col(0).copy_(dev(wl.normal_vector(1, 97, n)))
+
+    def poison(v_ptr, hv_ptr, stream):
+        j = (hv_ptr - Q.ptr) // (4 * Q.ld)
+        Q.col(j).fill_(float("nan"))
+        return 0
+
+    op = ctx.hvp_callback(n, poison)
+    with pytest.raises(fo.FosiError) as e:
+        fo.fosi_lanczos(ctx, op, Q, 5)
+    assert e.value.status == -4
+    op.close()
+
+
+def test_callback_operator_matches_builtin(fo, ctx):
+    n = 3000
+    d = dev(np.linspace(0.5, 9.0, n))
+    Q1, Q2 = fo.ColMajor(n, 9), fo.ColMajor(n, 9)
+    v1 = dev(wl.normal_vector(1, 96, n))
+    Q1.col(0).copy_(v1)
+    Q2.col(0).copy_(v1)
+
+    def cb(v_ptr, hv_ptr, stream):
+        jv = (v_ptr - Q2.ptr) // (4 * Q2.ld)
+        jh = (hv_ptr - Q2.ptr) // (4 * Q2.ld)
+        torch.mul(d, Q2.col(jv), out=Q2.col(jh))
+        return 0
+
+    op1, op2 = ctx.hvp_diag(d), ctx.hvp_callback(n, cb)
+    a1, b1, m1 = fo.fosi_lanczos(ctx, op1, Q1, 8)
+    a2, b2, m2 = fo.fosi_lanczos(ctx, op2, Q2, 8)
+    assert m1 == m2 == 8 and np.array_equal(a1, a2) and np.array_equal(b1, b2)
+    op1.close()
+    op2.close()
