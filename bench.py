@@ -80,6 +80,9 @@ def main() -> int:
     ap.add_argument("--passes", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=1_600_000)
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="short run for hardware-counter collection: 3 plain copies of 1 GiB (calibration), then a "
+                         "Lanczos run of 6 steps, Ritz vectors and one update on the chosen workload; no timing")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -122,6 +125,19 @@ def main() -> int:
         if w.admm:
             fo.fosi_admm_end(ctx, sp.sigma, anchor, wa, pi)
         state.update(m_eff=m_eff, evals=evals, resid=resid)
+
+    if args.pmc_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)            # reads 1 GiB, writes 1 GiB: the counters' calibration point
+        Q.col(0).copy_(w.v1)
+        alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, 6, reorth_passes=args.passes)
+        evals, _ = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, 3, 2, V)
+        fo.fosi_step(ctx, V, r_v, np.linspace(10.0, 1.0, r_v), g, pi, mom, wa, sp)
+        ctx.synchronize()
+        print(json.dumps({"pmc_probe": "done", "n": w.n, "r": w.r, "copy_bytes_each_way": 4 << 28}))
+        return 0
 
     for _ in range(args.warmup):
         one_step()
