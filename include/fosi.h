@@ -175,7 +175,8 @@ fosi_status fosi_admm_end(fosi_ctx* ctx, int64_t n, float sigma, const float* w_
 #define FOSI_PROF_RITZ_VECTORS  5   /* V = Q S                                         */
 #define FOSI_PROF_STEP          6   /* all kernels of one fosi_step                    */
 #define FOSI_PROF_ADMM          7   /* multiplier rule kernels                         */
-#define FOSI_PROF_HVP_GGN       8   /* softmax-GGN operator, whole apply               */
+#define FOSI_PROF_HVP_GGN       8   /* softmax-GGN operator, whole apply; the "bytes"   */
+                                    /* field returns its GEMM flops (4 B d C) instead  */
 #define FOSI_PROF_HVP_OTHER     9   /* diagonal / callback operators                   */
 #define FOSI_PROF_NUM          10
 fosi_status fosi_profile_enable(fosi_ctx* ctx, int on);

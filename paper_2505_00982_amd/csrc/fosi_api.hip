@@ -271,7 +271,8 @@ fosi_status hvp_apply(fosi_hvp* op, const float* v_dev, float* hv_dev) {
             break;
         }
         case fosi_hvp::GGN: {
-            ProfScope p(ctx, FOSI_PROF_HVP_GGN, 0.0);
+            // for this class the "bytes" slot carries the floating-point operations of the two GEMMs
+            ProfScope p(ctx, FOSI_PROF_HVP_GGN, 4.0 * op->B * (double)op->dim * op->C);
             if (fosi_status s = ggn_apply(op, v_dev, hv_dev)) return s;
             break;
         }

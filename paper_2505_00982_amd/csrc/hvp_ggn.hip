@@ -1,10 +1,252 @@
-// Softmax-GGN operator (placeholder until the MFMA kernels land).
+// Softmax-classifier generalised Gauss-Newton operator
+//     H v = X^T [ (diag(p_b) - p_b p_b^T) (X V)_b ]_b / B ,   V = v viewed as d x C row-major,
+// the one dense contraction on the path: two fp32 GEMMs on the matrix cores
+// (v_mfma_f32_32x32x2_f32, 64-lane wavefronts) around a row-wise
+// softmax-Jacobian.  The shapes are small (B x d x C = 512 x 2048 x 1000 in the
+// reference workload: 2 x 2.1 GFLOP), so the first GEMM is split along K to
+// give every CU a tile; the partial products are summed inside the
+// softmax-Jacobian kernel, in a fixed order.
 #include "fosi_internal.h"
 
 namespace fosi {
+namespace {
 
-fosi_status ggn_prepare(fosi_hvp* op) { return fail(op->ctx, FOSI_ERR_INVALID_ARG, "softmax-GGN operator not built yet"); }
-fosi_status ggn_apply(fosi_hvp* op, const float*, float*) { return fail(op->ctx, FOSI_ERR_INVALID_ARG, "softmax-GGN operator not built yet"); }
-void ggn_release(fosi_hvp*) {}
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int TM = 64, TN = 64, TK = 16;   // workgroup tile; each of the 4 waves owns a 32 x 32 quadrant
+constexpr int LDT = TM + 4;
+
+// C[z] (M x N, row-major, ldc) = scale * A[:, kz] * B[kz, :]   over the K range of split z.
+// A is M x K row-major (A_KM == false) or given transposed as K x M row-major (A_KM == true).
+// B is K x N row-major.  VEC: every row start and every 4-column group is 16-byte aligned.
+template <bool A_KM, bool VEC>
+__global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, int lda, const float* __restrict__ Bm,
+                                                  int ldb, float* __restrict__ Cout, int ldc, int M, int N, int K,
+                                                  int klen, int64_t cstride, float scale) {
+    __shared__ float As[2][TK][LDT];   // [k][m]
+    __shared__ float Bs[2][TK][LDT];   // [k][n]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32;
+    const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+    const int kbeg = blockIdx.z * klen;
+    const int kend = min(K, kbeg + klen);
+
+    // this thread's slots in the two tiles
+    const int bk = tid >> 4, bn4 = (tid & 15) * 4;          // B tile (and A tile when A_KM): row k, 4 columns
+    const int am = tid >> 2, ak4 = (tid & 3) * 4;           // A tile when stored M x K: row m, 4 k-values
+    float ra[4], rb[4];
+
+    auto load = [&](int k0) {
+        {   // B tile
+            const int k = k0 + bk, n = n0 + bn4;
+            const float* p = Bm + (int64_t)k * ldb + n;
+            if (VEC && k < kend && n + 3 < N) {
+                const float4 v = *reinterpret_cast<const float4*>(p);
+                rb[0] = v.x; rb[1] = v.y; rb[2] = v.z; rb[3] = v.w;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) rb[i] = (k < kend && n + i < N) ? p[i] : 0.f;
+            }
+        }
+        if (A_KM) {
+            const int k = k0 + bk, m = m0 + bn4;
+            const float* p = A + (int64_t)k * lda + m;
+            if (VEC && k < kend && m + 3 < M) {
+                const float4 v = *reinterpret_cast<const float4*>(p);
+                ra[0] = v.x; ra[1] = v.y; ra[2] = v.z; ra[3] = v.w;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) ra[i] = (k < kend && m + i < M) ? p[i] : 0.f;
+            }
+        } else {
+            const int m = m0 + am, k = k0 + ak4;
+            const float* p = A + (int64_t)m * lda + k;
+            if (VEC && m < M && k + 3 < kend) {
+                const float4 v = *reinterpret_cast<const float4*>(p);
+                ra[0] = v.x; ra[1] = v.y; ra[2] = v.z; ra[3] = v.w;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) ra[i] = (m < M && k + i < kend) ? p[i] : 0.f;
+            }
+        }
+    };
+    auto store = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) Bs[buf][bk][bn4 + i] = rb[i];
+        if (A_KM) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) As[buf][bk][bn4 + i] = ra[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) As[buf][ak4 + i][am] = ra[i];
+        }
+    };
+
+    floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+
+    const int nk = (kend - kbeg + TK - 1) / TK;
+    if (nk > 0) {
+        load(kbeg);
+        store(0);
+    }
+    __syncthreads();
+    const int half = lane >> 5, l32 = lane & 31;
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) load(kbeg + (kt + 1) * TK);       // next tile into registers while this one is multiplied
+#pragma unroll
+        for (int kk = 0; kk < TK; kk += 2) {
+            const float a = As[buf][kk + half][wm + l32];
+            const float b = Bs[buf][kk + half][wn + l32];
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+        }
+        if (kt + 1 < nk) store(buf ^ 1);
+        __syncthreads();
+    }
+    float* Cz = Cout + (int64_t)blockIdx.z * cstride;
+    const int col = n0 + wn + l32;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm + 8 * (v >> 2) + 4 * half + (v & 3);
+        if (row < M && col < N) Cz[(int64_t)row * ldc + col] = acc[v] * scale;
+    }
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_down(v, off, 64));
+    return v;
+}
+__device__ __forceinline__ double wave_sum_d(double v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ double block_sum_d(double v, double* red) {
+    v = wave_sum_d(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
+
+// P[b, :] = softmax(sum_s parts[s][b, :]); one workgroup per row.
+__global__ __launch_bounds__(256) void k_row_softmax(const float* __restrict__ parts, int nsplit, int64_t pstride,
+                                                     int C, float* __restrict__ P) {
+    __shared__ float redf[4];
+    __shared__ double red[4];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int64_t base = (int64_t)b * C;
+    float mx = -INFINITY;
+    for (int c = tid; c < C; c += 256) {
+        float z = 0.f;
+        for (int s = 0; s < nsplit; ++s) z += parts[s * pstride + base + c];
+        mx = fmaxf(mx, z);
+    }
+    mx = wave_max(mx);
+    if ((tid & 63) == 0) redf[tid >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(redf[0], redf[1]), fmaxf(redf[2], redf[3]));
+    double sum = 0.0;
+    for (int c = tid; c < C; c += 256) {
+        float z = 0.f;
+        for (int s = 0; s < nsplit; ++s) z += parts[s * pstride + base + c];
+        sum += exp((double)z - (double)mx);
+    }
+    sum = block_sum_d(sum, red);
+    for (int c = tid; c < C; c += 256) {
+        float z = 0.f;
+        for (int s = 0; s < nsplit; ++s) z += parts[s * pstride + base + c];
+        P[base + c] = (float)(exp((double)z - (double)mx) / sum);
+    }
+}
+
+// Row-wise softmax Jacobian: z = sum_s parts[s][b,:];  y = p . z - p (p^T z), written over parts[0][b,:].
+__global__ __launch_bounds__(256) void k_softmax_jacobian(float* __restrict__ parts, int nsplit, int64_t pstride,
+                                                          int C, const float* __restrict__ P) {
+    __shared__ double red[4];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int64_t base = (int64_t)b * C;
+    double dot = 0.0;
+    for (int c = tid; c < C; c += 256) {
+        float z = 0.f;
+        for (int s = 0; s < nsplit; ++s) z += parts[s * pstride + base + c];
+        dot = fma((double)P[base + c], (double)z, dot);
+    }
+    dot = block_sum_d(dot, red);
+    for (int c = tid; c < C; c += 256) {
+        float z = 0.f;
+        for (int s = 0; s < nsplit; ++s) z += parts[s * pstride + base + c];
+        const double p = P[base + c];
+        parts[base + c] = (float)(p * ((double)z - dot));
+    }
+}
+
+struct GemmPlan {
+    int nsplit, klen;
+};
+
+GemmPlan plan_split(int M, int N, int K, int sm_count) {
+    const int tiles = ((M + TM - 1) / TM) * ((N + TN - 1) / TN);
+    int s = (2 * sm_count) / (tiles > 0 ? tiles : 1);
+    if (s < 1) s = 1;
+    if (s > 8) s = 8;
+    int klen = ((K + s - 1) / s + TK - 1) / TK * TK;
+    if (klen < TK) klen = TK;
+    s = (K + klen - 1) / klen;
+    return {s, klen};
+}
+
+template <bool A_KM>
+void launch_gemm(fosi_ctx* ctx, const float* A, int lda, const float* Bm, int ldb, float* Cout, int ldc, int M, int N,
+                 int K, GemmPlan plan, int64_t cstride, float scale) {
+    const dim3 grid((N + TN - 1) / TN, (M + TM - 1) / TM, plan.nsplit);
+    const bool vec = (lda % 4 == 0) && (ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(A) & 15) == 0) &&
+                     ((reinterpret_cast<uintptr_t>(Bm) & 15) == 0);
+    if (vec)
+        hipLaunchKernelGGL((k_gemm_f32<A_KM, true>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N, K,
+                           plan.klen, cstride, scale);
+    else
+        hipLaunchKernelGGL((k_gemm_f32<A_KM, false>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N, K,
+                           plan.klen, cstride, scale);
+}
+
+}  // namespace
+
+fosi_status ggn_prepare(fosi_hvp* op) {
+    fosi_ctx* ctx = op->ctx;
+    const int B = op->B, d = op->dim, C = op->C;
+    const GemmPlan plan = plan_split(B, C, d, ctx->sm_count);
+    const size_t bc = (size_t)B * C;
+    if (hipMalloc(reinterpret_cast<void**>(&op->P), bc * sizeof(float)) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void**>(&op->Z), bc * sizeof(float) * plan.nsplit) != hipSuccess)
+        return fail(ctx, FOSI_ERR_NOMEM, "softmax-GGN work buffers");
+    // P = softmax(X W)
+    launch_gemm<false>(ctx, op->X, d, op->W, C, op->Z, C, B, C, d, plan, (int64_t)bc, 1.f);
+    hipLaunchKernelGGL(k_row_softmax, dim3(B), dim3(256), 0, ctx->stream, op->Z, plan.nsplit, (int64_t)bc, C, op->P);
+    return check_hip(ctx, hipGetLastError(), "softmax-GGN prepare");
+}
+
+fosi_status ggn_apply(fosi_hvp* op, const float* v, float* hv) {
+    fosi_ctx* ctx = op->ctx;
+    const int B = op->B, d = op->dim, C = op->C;
+    const GemmPlan plan = plan_split(B, C, d, ctx->sm_count);
+    const int64_t bc = (int64_t)B * C;
+    // Z = X V (split along d), Y = softmax-Jacobian rows of Z, hv = X^T Y / B
+    launch_gemm<false>(ctx, op->X, d, v, C, op->Z, C, B, C, d, plan, bc, 1.f);
+    hipLaunchKernelGGL(k_softmax_jacobian, dim3(B), dim3(256), 0, ctx->stream, op->Z, plan.nsplit, bc, C, op->P);
+    launch_gemm<true>(ctx, op->X, d, op->Z, C, hv, C, d, C, B, GemmPlan{1, (B + TK - 1) / TK * TK}, 0,
+                      1.f / (float)B);
+    return FOSI_OK;
+}
+
+void ggn_release(fosi_hvp* op) {
+    if (op->P != nullptr) (void)hipFree(op->P);
+    if (op->Z != nullptr) (void)hipFree(op->Z);
+    op->P = nullptr;
+    op->Z = nullptr;
+}
 
 }  // namespace fosi

@@ -42,3 +42,22 @@ def reduced_tridiagonal(U: np.ndarray, lam: np.ndarray, shift: float, v1: np.nda
     P = np.eye(len(z)) - 2.0 * np.outer(u, u) / (u @ u) if np.linalg.norm(u) > 0 else np.eye(len(z))
     Hh = sla.hessenberg(P.T @ M @ P)
     return np.diag(Hh).copy(), np.abs(np.diag(Hh, -1))
+
+
+def reduced_tridiagonal_from_gram(G: np.ndarray, lam: np.ndarray, shift: float):
+    """Same independent route as `reduced_tridiagonal`, for sizes where [U, v1]
+    cannot be factorised on the host: only its (r+1) x (r+1) Gram matrix G is
+    needed.  With [U, v1] = Bs R (R from the Cholesky factor of G), Bs^T U is the
+    first r columns of R and Bs^T v1 its last column."""
+    import scipy.linalg as sla
+    r = G.shape[0] - 1
+    R = np.linalg.cholesky(G).T
+    Ru = R[:, :r]
+    M = Ru @ np.diag(np.asarray(lam, dtype=np.float64)) @ Ru.T + float(shift) * np.eye(r + 1)
+    z = R[:, r] / np.linalg.norm(R[:, r])
+    e1 = np.zeros_like(z)
+    e1[0] = 1.0
+    u = z - e1
+    P = np.eye(len(z)) - 2.0 * np.outer(u, u) / (u @ u) if np.linalg.norm(u) > 0 else np.eye(len(z))
+    Hh = sla.hessenberg(P.T @ M @ P)
+    return np.diag(Hh).copy(), np.abs(np.diag(Hh, -1))

@@ -1,0 +1,174 @@
+"""GPU parity at the benchmark's sizes.
+
+Workload 2 (n = 2^20) is small enough for the complete CPU oracle.  Workload 4
+(n = 25.6 M, the configuration bench.py times) is too large for it, so the HIP
+path is checked there through (a) the tridiagonal obtained by an independent
+route (Householder reduction of the operator restricted to span([U, v1]), which
+needs only a small Gram matrix, accumulated in float64 by library matmuls),
+(b) invariants evaluated with library float64 operations, and (c) sampled rows
+of the Ritz vectors and of the update, which the oracle's formulas give one by
+one."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+from oracle.lanczos import tridiagonal
+from tests.helpers import reduced_tridiagonal_from_gram, rel_l2, sin_principal_angles
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fo():
+    import paper_2505_00982_amd as fo
+    return fo
+
+
+@pytest.fixture(scope="module")
+def ctx(fo):
+    c = fo.Context(0)
+    yield c
+    c.close()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def test_workload2_full_size_against_complete_oracle(fo, ctx):
+    w = wl.planted_workload(2)
+    ld = wl.padded_ld(w.n)
+    U = fo.ColMajor.from_numpy(w.U, ld)
+    op = ctx.hvp_planted(U, dev(w.lam), float(w.shift))
+    Q = fo.ColMajor(w.n, w.m + 1, ld)
+    Q.col(0).copy_(dev(w.v1))
+    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, w.m)
+    r_v = w.k + w.l
+    V = fo.ColMajor(w.n, r_v, ld)
+    evals, resid = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, w.k, w.l, V)
+    ctx.synchronize()
+
+    res = oracle.lanczos(lambda v: oracle.hvp_planted(w.U, w.lam, float(w.shift), v), w.v1, w.m)
+    rz = oracle.ritz(res.Q, res.alpha, res.beta, res.m_eff, w.k, w.l)
+    assert m_eff == res.m_eff == w.m
+    scale = np.abs(w.lam).max()
+    assert np.max(np.abs(alpha - res.alpha)) < 1e-5 * scale and np.max(np.abs(beta - res.beta)) < 1e-5 * scale
+    assert np.max(np.abs(evals - rz.evals) / np.abs(rz.evals)) <= 1e-4
+    Vg = V.to_numpy().astype(np.float64)
+    assert sin_principal_angles(rz.V[:, : w.k], Vg[:, : w.k]).max() < 1e-3
+    assert sin_principal_angles(rz.V[:, w.k:], Vg[:, w.k:]).max() < 1e-3
+
+    # one outer iteration of Algorithm 3: anchor, ten updates with fresh gradients, multiplier update
+    p = w.params
+    sig = float(p.sigma)
+    sp = fo.StepParams(float(p.alpha), float(p.lr), float(p.momentum), sig, 0)
+    pi0 = (1e-3 * wl.normal_vector(2, 40, w.n)).astype(np.float32)
+    wa, pi = dev(w.w0), dev(pi0)
+    mom, anchor = torch.zeros(w.n, device="cuda"), torch.zeros(w.n, device="cuda")
+    fo.fosi_admm_begin(ctx, sig, pi, anchor, wa)
+    for t in range(w.steps):
+        fo.fosi_step(ctx, V, r_v, evals, dev(w.grad(t)), pi, mom, wa, sp)
+    fo.fosi_admm_end(ctx, sig, anchor, wa, pi)
+    ctx.synchronize()
+    _, wa_ref = oracle.admm_begin(w.w0, pi0, sig)
+    b_ref = np.zeros(w.n)
+    for t in range(w.steps):
+        wa_ref, b_ref = oracle.fosi_step(wa_ref, w.grad(t), Vg, evals, b_ref, float(p.alpha), float(p.lr),
+                                         float(p.momentum), sig, pi=pi0)
+    assert rel_l2(wa.cpu().numpy(), wa_ref) <= 1e-5
+    assert rel_l2(mom.cpu().numpy(), b_ref) <= 1e-5
+    pi_ref = oracle.admm_end(anchor.cpu().numpy(), wa.cpu().numpy(), pi0, sig)
+    assert rel_l2(pi.cpu().numpy(), pi_ref) <= 1e-6
+    op.close()
+
+
+def _gram_f64(M: torch.Tensor, n: int, extra: torch.Tensor, chunk: int = 1 << 20) -> np.ndarray:
+    """Gram matrix of [rows of M transposed | extra] in float64, by row chunks (library matmul)."""
+    c = M.shape[0]
+    G = torch.zeros(c + 1, c + 1, dtype=torch.float64, device=M.device)
+    for lo in range(0, n, chunk):
+        hi = min(n, lo + chunk)
+        blk = torch.cat([M[:, lo:hi].double(), extra[lo:hi].double()[None, :]], dim=0)
+        G += blk @ blk.T
+    return G.cpu().numpy()
+
+
+def test_workload4_full_size(fo, ctx):
+    from workloads.device import planted_workload_device
+    w = planted_workload_device(4)
+    n, m, r = w.n, w.m, w.r
+    U = fo.ColMajor(n, r, w.ld, buf=w.U)
+    op = ctx.hvp_planted(U, w.lam, w.shift)
+    Q = fo.ColMajor(n, m + 1, w.ld)
+    Q.col(0).copy_(w.v1)
+    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, m)
+    r_v = w.k + w.l
+    V = fo.ColMajor(n, r_v, w.ld)
+    evals, resid = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, w.k, w.l, V)
+    ctx.synchronize()
+    assert m_eff == m
+    lam = w.lam.cpu().numpy().astype(np.float64)
+    scale = np.abs(lam).max()
+
+    # (a) tridiagonal by the independent route
+    G = _gram_f64(w.U.view(r, w.ld), n, w.v1)
+    a_ref, b_ref = reduced_tridiagonal_from_gram(G, lam, w.shift)
+    assert np.max(np.abs(alpha[:40] - a_ref[:40])) < 1e-5 * scale
+    assert np.max(np.abs(beta[:40] - b_ref[:40])) < 1e-5 * scale
+    u_ref = np.linalg.eigvalsh(tridiagonal(a_ref, b_ref, m))
+    ref_vals = np.concatenate([u_ref[::-1][: w.k], u_ref[: w.l]])
+    assert np.max(np.abs(evals - ref_vals) / np.abs(ref_vals)) <= 1e-4, (evals, ref_vals)
+
+    # (b) invariants with library float64 operations
+    Qm = Q.buf[: (m + 1) * w.ld].view(m + 1, w.ld)
+    Gq = torch.zeros(m, m, dtype=torch.float64, device="cuda")
+    for lo in range(0, n, 1 << 20):
+        blk = Qm[:m, lo:min(n, lo + (1 << 20))].double()
+        Gq += blk @ blk.T
+    assert (Gq - torch.eye(m, dtype=torch.float64, device="cuda")).abs().max().item() < 1e-5
+    Vm = V.buf[: r_v * w.ld].view(r_v, w.ld)
+    Gv = torch.zeros(r_v, r_v, dtype=torch.float64, device="cuda")
+    for lo in range(0, n, 1 << 20):
+        blk = Vm[:, lo:min(n, lo + (1 << 20))].double()
+        Gv += blk @ blk.T
+    assert (Gv - torch.eye(r_v, dtype=torch.float64, device="cuda")).abs().max().item() < 1e-5
+
+    # (c) sampled rows of the Ritz vectors: V[rows] = Q[rows, :m] S with S from LAPACK on the GPU's own T
+    rows = torch.from_numpy(np.random.default_rng(7).choice(n, 4096, replace=False)).cuda()
+    uT, ST = np.linalg.eigh(tridiagonal(alpha, beta, m))
+    sel = np.concatenate([np.arange(m - 1, m - 1 - w.k, -1), np.arange(w.l)])
+    Qs = Qm[:m][:, rows].double().cpu().numpy().T           # 4096 x m
+    Vs = Vm[:, rows].double().cpu().numpy().T               # 4096 x r_v
+    ref = Qs @ ST[:, sel]
+    sign = np.sign(np.sum(ref * Vs, axis=0))
+    assert np.max(np.abs(ref * sign - Vs)) <= 2e-6 * np.sqrt(m) * np.abs(Qs).max()
+
+    # (c) sampled rows of one update; the two small coefficient vectors come from library float64 products
+    p = w.params
+    sp = fo.StepParams(float(p.alpha), float(p.lr), float(p.momentum), float(p.sigma), 0)
+    g = w.grad(0)
+    wa, mom = w.w0.clone(), torch.zeros(n, device="cuda")
+    c = torch.zeros(r_v, dtype=torch.float64, device="cuda")
+    for lo in range(0, n, 1 << 20):
+        hi = min(n, lo + (1 << 20))
+        c += Vm[:, lo:hi].double() @ g[lo:hi].double()
+    fo.fosi_step(ctx, V, r_v, evals, g, None, mom, wa, sp)
+    ctx.synchronize()
+    c = c.cpu().numpy()
+    gs = g[rows].double().cpu().numpy()
+    w0s = w.w0[rows].double().cpu().numpy()
+    # b = g - V c (zero initial momentum); e = V^T b computed the same way
+    e = torch.zeros(r_v, dtype=torch.float64, device="cuda")
+    for lo in range(0, n, 1 << 20):
+        hi = min(n, lo + (1 << 20))
+        vb = Vm[:, lo:hi].double()
+        e += vb @ (g[lo:hi].double() - vb.T @ torch.from_numpy(c).cuda())
+    e = e.cpu().numpy()
+    al, lr = float(p.alpha), float(p.lr)
+    b_s = gs - Vs @ c
+    w_s = w0s - al * (Vs @ (c / evals)) - lr * b_s + lr * (Vs @ e)
+    assert rel_l2(mom[rows].cpu().numpy(), b_s) <= 1e-5
+    assert rel_l2(wa[rows].cpu().numpy(), w_s) <= 1e-5
+    op.close()

@@ -1,0 +1,106 @@
+"""CPU-side checks of the shared library: it loads, exports every function the
+header declares, and its host-only code (the tridiagonal eigen-solver, status
+strings) is correct.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def fo():
+    import paper_2505_00982_amd as fo
+    if not os.path.exists(fo.library_path()):
+        from paper_2505_00982_amd.build import build_library
+        build_library(verbose=False)
+    return fo
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "fosi.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(?:fosi_status|const char\*)\s+((?:fosi|hvp)_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_header_declares_the_boundary():
+    names = declared_functions()
+    for must in ("fosi_lanczos", "fosi_ritz", "fosi_step", "fosi_admm_begin", "fosi_admm_end", "hvp_planted_create",
+                 "hvp_diag_create", "hvp_softmax_ggn_create", "hvp_callback_create", "hvp_apply", "hvp_destroy",
+                 "fosi_ctx_create", "fosi_tridiag_eigh"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(fo):
+    lib = fo.load_library()
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+    assert sorted(fo.binding.EXPORTS) == declared_functions()
+
+
+def test_status_strings(fo):
+    lib = fo.load_library()
+    assert lib.fosi_status_string(0) == b"ok"
+    assert b"layout" in lib.fosi_status_string(-2)
+    assert lib.fosi_status_string(-99) == b"unknown status"
+    assert lib.fosi_last_error(None) == b"null context"
+
+
+@pytest.mark.parametrize("m", [1, 2, 3, 17, 61, 101, 255])
+def test_tridiagonal_solver_against_lapack(fo, m):
+    rng = np.random.default_rng(m)
+    a = rng.standard_normal(m) * 10.0 ** rng.uniform(-2, 4, m)
+    b = np.abs(rng.standard_normal(max(m - 1, 0))) * 10.0 ** rng.uniform(-3, 3, max(m - 1, 0))
+    ev, Z = fo.fosi_tridiag_eigh(a, b)
+    T = np.diag(a) + (np.diag(b, 1) + np.diag(b, -1) if m > 1 else 0)
+    ref = np.linalg.eigvalsh(T)
+    scale = max(np.abs(ref).max(), 1e-300)
+    assert np.all(np.diff(ev) >= 0)
+    assert np.abs(ev - ref).max() <= 1e-13 * scale
+    assert np.abs(T @ Z - Z * ev).max() <= 1e-12 * scale
+    assert np.abs(Z.T @ Z - np.eye(m)).max() <= 1e-12
+
+
+def test_tridiagonal_solver_special_cases(fo):
+    # decoupled blocks (zero off-diagonal entries) and repeated eigenvalues
+    a = np.array([2.0, 2.0, 5.0, 5.0, -1.0])
+    b = np.array([0.0, 0.0, 0.0, 0.0])
+    ev, Z = fo.fosi_tridiag_eigh(a, b)
+    assert np.allclose(ev, [-1, 2, 2, 5, 5])
+    assert np.abs(Z.T @ Z - np.eye(5)).max() < 1e-14
+    # the (1, -2, 1)-type matrix has the closed-form spectrum 2 - 2 cos(j pi / (m+1))
+    m = 50
+    ev = fo.fosi_tridiag_eigh(np.full(m, 2.0), np.full(m - 1, -1.0), vectors=False)
+    j = np.arange(1, m + 1)
+    assert np.abs(ev - (2 - 2 * np.cos(j * np.pi / (m + 1)))).max() < 1e-13
+
+
+def test_tridiagonal_solver_rejects_bad_input(fo):
+    lib = fo.load_library()
+    ev = np.zeros(3)
+    dp = C.POINTER(C.c_double)
+    a = np.array([1.0, np.nan, 2.0])
+    b = np.array([1.0, 1.0, 0.0])
+    assert lib.fosi_tridiag_eigh(3, a.ctypes.data_as(dp), b.ctypes.data_as(dp), ev.ctypes.data_as(dp), None) == -4
+    assert lib.fosi_tridiag_eigh(0, a.ctypes.data_as(dp), b.ctypes.data_as(dp), ev.ctypes.data_as(dp), None) == -1
+    assert lib.fosi_tridiag_eigh(3, None, b.ctypes.data_as(dp), ev.ctypes.data_as(dp), None) == -1
+
+
+def test_null_context_is_rejected_without_touching_a_gpu(fo):
+    lib = fo.load_library()
+    assert lib.fosi_ctx_synchronize(None) == -1
+    assert lib.fosi_ctx_destroy(None) == -1
+    assert lib.hvp_apply(None, None, None) == -1
+    assert lib.fosi_profile_enable(None, 1) == -1
+    assert lib.fosi_admm_begin(None, 10, 0.1, None, None, None) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr
