@@ -26,14 +26,22 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_vectors(m_eff: int, r: int, r_v: int, passes: int, with_pi: bool) -> dict:
+REORTH_MODES = {"single": 1, "twice": 2, "local_full": 3}
+
+
+def algorithmic_vectors(m_eff: int, r: int, r_v: int, reorth: str, with_pi: bool) -> dict:
     """Vectors (4n bytes each) the variant that is run must move, per phase.
-    Per Lanczos step with c = i+1 live columns: operator (r+1) + (r+2); each
-    Gram-Schmidt pass (c+1) + (c+2); normalisation 2.  Start vector 3.  Ritz
-    vectors m_eff + r_v.  Update: 4 sweeps of V-hat plus 8 vector accesses (+2
-    with a dual variable)."""
+    Per Lanczos step with c = i+1 live columns: operator (r+1) + (r+2); a
+    Gram-Schmidt pass against p columns (p+1) + (p+2) -- "single": p = c,
+    "twice": that two times, "local_full": p = min(c, 2) then p = c;
+    normalisation 2.  Start vector 3.  Ritz vectors m_eff + r_v.  Update: 4
+    sweeps of V-hat plus 8 vector accesses (+2 with a dual variable)."""
     hvp = m_eff * (2 * r + 3)
-    reorth = sum(passes * (2 * (i + 1) + 3) for i in range(m_eff))
+
+    def gs(c):
+        full = 2 * c + 3
+        return {"single": full, "twice": 2 * full, "local_full": 2 * min(c, 2) + 3 + full}[reorth]
+    reorth = sum(gs(i + 1) for i in range(m_eff))
     norm = 2 * m_eff + 3
     ritz = m_eff + r_v
     step = 4 * r_v + 8 + (2 if with_pi else 0)
@@ -56,7 +64,7 @@ def cpu_baseline(cfg_id: int, n_sample: int) -> dict:
     rz = oracle.ritz(res.Q, res.alpha, res.beta, res.m_eff, w.k, w.l)
     oracle.fosi_step(w.w0, g, rz.V, rz.evals, np.zeros(w.n), float(p.alpha), float(p.lr), float(p.momentum))
     dt = time.perf_counter() - t0
-    vecs = algorithmic_vectors(res.m_eff, w.r, w.k + w.l, 1, False)   # the oracle does one Gram-Schmidt pass
+    vecs = algorithmic_vectors(res.m_eff, w.r, w.k + w.l, "single", False)   # the oracle does one Gram-Schmidt pass
     gbs = vecs["total"] * 4.0 * n_sample / dt / 1e9
     try:
         from threadpoolctl import threadpool_info
@@ -77,7 +85,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=4, help="workload id (4 = n 25.6M headline; 2 = n 1M; 5 = n 125M)")
     ap.add_argument("--n", type=int, default=None, help="override the row count (debugging)")
-    ap.add_argument("--passes", type=int, default=2)
+    ap.add_argument("--reorth", choices=sorted(REORTH_MODES), default="local_full",
+                    help="Gram-Schmidt scheme of the Lanczos run (library default: local_full)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=1_600_000)
     ap.add_argument("--pmc-probe", action="store_true",
@@ -117,7 +126,7 @@ def main() -> int:
 
     def one_step():
         Q.col(0).copy_(w.v1)
-        alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, w.m, reorth_passes=args.passes)
+        alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, w.m, reorth_mode=REORTH_MODES[args.reorth])
         evals, resid = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, w.k, w.l, V)
         if w.admm:
             fo.fosi_admm_begin(ctx, sp.sigma, pi, anchor, wa)
@@ -132,7 +141,7 @@ def main() -> int:
         for _ in range(3):
             dst.copy_(src)            # reads 1 GiB, writes 1 GiB: the counters' calibration point
         Q.col(0).copy_(w.v1)
-        alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, 6, reorth_passes=args.passes)
+        alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, 6, reorth_mode=REORTH_MODES[args.reorth])
         evals, _ = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, 3, 2, V)
         fo.fosi_step(ctx, V, r_v, np.linspace(10.0, 1.0, r_v), g, pi, mom, wa, sp)
         ctx.synchronize()
@@ -153,7 +162,7 @@ def main() -> int:
 
     ms_per_step = dt / args.steps * 1e3
     vec_bytes = 4.0 * w.n
-    vecs = algorithmic_vectors(state["m_eff"], w.r, r_v, args.passes, w.admm)
+    vecs = algorithmic_vectors(state["m_eff"], w.r, r_v, args.reorth, w.admm)
     if w.admm:
         vecs["total"] += 8
     step_bytes = vecs["total"] * vec_bytes
@@ -187,7 +196,7 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"cfg{args.config}: planted spectrum n={w.n}, r={w.r}, Lanczos m={w.m} with "
-                               f"{args.passes} Gram-Schmidt passes, k={w.k}, l={w.l}, one update"
+                               f"'{args.reorth}' Gram-Schmidt, k={w.k}, l={w.l}, one update"
                                f"{' with ADMM begin/end' if w.admm else ''}",
                    "accumulation": "f64 products and sums, one rounding per stored fp32 vector",
                    "m_eff": state["m_eff"], "algorithmic_GB_per_step": round(step_bytes / 1e9, 1),

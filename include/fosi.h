@@ -89,12 +89,18 @@ fosi_status hvp_destroy(fosi_hvp* op);
 
 /* ---- Algorithm 1: Lanczos with full reorthogonalisation ------------------- */
 
+/* How the Gram-Schmidt line of Algorithm 1 (h <- h - D (D^T h)) is carried out. */
+#define FOSI_REORTH_SINGLE      1   /* one pass against all columns: the line as printed            */
+#define FOSI_REORTH_TWICE       2   /* that pass done twice                                         */
+#define FOSI_REORTH_LOCAL_FULL  3   /* default: a pass against the last two columns (the only ones  */
+                                    /* h is not orthogonal to in exact arithmetic), then the        */
+                                    /* printed pass against all columns                             */
 typedef struct {
-    /* Gram-Schmidt passes per step.  1 is the paper's single pass; 2 (default)
-     * repeats it once, which fp32 storage needs to keep Q orthonormal.  With 2
-     * passes the diagonal entry is the sum of the two coefficients removed
+    /* 0 selects the default.  fp32 storage needs a second pass of some kind to keep Q orthonormal:
+     * TWICE and LOCAL_FULL reach the same orthogonality (~1e-8), LOCAL_FULL with about half the
+     * traffic.  With more than one pass the diagonal entry is the sum of the coefficients removed
      * along the current vector. */
-    int32_t reorth_passes;
+    int32_t reorth_mode;
     /* The step count stops early (m_eff < m) when ||h after orthogonalisation||
      * <= breakdown_tol * ||H q_i||: the Krylov space is exhausted.  Default 1e-6. */
     double breakdown_tol;

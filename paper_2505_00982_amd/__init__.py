@@ -11,6 +11,9 @@ from .binding import (  # noqa: F401
     ColMajor,
     StepParams,
     fosi_lanczos,
+    REORTH_SINGLE,
+    REORTH_TWICE,
+    REORTH_LOCAL_FULL,
     fosi_ritz,
     fosi_step,
     fosi_admm_begin,

@@ -38,7 +38,7 @@ class FosiError(RuntimeError):
 
 
 class _LanczosOpts(C.Structure):
-    _fields_ = [("reorth_passes", C.c_int32), ("breakdown_tol", C.c_double)]
+    _fields_ = [("reorth_mode", C.c_int32), ("breakdown_tol", C.c_double)]
 
 
 class _StepParams(C.Structure):
@@ -234,12 +234,15 @@ class Hvp:
             self.handle = None
 
 
-def fosi_lanczos(ctx: Context, op: Hvp, Q: ColMajor, m: int, reorth_passes: int = 2,
+REORTH_SINGLE, REORTH_TWICE, REORTH_LOCAL_FULL = 1, 2, 3
+
+
+def fosi_lanczos(ctx: Context, op: Hvp, Q: ColMajor, m: int, reorth_mode: int = 0,
                  breakdown_tol: float = 1e-6) -> Tuple[np.ndarray, np.ndarray, int]:
-    """Q.col(0) holds the start vector.  Returns (alpha, beta, m_eff)."""
+    """Q.col(0) holds the start vector.  reorth_mode 0 = library default.  Returns (alpha, beta, m_eff)."""
     alpha, beta = np.zeros(m), np.zeros(m)
     m_eff = C.c_int32(0)
-    opts = _LanczosOpts(reorth_passes, breakdown_tol)
+    opts = _LanczosOpts(reorth_mode, breakdown_tol)
     ctx.check(ctx.lib.fosi_lanczos(ctx.handle, op.handle, Q.n, m, Q.ptr, Q.ld, _dptr(alpha), _dptr(beta),
                                    C.byref(m_eff), C.byref(opts)))
     return alpha, beta, int(m_eff.value)

@@ -111,7 +111,9 @@ fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
     if (hipGetDeviceProperties(&prop, device) == hipSuccess) ctx->sm_count = prop.multiProcessorCount;
     ctx->tun.dot_cols_per_block = env_int("FOSI_DOT_COLS", 16);
     ctx->tun.dot_target_blocks = env_int("FOSI_DOT_BLOCKS", 8 * ctx->sm_count);
-    ctx->tun.comb_rows_per_thread = env_int("FOSI_COMB_ROWS", 1);
+    ctx->tun.comb_rows_per_thread = env_int("FOSI_COMB_ROWS", 4);
+    ctx->tun.comb_cols_unroll = env_int("FOSI_COMB_COLS", 8);
+    ctx->tun.comb_max_blocks = env_int("FOSI_COMB_BLOCKS", 0);
 
     const size_t cols1 = kMaxCols + 1;
     size_t off = 0;
@@ -308,13 +310,15 @@ fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q
     if (op->n != n) return fail(ctx, FOSI_ERR_INVALID_ARG, "operator size differs from n");
     if (m + 1 > kMaxCols) return fail(ctx, FOSI_ERR_LIMIT, "m + 1 exceeds FOSI_MAX_COLS");
     if (fosi_status s = check_matrix(ctx, "Q_dev", Q_dev, n, ldq, m + 1)) return s;
-    int passes = 2;
+    int mode = FOSI_REORTH_LOCAL_FULL;
     double tol = 1e-6;
     if (opts != nullptr) {
-        if (opts->reorth_passes != 0) passes = opts->reorth_passes;
+        if (opts->reorth_mode != 0) mode = opts->reorth_mode;
         if (opts->breakdown_tol > 0.0) tol = opts->breakdown_tol;
     }
-    if (passes != 1 && passes != 2) return fail(ctx, FOSI_ERR_INVALID_ARG, "reorth_passes must be 1 or 2");
+    if (mode != FOSI_REORTH_SINGLE && mode != FOSI_REORTH_TWICE && mode != FOSI_REORTH_LOCAL_FULL)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "unknown reorth_mode");
+    const int passes = mode == FOSI_REORTH_SINGLE ? 1 : 2;
     *m_eff = 0;
 
     const double vec = kVec * (double)n;
@@ -333,14 +337,20 @@ fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q
         const int ncols = i + 1;
         double* coef[2] = {ctx->s.coef_a, ctx->s.coef_b};
         int norm_slots = 0;
+        int pass_cols[2] = {0, 0};
         for (int p = 0; p < passes; ++p) {
-            // Gram-Schmidt against every column built so far; the coefficient along q_i is the diagonal entry
-            launch_dot_columns(ctx, Q_dev, ldq, ncols, h, nullptr, n, coef[p], nullptr, 0, 1.0, flags,
-                               FOSI_PROF_REORTH_DOT, (ncols + 1) * vec);
-            norm_slots = launch_combine_columns(ctx, Q_dev, ldq, ncols, coef[p], h, 1.0, nullptr, 0.0, nullptr, 0.0,
-                                                -1.0, h, n, true, flags, FOSI_PROF_REORTH_SUB, (ncols + 2) * vec);
+            // Gram-Schmidt against the columns built so far (the local first pass: only the last two); the
+            // coefficient along q_i, the last column of either range, is (part of) the diagonal entry
+            const int first = (mode == FOSI_REORTH_LOCAL_FULL && p == 0 && ncols > 2) ? ncols - 2 : 0;
+            const int pc = ncols - first;
+            const float* Qp = Q_dev + (int64_t)first * ldq;
+            launch_dot_columns(ctx, Qp, ldq, pc, h, nullptr, n, coef[p], nullptr, 0, 1.0, flags,
+                               FOSI_PROF_REORTH_DOT, (pc + 1) * vec);
+            norm_slots = launch_combine_columns(ctx, Qp, ldq, pc, coef[p], h, 1.0, nullptr, 0.0, nullptr, 0.0,
+                                                -1.0, h, n, true, flags, FOSI_PROF_REORTH_SUB, (pc + 2) * vec);
+            pass_cols[p] = pc;
         }
-        launch_lanczos_finalize(ctx, i, norm_slots, passes == 2, tol);
+        launch_lanczos_finalize(ctx, i, norm_slots, pass_cols[0], passes == 2 ? pass_cols[1] : 0, tol);
         {
             ProfScope ps(ctx, FOSI_PROF_NORMALISE, 2 * vec);
             launch_scale(ctx, h, ctx->s.scal, n, flags);

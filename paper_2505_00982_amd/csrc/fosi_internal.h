@@ -26,7 +26,9 @@ struct ProfRecord {
 struct Tunables {
     int dot_cols_per_block;   // JB: columns a block of the transposed product accumulates (8, 16 or 32)
     int dot_target_blocks;    // total resident blocks aimed at by the transposed product
-    int comb_rows_per_thread; // float4 row groups per thread in the column-combination kernel (1 or 2)
+    int comb_rows_per_thread; // RPT: float4 row groups per thread in the column-combination kernel
+    int comb_cols_unroll;     // CU: columns loaded together in that kernel
+    int comb_max_blocks;      // cap on that kernel's grid (it grid-strides over row tiles); 0 = no cap
 };
 
 // Device scratch layout (one allocation per context).
@@ -115,7 +117,9 @@ int launch_combine_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols
                            double a2, double sa, float* out, int64_t n, bool want_norm, const int* stop,
                            int prof_cls, double prof_bytes);
 
-void launch_lanczos_finalize(fosi_ctx* ctx, int step, int norm_slots, bool two_pass, double tol);
+// cols_a / cols_b: number of columns of the first / second Gram-Schmidt pass (cols_b == 0: single pass);
+// in both the current Lanczos vector is the last column of the range.
+void launch_lanczos_finalize(fosi_ctx* ctx, int step, int norm_slots, int cols_a, int cols_b, double tol);
 void launch_inv_sqrt(fosi_ctx* ctx, const double* in, double* out);
 void launch_scale(fosi_ctx* ctx, float* x, const double* factor, int64_t n, const int* stop);
 void launch_diag_apply(fosi_ctx* ctx, const float* d, const float* v, float* out, int64_t n);

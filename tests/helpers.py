@@ -61,3 +61,30 @@ def reduced_tridiagonal_from_gram(G: np.ndarray, lam: np.ndarray, shift: float):
     P = np.eye(len(z)) - 2.0 * np.outer(u, u) / (u @ u) if np.linalg.norm(u) > 0 else np.eye(len(z))
     Hh = sla.hessenberg(P.T @ M @ P)
     return np.diag(Hh).copy(), np.abs(np.diag(Hh, -1))
+
+
+def reduced_ritz_coefficients(G: np.ndarray, lam: np.ndarray, shift: float, m: int, k: int, l: int):
+    """Reference Ritz pairs of the planted operator expressed in the basis [U, v1]: returns (evals, Cmat)
+    with V_ref = [U, v1] @ Cmat, from the same Householder route as `reduced_tridiagonal_from_gram` (the
+    Lanczos vectors of the restricted problem are the leading columns of the accumulated reflectors).
+    Everything is (r+1)-dimensional float64 work, so it is available at any n."""
+    import scipy.linalg as sla
+    r = G.shape[0] - 1
+    R = np.linalg.cholesky(G).T
+    Ru = R[:, :r]
+    M = Ru @ np.diag(np.asarray(lam, dtype=np.float64)) @ Ru.T + float(shift) * np.eye(r + 1)
+    z = R[:, r] / np.linalg.norm(R[:, r])
+    e1 = np.zeros_like(z)
+    e1[0] = 1.0
+    u = z - e1
+    P = np.eye(len(z)) - 2.0 * np.outer(u, u) / (u @ u) if np.linalg.norm(u) > 0 else np.eye(len(z))
+    Hh, Qh = sla.hessenberg(P.T @ M @ P, calc_q=True)
+    T = Hh[:m, :m]
+    T = np.triu(np.tril(T, 1), -1)
+    T = 0.5 * (T + T.T)
+    ev, S = np.linalg.eigh(T)
+    sel = np.concatenate([np.arange(m - 1, m - 1 - k, -1), np.arange(l)]).astype(int)
+    Qred = P @ Qh[:, :m]                      # Lanczos vectors of the restricted problem
+    Cmat = np.linalg.solve(R, Qred @ S[:, sel])
+    resid = abs(Hh[m, m - 1]) * np.abs(S[m - 1, sel]) if Hh.shape[0] > m else np.zeros(len(sel))
+    return ev[sel], Cmat, resid, ev

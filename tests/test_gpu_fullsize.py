@@ -15,7 +15,8 @@ import torch
 import oracle
 import workloads as wl
 from oracle.lanczos import tridiagonal
-from tests.helpers import reduced_tridiagonal_from_gram, rel_l2, sin_principal_angles
+from tests.helpers import (reduced_ritz_coefficients, reduced_tridiagonal_from_gram, rel_l2,
+                           sin_principal_angles)
 
 pytestmark = pytest.mark.gpu
 
@@ -120,6 +121,34 @@ def test_workload4_full_size(fo, ctx):
     u_ref = np.linalg.eigvalsh(tridiagonal(a_ref, b_ref, m))
     ref_vals = np.concatenate([u_ref[::-1][: w.k], u_ref[: w.l]])
     assert np.max(np.abs(evals - ref_vals) / np.abs(ref_vals)) <= 1e-4, (evals, ref_vals)
+
+    # (a') Ritz subspaces against the reference Ritz vectors V_ref = [U, v1] C (C from the same independent
+    # route): the cross products V^T [U, v1] are library float64 matmuls
+    ev_ref, Cmat, resid_ref, all_ref = reduced_ritz_coefficients(G, lam, w.shift, m, w.k, w.l)
+    assert np.max(np.abs(evals - ev_ref) / np.abs(ev_ref)) <= 1e-4
+    Vm_ = V.buf[: r_v * w.ld].view(r_v, w.ld)
+    Um_ = w.U.view(r, w.ld)
+    cross = torch.zeros(r_v, r + 1, dtype=torch.float64, device="cuda")
+    for lo in range(0, n, 1 << 20):
+        hi = min(n, lo + (1 << 20))
+        basis = torch.cat([Um_[:, lo:hi].double(), w.v1[lo:hi].double()[None, :]], dim=0)
+        cross += Vm_[:, lo:hi].double() @ basis.T
+    overlap = cross.cpu().numpy() @ Cmat                       # V_gpu^T V_ref, r_v x r_v
+    u32 = 2.0 ** -24
+    for name, blk, outside in (("top", slice(0, w.k), all_ref[m - 1 - w.k]), ("bottom", slice(w.k, r_v), all_ref[w.l])):
+        sv = np.linalg.svd(overlap[blk, blk], compute_uv=False)
+        sines = np.sqrt(np.maximum(0.0, 1.0 - np.minimum(sv, 1.0) ** 2))
+        # per pair: how far the GPU's Ritz vector leaves the reference block
+        leave = np.sqrt(np.maximum(0.0, 1.0 - np.sum(overlap[blk, blk] ** 2, axis=1)))
+        gap = np.min(np.abs(ev_ref[blk] - outside))
+        print(f"[workload 4] {name} block: max sin(angle) {sines.max():.2e}; per pair {np.array2string(leave, precision=1)}; "
+              f"reference residuals {np.array2string(resid_ref[blk], precision=1)}; gap to the next Ritz value {gap:.3f}")
+        resolved = resid_ref[blk] <= 1e-2 * np.abs(ev_ref[blk])
+        # pairs the fp64 reference has resolved: the 1e-3 rad bar
+        assert leave[resolved].max() < 1e-3
+        # the whole block, unresolved pairs included: fp32 storage of the basis perturbs the operator by
+        # ~u32 ||H|| per step, and a Ritz vector moves by about that over the gap to the next Ritz value
+        assert sines.max() < max(1e-3, 16 * u32 * scale / gap)
 
     # (b) invariants with library float64 operations
     Qm = Q.buf[: (m + 1) * w.ld].view(m + 1, w.ld)

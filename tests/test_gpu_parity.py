@@ -46,7 +46,7 @@ def planted_op(w):
     return lambda v: oracle.hvp_planted(w.U, w.lam, float(w.shift), v)
 
 
-def gpu_curvature(fo, ctx, w, m=None, k=None, l=None, passes=2):
+def gpu_curvature(fo, ctx, w, m=None, k=None, l=None, mode=0):
     """Lanczos + Ritz on the GPU for a planted workload; returns a dict of host results."""
     m = m or w.m
     k = w.k if k is None else k
@@ -56,7 +56,7 @@ def gpu_curvature(fo, ctx, w, m=None, k=None, l=None, passes=2):
     op = ctx.hvp_planted(U, dev(w.lam), float(w.shift))
     Q = fo.ColMajor(w.n, m + 1, ld)
     Q.col(0).copy_(dev(w.v1))
-    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, m, reorth_passes=passes)
+    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, m, reorth_mode=mode)
     V = fo.ColMajor(w.n, k + l, ld)
     evals, resid = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, k, l, V)
     ctx.synchronize()
@@ -166,6 +166,16 @@ def test_cfg1_update_step(fo, ctx, cfg1):
     assert rel_l2(md.cpu().numpy(), b_ref) <= STEP_RTOL
 
 
+def test_cfg1_two_full_passes_agree_with_default(fo, ctx, cfg1):
+    w, g, res_or = cfg1
+    g2 = gpu_curvature(fo, ctx, w, mode=fo.REORTH_TWICE)
+    assert g2["m_eff"] in (33, 34)
+    assert np.max(np.abs(g2["alpha"][:16] - g["alpha"][:16])) < 2e-4 * 1e3
+    check_ritz_parity(w, g2, res_or)
+    Q = g2["Q"].to_numpy(g2["m_eff"]).astype(np.float64)
+    assert np.abs(Q.T @ Q - np.eye(g2["m_eff"])).max() < 1e-5
+
+
 def test_repeat_is_bit_identical(fo, ctx, cfg1):
     w, g, _ = cfg1
     g2 = gpu_curvature(fo, ctx, w)
@@ -174,10 +184,11 @@ def test_repeat_is_bit_identical(fo, ctx, cfg1):
 
 
 # ------------------------------------------------------------------ ragged sizes, single pass, small k+l
+@pytest.mark.parametrize("mode", [2, 3])      # two full passes; local pass + full pass (the default)
 @pytest.mark.parametrize("n,m,k,l", [(1000 + 3, 12, 1, 0), (4096 + 61, 20, 3, 2), (70001, 24, 4, 3)])
-def test_ragged_sizes(fo, ctx, n, m, k, l):
+def test_ragged_sizes(fo, ctx, n, m, k, l, mode):
     w = wl.planted_workload(2, n=n)
-    g = gpu_curvature(fo, ctx, w, m=m, k=k, l=l)
+    g = gpu_curvature(fo, ctx, w, m=m, k=k, l=l, mode=mode)
     res_or = oracle.lanczos(planted_op(w), w.v1, m)
     assert g["m_eff"] == res_or.m_eff == m
     scale = np.abs(w.lam).max()
@@ -196,7 +207,7 @@ def test_single_pass_option(fo, ctx):
     op = ctx.hvp_diag(dev(d))
     Q = fo.ColMajor(n, 11)
     Q.col(0).copy_(dev(v1))
-    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, 10, reorth_passes=1)
+    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, 10, reorth_mode=fo.REORTH_SINGLE)
     res = oracle.lanczos(lambda v: oracle.hvp_diag(d, v), v1, 10)
     assert m_eff == 10
     # a single classical Gram-Schmidt pass in fp32 loses orthogonality quickly (the error grows ~30x per

@@ -7,7 +7,7 @@ import pytest
 import oracle
 import workloads as wl
 from oracle.lanczos import lanczos_row_sharded, tridiagonal
-from tests.helpers import reduced_tridiagonal, rel_l2, sin_principal_angles
+from tests.helpers import reduced_ritz_coefficients, reduced_tridiagonal, rel_l2, sin_principal_angles
 
 
 def planted_op(w):
@@ -89,6 +89,18 @@ def test_tridiagonal_matches_householder_reduction(cfg1, cfg2_small):
         scale = np.abs(w.lam).max()
         assert np.max(np.abs(a[:me] - res.alpha[:me])) < 1e-12 * scale
         assert np.max(np.abs(b[: me - 1] - res.beta[: me - 1])) < 1e-12 * scale
+
+
+def test_ritz_pairs_match_householder_route(cfg2_small):
+    # Ritz values *and vectors* (converged or not) from the restricted problem, reduced by Householder reflectors
+    w, res = cfg2_small
+    rz = oracle.ritz(res.Q, res.alpha, res.beta, res.m_eff, w.k, w.l)
+    B = np.column_stack([w.U.astype(np.float64), w.v1.astype(np.float64)])
+    ev, Cm, resid, _ = reduced_ritz_coefficients(B.T @ B, w.lam, w.shift, w.m, w.k, w.l)
+    assert np.allclose(resid, rz.resid, rtol=1e-6, atol=1e-9)
+    assert np.max(np.abs(ev - rz.evals)) < 1e-9 * np.abs(w.lam).max()
+    assert sin_principal_angles(rz.V[:, : w.k], (B @ Cm)[:, : w.k]).max() < 1e-8
+    assert sin_principal_angles(rz.V[:, w.k:], (B @ Cm)[:, w.k:]).max() < 1e-8
 
 
 def test_lanczos_invariants(cfg2_small):
