@@ -32,15 +32,21 @@ REORTH_MODES = {"single": 1, "twice": 2, "local_full": 3}
 def algorithmic_vectors(m_eff: int, r: int, r_v: int, reorth: str, with_pi: bool) -> dict:
     """Vectors (4n bytes each) the variant that is run must move, per phase.
     Per Lanczos step with c = i+1 live columns: operator (r+1) + (r+2); a
-    Gram-Schmidt pass against p columns (p+1) + (p+2) -- "single": p = c,
-    "twice": that two times, "local_full": p = min(c, 2) then p = c;
-    normalisation 2.  Start vector 3.  Ritz vectors m_eff + r_v.  Update: 4
-    sweeps of V-hat plus 8 vector accesses (+2 with a dual variable)."""
+    Gram-Schmidt pass against all columns (c+1) + (c+2) -- "single": once,
+    "twice": two times; "local_full": the local pass rides on the operator's
+    expand sweep (+1 vector, q_{i-1}, when i > 0), the full pass reads h, q_i and
+    q_{i-1} to form its vector (c + 2 + [i > 0]) and one subtraction follows
+    (c+2); normalisation 2.  Start vector 3.  Ritz vectors m_eff + r_v.  Update:
+    4 sweeps of V-hat plus 8 vector accesses (+2 with a dual variable)."""
     hvp = m_eff * (2 * r + 3)
+    if reorth == "local_full":
+        hvp += max(0, m_eff - 1)
 
     def gs(c):
         full = 2 * c + 3
-        return {"single": full, "twice": 2 * full, "local_full": 2 * min(c, 2) + 3 + full}[reorth]
+        if reorth == "local_full":
+            return full + 1 + (1 if c > 1 else 0)
+        return {"single": full, "twice": 2 * full}[reorth]
     reorth = sum(gs(i + 1) for i in range(m_eff))
     norm = 2 * m_eff + 3
     ritz = m_eff + r_v

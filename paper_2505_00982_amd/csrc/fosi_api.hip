@@ -109,20 +109,21 @@ fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
     ctx->stream = static_cast<hipStream_t>(hip_stream);
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) == hipSuccess) ctx->sm_count = prop.multiProcessorCount;
-    ctx->tun.dot_cols_per_block = env_int("FOSI_DOT_COLS", 16);
-    ctx->tun.dot_target_blocks = env_int("FOSI_DOT_BLOCKS", 8 * ctx->sm_count);
+    ctx->tun.dot_target_blocks = env_int("FOSI_DOT_BLOCKS", 2 * ctx->sm_count);
     ctx->tun.comb_rows_per_thread = env_int("FOSI_COMB_ROWS", 4);
     ctx->tun.comb_cols_unroll = env_int("FOSI_COMB_COLS", 8);
     ctx->tun.comb_max_blocks = env_int("FOSI_COMB_BLOCKS", 0);
+    ctx->tun.xcd_partition = env_int("FOSI_XCD_PARTITION", 0);
 
     const size_t cols1 = kMaxCols + 1;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += round256(bytes); return o; };
     const size_t o_part = take(sizeof(double) * kMaxDotSlots * cols1);
-    const size_t o_norm = take(sizeof(double) * kMaxNormSlots);
+    const size_t o_norm = take(sizeof(double) * 3 * kMaxNormSlots);
     const size_t o_ca = take(sizeof(double) * cols1), o_cb = take(sizeof(double) * cols1);
     const size_t o_cc = take(sizeof(double) * cols1), o_ch = take(sizeof(double) * cols1);
     const size_t o_scal = take(sizeof(double) * 8);
+    const size_t o_loc = take(sizeof(double) * 8);
     const size_t o_al = take(sizeof(double) * kMaxCols), o_be = take(sizeof(double) * kMaxCols);
     const size_t o_hn = take(sizeof(double) * kMaxCols), o_nw = take(sizeof(double) * kMaxCols);
     const size_t o_S = take(sizeof(float) * kMaxCols * kMaxCols);
@@ -139,13 +140,17 @@ fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
     ctx->s.coef_c = reinterpret_cast<double*>(b + o_cc);
     ctx->s.coef_h = reinterpret_cast<double*>(b + o_ch);
     ctx->s.scal = reinterpret_cast<double*>(b + o_scal);
+    ctx->s.loc = reinterpret_cast<double*>(b + o_loc);
     ctx->s.alpha = reinterpret_cast<double*>(b + o_al);
     ctx->s.beta = reinterpret_cast<double*>(b + o_be);
     ctx->s.hnorm = reinterpret_cast<double*>(b + o_hn);
     ctx->s.newton = reinterpret_cast<double*>(b + o_nw);
     ctx->s.S = reinterpret_cast<float*>(b + o_S);
     ctx->s.flags = reinterpret_cast<int*>(b + o_fl);
-    if (hipMemsetAsync(ctx->scratch_base, 0, off, ctx->stream) != hipSuccess) {
+    const double ones[2] = {1.0, 1.0};
+    if (hipMemsetAsync(ctx->scratch_base, 0, off, ctx->stream) != hipSuccess ||
+        hipMemcpyAsync(ctx->s.scal + 2, ones, sizeof(ones), hipMemcpyHostToDevice, ctx->stream) != hipSuccess ||
+        hipStreamSynchronize(ctx->stream) != hipSuccess) {
         (void)hipFree(ctx->scratch_base);
         delete ctx;
         return FOSI_ERR_HIP;
@@ -249,26 +254,30 @@ fosi_status hvp_callback_create(fosi_ctx* ctx, int64_t n, fosi_hvp_fn fn, void* 
     return FOSI_OK;
 }
 
-fosi_status hvp_apply(fosi_hvp* op, const float* v_dev, float* hv_dev) {
-    if (op == nullptr) return FOSI_ERR_INVALID_ARG;
+// Applies the operator.  With want_local the scalars of the local Gram-Schmidt pass are produced as
+// well: ctx->s.loc = {hv . v, hv . vprev, ||hv||^2} (vprev may be null: second entry 0) and their
+// negatives in ctx->s.scal[4..5].  The planted operator gets them for free inside its expand sweep;
+// the other operators pay one transposed product against [vprev, v].
+static fosi_status apply_operator(fosi_hvp* op, const float* v_dev, float* hv_dev, const float* vprev,
+                                  bool want_local) {
     fosi_ctx* ctx = op->ctx;
-    if (fosi_status s = check_vector(ctx, "v_dev", v_dev)) return s;
-    if (fosi_status s = check_vector(ctx, "hv_dev", hv_dev)) return s;
-    if (v_dev == hv_dev) return fail(ctx, FOSI_ERR_INVALID_ARG, "v_dev and hv_dev must be distinct");
     const int64_t n = op->n;
     const int* stop = ctx->s.flags;   // zero outside a Lanczos run
+    const double vec = kVec * (double)n;
     switch (op->kind) {
         case fosi_hvp::PLANTED: {
-            const double vec = kVec * (double)n;
             // coefficients lam_j * (u_j . v), then shift v + U (coefficients)
-            launch_dot_columns(ctx, op->U, op->ldu, op->r, v_dev, nullptr, n, ctx->s.coef_h, op->lam, op->r, 1.0, stop,
-                               FOSI_PROF_HVP_PROJECT, (op->r + 1) * vec);
-            launch_combine_columns(ctx, op->U, op->ldu, op->r, ctx->s.coef_h, nullptr, 0.0, v_dev, (double)op->shift,
-                                   nullptr, 0.0, 1.0, hv_dev, n, false, stop, FOSI_PROF_HVP_EXPAND, (op->r + 2) * vec);
-            break;
+            launch_dot_columns(ctx, op->U, op->ldu, op->r, v_dev, nullptr, nullptr, nullptr, n, ctx->s.coef_h, op->lam,
+                               op->r, 1.0, nullptr, stop, FOSI_PROF_HVP_PROJECT, (op->r + 1) * vec);
+            const int extra = (want_local && vprev != nullptr) ? 1 : 0;
+            const int slots = launch_combine_columns(ctx, op->U, op->ldu, op->r, ctx->s.coef_h, nullptr, 0.0, v_dev,
+                                                     (double)op->shift, nullptr, 0.0, vprev, want_local, 1.0, hv_dev, n,
+                                                     false, stop, FOSI_PROF_HVP_EXPAND, (op->r + 2 + extra) * vec);
+            if (want_local) launch_reduce_local(ctx, slots, stop);
+            return launch_status(ctx, "hvp_apply");
         }
         case fosi_hvp::DIAG: {
-            ProfScope p(ctx, FOSI_PROF_HVP_OTHER, 3 * kVec * (double)n);
+            ProfScope p(ctx, FOSI_PROF_HVP_OTHER, 3 * vec);
             launch_diag_apply(ctx, op->d, v_dev, hv_dev, n);
             break;
         }
@@ -285,7 +294,25 @@ fosi_status hvp_apply(fosi_hvp* op, const float* v_dev, float* hv_dev) {
             break;
         }
     }
+    if (want_local) {
+        // vprev, when given, is the column just before v in the caller's matrix
+        const int nc = vprev != nullptr ? 2 : 1;
+        const float* base = vprev != nullptr ? vprev : v_dev;
+        const int64_t ld = vprev != nullptr ? (int64_t)(v_dev - vprev) : 0;
+        launch_dot_columns(ctx, base, ld, nc, hv_dev, nullptr, nullptr, nullptr, n, ctx->s.coef_a, nullptr, 0, 1.0,
+                           nullptr, stop, FOSI_PROF_REORTH_DOT, (nc + 1) * vec);
+        launch_local_from_coef(ctx, ctx->s.coef_a, nc, stop);
+    }
     return launch_status(ctx, "hvp_apply");
+}
+
+fosi_status hvp_apply(fosi_hvp* op, const float* v_dev, float* hv_dev) {
+    if (op == nullptr) return FOSI_ERR_INVALID_ARG;
+    fosi_ctx* ctx = op->ctx;
+    if (fosi_status s = check_vector(ctx, "v_dev", v_dev)) return s;
+    if (fosi_status s = check_vector(ctx, "hv_dev", hv_dev)) return s;
+    if (v_dev == hv_dev) return fail(ctx, FOSI_ERR_INVALID_ARG, "v_dev and hv_dev must be distinct");
+    return apply_operator(op, v_dev, hv_dev, nullptr, false);
 }
 
 fosi_status hvp_destroy(fosi_hvp* op) {
@@ -326,31 +353,42 @@ fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q
     if (fosi_status s = check_hip(ctx, hipMemsetAsync(flags, 0, 8 * sizeof(int), ctx->stream), "clear flags")) return s;
 
     // first column: the caller's vector, normalised in place
-    launch_dot_columns(ctx, nullptr, 0, 0, Q_dev, nullptr, n, ctx->s.coef_a, nullptr, 0, 1.0, nullptr, -1, 0.0);
+    launch_dot_columns(ctx, nullptr, 0, 0, Q_dev, nullptr, nullptr, nullptr, n, ctx->s.coef_a, nullptr, 0, 1.0, nullptr,
+                       nullptr, -1, 0.0);
     launch_inv_sqrt(ctx, ctx->s.coef_a, ctx->s.scal + 1);
     launch_scale(ctx, Q_dev, ctx->s.scal + 1, n, nullptr);
 
     for (int i = 0; i < m; ++i) {
         const float* q = Q_dev + (int64_t)i * ldq;
         float* h = Q_dev + (int64_t)(i + 1) * ldq;     // the new direction is built in place in the next column
-        if (fosi_status s = hvp_apply(op, q, h)) return s;
         const int ncols = i + 1;
-        double* coef[2] = {ctx->s.coef_a, ctx->s.coef_b};
         int norm_slots = 0;
-        int pass_cols[2] = {0, 0};
-        for (int p = 0; p < passes; ++p) {
-            // Gram-Schmidt against the columns built so far (the local first pass: only the last two); the
-            // coefficient along q_i, the last column of either range, is (part of) the diagonal entry
-            const int first = (mode == FOSI_REORTH_LOCAL_FULL && p == 0 && ncols > 2) ? ncols - 2 : 0;
-            const int pc = ncols - first;
-            const float* Qp = Q_dev + (int64_t)first * ldq;
-            launch_dot_columns(ctx, Qp, ldq, pc, h, nullptr, n, coef[p], nullptr, 0, 1.0, flags,
-                               FOSI_PROF_REORTH_DOT, (pc + 1) * vec);
-            norm_slots = launch_combine_columns(ctx, Qp, ldq, pc, coef[p], h, 1.0, nullptr, 0.0, nullptr, 0.0,
-                                                -1.0, h, n, true, flags, FOSI_PROF_REORTH_SUB, (pc + 2) * vec);
-            pass_cols[p] = pc;
+        if (mode == FOSI_REORTH_LOCAL_FULL) {
+            // local pass: alpha~ = h . q_i and beta~ = h . q_{i-1} come with the operator; h itself is left
+            // untouched and the full pass works on h - alpha~ q_i - beta~ q_{i-1}, formed on the fly in fp64
+            const float* qprev = i > 0 ? q - ldq : nullptr;
+            if (fosi_status s = apply_operator(op, q, h, qprev, true)) return s;
+            launch_dot_columns(ctx, Q_dev, ldq, ncols, h, q, qprev, ctx->s.scal + 4, n, ctx->s.coef_b, nullptr, 0, 1.0,
+                               ctx->s.loc, flags, FOSI_PROF_REORTH_DOT, (ncols + 1 + (qprev != nullptr ? 2 : 1)) * vec);
+            // coef_b now holds the total coefficient per column (local + full); one subtraction removes both
+            norm_slots = launch_combine_columns(ctx, Q_dev, ldq, ncols, ctx->s.coef_b, h, 1.0, nullptr, 0.0, nullptr,
+                                                0.0, nullptr, false, -1.0, h, n, true, flags, FOSI_PROF_REORTH_SUB,
+                                                (ncols + 2) * vec);
+            launch_lanczos_finalize(ctx, i, norm_slots, ctx->s.coef_b, ncols, nullptr, 0, ctx->s.loc + 2, tol);
+        } else {
+            if (fosi_status s = apply_operator(op, q, h, nullptr, false)) return s;
+            double* coef[2] = {ctx->s.coef_a, ctx->s.coef_b};
+            for (int p = 0; p < passes; ++p) {
+                // Gram-Schmidt against every column built so far; the coefficient along q_i is the diagonal entry
+                launch_dot_columns(ctx, Q_dev, ldq, ncols, h, nullptr, nullptr, nullptr, n, coef[p], nullptr, 0, 1.0,
+                                   nullptr, flags, FOSI_PROF_REORTH_DOT, (ncols + 1) * vec);
+                norm_slots = launch_combine_columns(ctx, Q_dev, ldq, ncols, coef[p], h, 1.0, nullptr, 0.0, nullptr, 0.0,
+                                                    nullptr, false, -1.0, h, n, true, flags, FOSI_PROF_REORTH_SUB,
+                                                    (ncols + 2) * vec);
+            }
+            launch_lanczos_finalize(ctx, i, norm_slots, ctx->s.coef_a, ncols, passes == 2 ? ctx->s.coef_b : nullptr,
+                                    passes == 2 ? ncols : 0, nullptr, tol);
         }
-        launch_lanczos_finalize(ctx, i, norm_slots, pass_cols[0], passes == 2 ? pass_cols[1] : 0, tol);
         {
             ProfScope ps(ctx, FOSI_PROF_NORMALISE, 2 * vec);
             launch_scale(ctx, h, ctx->s.scal, n, flags);
@@ -464,17 +502,19 @@ fosi_status fosi_step(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int
     const int extra = pi_dev != nullptr ? 1 : 0;
     ProfScope ps(ctx, FOSI_PROF_STEP, r_v > 0 ? (4.0 * r_v + 8 + 2 * extra) * vec : (6.0 + extra) * vec);
     if (r_v > 0)   // c = V^T (g + pi)
-        launch_dot_columns(ctx, V_dev, ldv, r_v, g_dev, pi_dev, n, ctx->s.coef_a, nullptr, 0, 1.0, nullptr, -1, 0.0);
+        launch_dot_columns(ctx, V_dev, ldv, r_v, g_dev, pi_dev, nullptr, nullptr, n, ctx->s.coef_a, nullptr, 0, 1.0,
+                           nullptr, nullptr, -1, 0.0);
     // b <- momentum b + (g + pi) - V c
-    launch_combine_columns(ctx, V_dev, ldv, r_v, ctx->s.coef_a, mom_dev, mu, g_dev, 1.0, pi_dev, 1.0, -1.0, mom_dev, n,
-                           false, nullptr, -1, 0.0);
+    launch_combine_columns(ctx, V_dev, ldv, r_v, ctx->s.coef_a, mom_dev, mu, g_dev, 1.0, pi_dev, 1.0, nullptr, false,
+                           -1.0, mom_dev, n, false, nullptr, -1, 0.0);
     if (r_v > 0) {   // e = V^T b ;  d = newton . c - lr e
-        launch_dot_columns(ctx, V_dev, ldv, r_v, mom_dev, nullptr, n, ctx->s.coef_b, nullptr, 0, 1.0, nullptr, -1, 0.0);
+        launch_dot_columns(ctx, V_dev, ldv, r_v, mom_dev, nullptr, nullptr, nullptr, n, ctx->s.coef_b, nullptr, 0, 1.0,
+                           nullptr, nullptr, -1, 0.0);
         launch_step_coefficients(ctx, r_v, lr);
     }
     // w <- w - lr b - V d   ( = w + Delta_1 + Delta_2 )
-    launch_combine_columns(ctx, V_dev, ldv, r_v, ctx->s.coef_c, w_dev, 1.0, mom_dev, -lr, nullptr, 0.0, -1.0, w_dev, n,
-                           false, nullptr, -1, 0.0);
+    launch_combine_columns(ctx, V_dev, ldv, r_v, ctx->s.coef_c, w_dev, 1.0, mom_dev, -lr, nullptr, 0.0, nullptr, false,
+                           -1.0, w_dev, n, false, nullptr, -1, 0.0);
     return launch_status(ctx, "fosi_step");
 }
 

@@ -24,22 +24,23 @@ struct ProfRecord {
 };
 
 struct Tunables {
-    int dot_cols_per_block;   // JB: columns a block of the transposed product accumulates (8, 16 or 32)
-    int dot_target_blocks;    // total resident blocks aimed at by the transposed product
+    int dot_target_blocks;    // workgroups launched by the transposed product (it grid-strides over rows)
     int comb_rows_per_thread; // RPT: float4 row groups per thread in the column-combination kernel
     int comb_cols_unroll;     // CU: columns loaded together in that kernel
+    int xcd_partition;        // give each XCD a contiguous eighth of the rows (1) or interleave rows over all XCDs (0)
     int comb_max_blocks;      // cap on that kernel's grid (it grid-strides over row tiles); 0 = no cap
 };
 
 // Device scratch layout (one allocation per context).
 struct Scratch {
     double* partials;      // kMaxDotSlots x (kMaxCols + 1)
-    double* norm_partials; // kMaxNormSlots
+    double* norm_partials; // 3 * kMaxNormSlots
     double* coef_a;        // kMaxCols + 1  (first Gram-Schmidt pass / operator coefficients)
     double* coef_b;        // kMaxCols + 1  (second pass)
     double* coef_c;        // kMaxCols + 1  (update-rule coefficients)
     double* coef_h;        // kMaxCols + 1  (planted operator)
-    double* scal;          // 8 scalars: [0] = 1/beta, [1] = 1/||v||
+    double* scal;          // 8 scalars: [0] = 1/beta, [1] = 1/||v||, [2..3] = 1, [4..5] = -alpha~, -beta~
+    double* loc;           // 8 scalars: alpha~, beta~, ||H q||^2 of the local (two-column) pass
     double* alpha;         // kMaxCols
     double* beta;          // kMaxCols
     double* hnorm;         // kMaxCols
@@ -105,21 +106,29 @@ struct ProfScope {
 
 // coef[j] = (sum_rows A[row,j] * (x[row] + x2[row])) * (scale ? scale[j] : 1) * gscale  for j < ncols,
 // coef[ncols] = sum_rows (x + x2)^2.   x2 and scale may be null.  stop may be null.
+// The vector is x, or x + xs[0] x2 (+ xs[1] x3) with xs in device memory (xs == null: scales 1).
+// add_last2 (device, may be null): values added to the last and the last-but-one coefficient.
 void launch_dot_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const float* x,
-                        const float* x2, int64_t n, double* coef, const float* scale, int nscale,
-                        double gscale, const int* stop, int prof_cls, double prof_bytes);
+                        const float* x2, const float* x3, const double* xs, int64_t n, double* coef,
+                        const float* scale, int nscale, double gscale, const double* add_last2,
+                        const int* stop, int prof_cls, double prof_bytes);
 
 // out = a0*y + a1*x1 + a2*x2 + sa * A[:, :ncols] d   (null pointers drop their term; out may alias y).
 // With want_norm the per-block partial sums of out^2 are left in ctx->s.norm_partials; their count is
 // returned.  Only the main kernel of each launcher is bracketed by the profiling events (prof_cls < 0: none).
 int launch_combine_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const double* d,
                            const float* y, double a0, const float* x1, double a1, const float* x2,
-                           double a2, double sa, float* out, int64_t n, bool want_norm, const int* stop,
-                           int prof_cls, double prof_bytes);
+                           double a2, const float* x3, bool local_dots, double sa, float* out, int64_t n,
+                           bool want_norm, const int* stop, int prof_cls, double prof_bytes);
 
 // cols_a / cols_b: number of columns of the first / second Gram-Schmidt pass (cols_b == 0: single pass);
 // in both the current Lanczos vector is the last column of the range.
-void launch_lanczos_finalize(fosi_ctx* ctx, int step, int norm_slots, int cols_a, int cols_b, double tol);
+void launch_lanczos_finalize(fosi_ctx* ctx, int step, int norm_slots, const double* coef_a, int cols_a,
+                             const double* coef_b, int cols_b, const double* hh, double tol);
+// local_dots variant of launch_combine_columns leaves {out^2, out.x1, out.x3} partials (3 per block);
+// this sums them into ctx->s.loc = {alpha~, beta~, ||h||^2} and ctx->s.scal[4..5] = {-alpha~, -beta~}.
+void launch_reduce_local(fosi_ctx* ctx, int nslots, const int* stop);
+void launch_local_from_coef(fosi_ctx* ctx, const double* coef, int nc, const int* stop);
 void launch_inv_sqrt(fosi_ctx* ctx, const double* in, double* out);
 void launch_scale(fosi_ctx* ctx, float* x, const double* factor, int64_t n, const int* stop);
 void launch_diag_apply(fosi_ctx* ctx, const float* d, const float* v, float* out, int64_t n);

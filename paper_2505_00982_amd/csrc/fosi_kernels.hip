@@ -52,86 +52,171 @@ __device__ __forceinline__ double block_sum(double v, double* lds4) {
 }
 
 // ---------------------------------------------------------------- dot_columns
-// grid = (row slots, column blocks).  Block (bx, by) accumulates columns
-// [by*JB, by*JB+JB) over the float4 row groups bx*256+tid, += gridDim.x*256, ...
-// and writes one partial per column to partials[bx*pstride + column].  Column
-// index `ncols` of the partial row receives the partial of sum(x^2) (from the
-// blocks with by == 0).
-template <int JB, bool HAS_X2>
+// Work is split per wavefront: a wave owns a "slot" of up to JB consecutive columns and sweeps
+// float4 row groups (64 lanes x 4 rows) with a grid stride, keeping one fp64 accumulator per
+// column.  The S (= 1, 2 or 4) waves of a block that own different slots walk the SAME rows, so
+// the vector x is fetched from HBM once and re-read from the CU's L1; the remaining 4/S waves of
+// the block take other rows.  A slot with fewer than JB columns is processed as 16 + 8 + 4 + 2 + 1
+// sub-blocks, so no column is ever loaded twice.  partials[rowslot * pstride + column] receives
+// the wave's sums, column index `ncols` the partial of sum(x^2) (from the waves of slot 0).
+// Loads the tile's float4 of NB consecutive columns.  `tile` points at the tile's first row in column
+// col0 and is the same for all lanes, `lane_off` (in floats) is the only per-lane part of the address:
+// the loads can then use a scalar base register pair plus one shared 32-bit offset register instead of
+// a 64-bit address per column.
+template <int NB>
+__device__ __forceinline__ void dot_load(const float* __restrict__ tile, int64_t lda, uint32_t lane_off, float4* a) {
+#pragma unroll
+    for (int j = 0; j < NB; ++j) a[j] = load_stream4(tile + (int64_t)j * lda + lane_off);
+}
+
+template <int NB>
+__device__ __forceinline__ void dot_fma(const float4* a, double d0, double d1, double d2, double d3, double* acc) {
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+        acc[j] = fma((double)a[j].x, d0, fma((double)a[j].y, d1, fma((double)a[j].z, d2, fma((double)a[j].w, d3, acc[j]))));
+}
+
+template <int NB>
+__device__ __forceinline__ void dot_tail_row(const float* __restrict__ A, int64_t lda, int col0, int64_t row, double dx,
+                                             double* acc) {
+#pragma unroll
+    for (int j = 0; j < NB; ++j) acc[j] = fma((double)A[(int64_t)(col0 + j) * lda + row], dx, acc[j]);
+}
+
+template <int NB>
+__device__ __forceinline__ void dot_emit(const double* acc, double* prow, int col0, int lane) {
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const double v = wave_sum(acc[j]);
+        if (lane == 0) prow[col0 + j] = v;
+    }
+}
+
+// The vector is x (NX == 1), x + xs[0] x2 (NX == 2) or x + xs[0] x2 + xs[1] x3 (NX == 3), formed in fp64
+// on the fly; xs points to device memory.
+template <int JB, int NX>
 __global__ __launch_bounds__(kThreads) void k_dot_columns(
     const float* __restrict__ A, int64_t lda, int ncols, const float* __restrict__ x,
-    const float* __restrict__ x2, int64_t n, double* __restrict__ partials, int pstride,
-    const int* __restrict__ stop) {
+    const float* __restrict__ x2, const float* __restrict__ x3, const double* __restrict__ xs, int64_t n,
+    double* __restrict__ partials, int pstride, int S, int xcd_part, const int* __restrict__ stop) {
+    static_assert(JB == 32, "sub-block decomposition below is written for 32-column slots");
     if (stop != nullptr && *stop != 0) return;
-    __shared__ double red[4][JB + 1];
-    const int tid = threadIdx.x;
-    const int j0 = blockIdx.y * JB;
-    const int nc = min(JB, ncols - j0);          // >= 1 by construction of the grid (or 0 when ncols == 0)
-    const int last = nc > 0 ? nc - 1 : 0;
+    const int lane = threadIdx.x & 63;
+    // the wave index is the same for all 64 lanes: tell the compiler, so that the slot, its column bases and
+    // the sub-block tests below live in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int slot = blockIdx.y * S + (wave % S);       // column slot of this wave
+    const int rowlane = wave / S;                       // which of the block's 4/S row groups
+    const int rows_per_block = 4 / S;
+    const int j0 = slot * JB;
+    const int nc = max(0, min(JB, ncols - j0));
+    const bool do_xx = (slot == 0);
+    if (nc == 0 && !do_xx) return;
+
     double acc[JB];
 #pragma unroll
     for (int j = 0; j < JB; ++j) acc[j] = 0.0;
     double xx = 0.0;
+    // sub-block layout of a ragged slot: 16 columns in acc[0..15], then 8 in acc[16..23], 4, 2, 1
+    const int o16 = j0, o8 = o16 + (nc & 16), o4 = o8 + (nc & 8), o2 = o4 + (nc & 4), o1 = o2 + (nc & 2);
 
     const int64_t n4 = n >> 2;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    const float4* __restrict__ x4 = reinterpret_cast<const float4*>(x);
-    const float4* __restrict__ x24 = reinterpret_cast<const float4*>(x2);
-    for (int64_t r4 = (int64_t)blockIdx.x * kThreads + tid; r4 < n4; r4 += stride) {
-        float4 xv = x4[r4];
-        if (HAS_X2) {
-            const float4 t = x24[r4];
-            xv.x += t.x; xv.y += t.y; xv.z += t.z; xv.w += t.w;
+    // Row ranges.  Workgroups are handed to the 8 XCDs round-robin, so with xcd_part every XCD is given
+    // one contiguous eighth of the rows: its address-translation cache then only ever sees an eighth of
+    // the pages of the matrix.  (Correctness does not depend on how the hardware places workgroups.)
+    int64_t t_begin, r_end, stride;          // all uniform across the wave (float4 units)
+    if (xcd_part) {
+        const int nx = gridDim.x >> 3;                                     // gridDim.x is a multiple of 8
+        const int64_t chunk = ((n4 + 7) / 8 + 63) / 64 * 64;
+        const int part = blockIdx.x & 7;
+        t_begin = part * chunk + ((int64_t)(blockIdx.x >> 3) * rows_per_block + rowlane) * 64;
+        r_end = min(n4, (part + 1) * chunk);
+        stride = (int64_t)nx * rows_per_block * 64;
+    } else {
+        t_begin = ((int64_t)blockIdx.x * rows_per_block + rowlane) * 64;
+        r_end = n4;
+        stride = (int64_t)gridDim.x * rows_per_block * 64;
+    }
+    const double s2 = NX >= 2 ? xs[0] : 0.0, s3 = NX >= 3 ? xs[1] : 0.0;
+    for (int64_t t = t_begin; t < r_end; t += stride) {
+        // lanes past the end of a ragged last tile re-read its last row group and contribute zeros
+        const int64_t rem = r_end - t;
+        const bool ok = lane < rem;
+        const uint32_t lane_off = (uint32_t)(ok ? lane : (int)rem - 1) << 2;
+        const float* xt = x + (t << 2);
+        const float4 xv = *reinterpret_cast<const float4*>(xt + lane_off);
+        double d0 = xv.x, d1 = xv.y, d2 = xv.z, d3 = xv.w;
+        if (NX >= 2) {
+            const float4 u = *reinterpret_cast<const float4*>(x2 + (t << 2) + lane_off);
+            d0 = fma(s2, (double)u.x, d0); d1 = fma(s2, (double)u.y, d1);
+            d2 = fma(s2, (double)u.z, d2); d3 = fma(s2, (double)u.w, d3);
         }
-        const double d0 = xv.x, d1 = xv.y, d2 = xv.z, d3 = xv.w;
-        xx = fma(d0, d0, fma(d1, d1, fma(d2, d2, fma(d3, d3, xx))));
-        if (nc > 0) {
-            float4 a[JB];
-#pragma unroll
-            for (int j = 0; j < JB; ++j) {
-                // columns past the end of a ragged last block re-read its last valid column
-                const int col = j0 + (j < nc ? j : last);
-                a[j] = load_stream4(A + (int64_t)col * lda + (r4 << 2));
-            }
-#pragma unroll
-            for (int j = 0; j < JB; ++j)
-                acc[j] = fma((double)a[j].x, d0, fma((double)a[j].y, d1,
-                         fma((double)a[j].z, d2, fma((double)a[j].w, d3, acc[j]))));
+        if (NX >= 3) {
+            const float4 u = *reinterpret_cast<const float4*>(x3 + (t << 2) + lane_off);
+            d0 = fma(s3, (double)u.x, d0); d1 = fma(s3, (double)u.y, d1);
+            d2 = fma(s3, (double)u.z, d2); d3 = fma(s3, (double)u.w, d3);
+        }
+        if (!ok) d0 = d1 = d2 = d3 = 0.0;
+        if (do_xx) xx = fma(d0, d0, fma(d1, d1, fma(d2, d2, fma(d3, d3, xx))));
+        const float* At = A + (t << 2);
+        float4 a[JB];
+        if (nc == JB) {
+            dot_load<JB>(At + (int64_t)j0 * lda, lda, lane_off, a);
+            dot_fma<JB>(a, d0, d1, d2, d3, acc);
+        } else {
+            // ragged slot: issue every load first, then multiply, so the sub-blocks share one memory round trip
+            if (nc & 16) dot_load<16>(At + (int64_t)o16 * lda, lda, lane_off, a);
+            if (nc & 8) dot_load<8>(At + (int64_t)o8 * lda, lda, lane_off, a + 16);
+            if (nc & 4) dot_load<4>(At + (int64_t)o4 * lda, lda, lane_off, a + 24);
+            if (nc & 2) dot_load<2>(At + (int64_t)o2 * lda, lda, lane_off, a + 28);
+            if (nc & 1) dot_load<1>(At + (int64_t)o1 * lda, lda, lane_off, a + 30);
+            if (nc & 16) dot_fma<16>(a, d0, d1, d2, d3, acc);
+            if (nc & 8) dot_fma<8>(a + 16, d0, d1, d2, d3, acc + 16);
+            if (nc & 4) dot_fma<4>(a + 24, d0, d1, d2, d3, acc + 24);
+            if (nc & 2) dot_fma<2>(a + 28, d0, d1, d2, d3, acc + 28);
+            if (nc & 1) dot_fma<1>(a + 30, d0, d1, d2, d3, acc + 30);
         }
     }
-    // the last (n mod 4) rows: one scalar row per thread of block row 0
-    const int64_t tail_row = (n4 << 2) + tid;
-    if (blockIdx.x == 0 && tid < 3 && tail_row < n) {
-        float xs = x[tail_row];
-        if (HAS_X2) xs += x2[tail_row];
-        const double dx = xs;
-        xx = fma(dx, dx, xx);
-#pragma unroll
-        for (int j = 0; j < JB; ++j)
-            if (j < nc) acc[j] = fma((double)A[(int64_t)(j0 + j) * lda + tail_row], dx, acc[j]);
+    // the last (n mod 4) rows: one scalar row per lane of the first row group
+    const int64_t tail_row = (n4 << 2) + lane;
+    if (blockIdx.x == 0 && rowlane == 0 && lane < 3 && tail_row < n) {
+        double dx = x[tail_row];
+        if (NX >= 2) dx = fma(s2, (double)x2[tail_row], dx);
+        if (NX >= 3) dx = fma(s3, (double)x3[tail_row], dx);
+        if (do_xx) xx = fma(dx, dx, xx);
+        if (nc == JB) {
+            dot_tail_row<JB>(A, lda, j0, tail_row, dx, acc);
+        } else {
+            if (nc & 16) dot_tail_row<16>(A, lda, o16, tail_row, dx, acc);
+            if (nc & 8) dot_tail_row<8>(A, lda, o8, tail_row, dx, acc + 16);
+            if (nc & 4) dot_tail_row<4>(A, lda, o4, tail_row, dx, acc + 24);
+            if (nc & 2) dot_tail_row<2>(A, lda, o2, tail_row, dx, acc + 28);
+            if (nc & 1) dot_tail_row<1>(A, lda, o1, tail_row, dx, acc + 30);
+        }
     }
 
-    const int lane = tid & 63, wave = tid >> 6;
-#pragma unroll
-    for (int j = 0; j < JB; ++j) {
-        const double v = wave_sum(acc[j]);
-        if (lane == 0) red[wave][j] = v;
+    double* prow = partials + ((int64_t)blockIdx.x * rows_per_block + rowlane) * pstride;
+    if (nc == JB) {
+        dot_emit<JB>(acc, prow, j0, lane);
+    } else {
+        if (nc & 16) dot_emit<16>(acc, prow, o16, lane);
+        if (nc & 8) dot_emit<8>(acc + 16, prow, o8, lane);
+        if (nc & 4) dot_emit<4>(acc + 24, prow, o4, lane);
+        if (nc & 2) dot_emit<2>(acc + 28, prow, o2, lane);
+        if (nc & 1) dot_emit<1>(acc + 30, prow, o1, lane);
     }
-    {
+    if (do_xx) {
         const double v = wave_sum(xx);
-        if (lane == 0) red[wave][JB] = v;
+        if (lane == 0) prow[ncols] = v;
     }
-    __syncthreads();
-    double* prow = partials + (int64_t)blockIdx.x * pstride;
-    if (tid < nc) prow[j0 + tid] = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
-    if (tid == JB && blockIdx.y == 0) prow[ncols] = red[0][JB] + red[1][JB] + red[2][JB] + red[3][JB];
 }
 
 // Second stage: one wavefront per output column sums the row-slot partials in
 // a fixed order and applies the per-column scale.
 __global__ __launch_bounds__(64) void k_reduce_columns(
     const double* __restrict__ partials, int nslots, int pstride, double* __restrict__ out,
-    const float* __restrict__ scale, int nscale, double gscale, int ncols, const int* __restrict__ stop) {
+    const float* __restrict__ scale, int nscale, double gscale, int ncols, const double* __restrict__ add_last2,
+    const int* __restrict__ stop) {
     if (stop != nullptr && *stop != 0) return;
     const int j = blockIdx.x;
     double s = 0.0;
@@ -141,6 +226,10 @@ __global__ __launch_bounds__(64) void k_reduce_columns(
         if (j < ncols) {
             s *= gscale;
             if (scale != nullptr && j < nscale) s *= (double)scale[j];
+            if (add_last2 != nullptr) {          // coefficients already removed along the last two columns
+                if (j == ncols - 1) s += add_last2[0];
+                if (j == ncols - 2) s += add_last2[1];
+            }
         }
         out[j] = s;   // j == ncols: the plain sum of squares
     }
@@ -154,19 +243,31 @@ __global__ __launch_bounds__(64) void k_reduce_columns(
 // touched in one burst (a workgroup that hops across all columns for every 4 KiB thrashes the
 // address-translation caches).  d is read through uniform (scalar) loads.  With NORM the block's
 // sum of out^2 (of the stored, rounded values) goes to norm_partials[blockIdx.x].
-template <bool HAS_Y, bool HAS_X1, bool HAS_X2, bool NORM, int RPT, int CU>
+// With LDOT (used by the planted operator inside a Lanczos run) the block also emits the partial sums
+// of out.x1 and out.x3 (x3 may be null): norm_partials[3*block + {0,1,2}] = {out^2, out.x1, out.x3}.
+template <bool HAS_Y, bool HAS_X1, bool HAS_X2, bool NORM, bool LDOT, int RPT, int CU>
 __global__ __launch_bounds__(kThreads) void k_combine_columns(
     const float* __restrict__ A, int64_t lda, int ncols, const double* __restrict__ d, const float* y,
     double a0, const float* __restrict__ x1, double a1, const float* __restrict__ x2, double a2,
-    double sa, float* out, int64_t n, double* __restrict__ norm_partials, const int* __restrict__ stop) {
+    const float* __restrict__ x3, double sa, float* out, int64_t n, double* __restrict__ norm_partials,
+    int xcd_part, const int* __restrict__ stop) {
     if (stop != nullptr && *stop != 0) return;
     __shared__ double red[4];
     const int tid = threadIdx.x;
     const int64_t n4 = n >> 2;
     const int64_t tile = (int64_t)kThreads * RPT;
     const int64_t ntiles = (n4 + tile - 1) / tile;
-    double nrm = 0.0;
-    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    double nrm = 0.0, dot1 = 0.0, dot3 = 0.0;
+    // tile ranges: with xcd_part each XCD (workgroup index mod 8) owns one contiguous eighth of the tiles
+    int64_t t_begin = blockIdx.x, t_end = ntiles, t_step = gridDim.x;
+    if (xcd_part) {
+        const int64_t per = (ntiles + 7) / 8;
+        const int part = blockIdx.x & 7;
+        t_begin = part * per + (blockIdx.x >> 3);
+        t_end = min(ntiles, (part + 1) * per);
+        t_step = gridDim.x >> 3;
+    }
+    for (int64_t t = t_begin; t < t_end; t += t_step) {
         int64_t r4[RPT], rc[RPT];
 #pragma unroll
         for (int q = 0; q < RPT; ++q) {
@@ -215,10 +316,11 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
                 o0 = fma(a0, (double)v.x, o0); o1 = fma(a0, (double)v.y, o1);
                 o2 = fma(a0, (double)v.z, o2); o3 = fma(a0, (double)v.w, o3);
             }
+            float4 v1 = make_float4(0.f, 0.f, 0.f, 0.f);
             if (HAS_X1) {
-                const float4 v = reinterpret_cast<const float4*>(x1)[r4[q]];
-                o0 = fma(a1, (double)v.x, o0); o1 = fma(a1, (double)v.y, o1);
-                o2 = fma(a1, (double)v.z, o2); o3 = fma(a1, (double)v.w, o3);
+                v1 = reinterpret_cast<const float4*>(x1)[r4[q]];
+                o0 = fma(a1, (double)v1.x, o0); o1 = fma(a1, (double)v1.y, o1);
+                o2 = fma(a1, (double)v1.z, o2); o3 = fma(a1, (double)v1.w, o3);
             }
             if (HAS_X2) {
                 const float4 v = reinterpret_cast<const float4*>(x2)[r4[q]];
@@ -227,8 +329,17 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
             }
             const float4 o = make_float4((float)o0, (float)o1, (float)o2, (float)o3);
             store_stream4(out + (r4[q] << 2), o);
-            if (NORM) nrm = fma((double)o.x, (double)o.x, fma((double)o.y, (double)o.y,
-                            fma((double)o.z, (double)o.z, fma((double)o.w, (double)o.w, nrm))));
+            if (NORM || LDOT) nrm = fma((double)o.x, (double)o.x, fma((double)o.y, (double)o.y,
+                                    fma((double)o.z, (double)o.z, fma((double)o.w, (double)o.w, nrm))));
+            if (LDOT) {
+                dot1 = fma((double)o.x, (double)v1.x, fma((double)o.y, (double)v1.y,
+                       fma((double)o.z, (double)v1.z, fma((double)o.w, (double)v1.w, dot1))));
+                if (x3 != nullptr) {
+                    const float4 v3 = reinterpret_cast<const float4*>(x3)[r4[q]];
+                    dot3 = fma((double)o.x, (double)v3.x, fma((double)o.y, (double)v3.y,
+                           fma((double)o.z, (double)v3.z, fma((double)o.w, (double)v3.w, dot3))));
+                }
+            }
         }
     }
     const int64_t tail_row = (n4 << 2) + tid;
@@ -241,9 +352,20 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
         if (HAS_X2) o = fma(a2, (double)x2[tail_row], o);
         const float of = (float)o;
         out[tail_row] = of;
-        if (NORM) nrm = fma((double)of, (double)of, nrm);
+        if (NORM || LDOT) nrm = fma((double)of, (double)of, nrm);
+        if (LDOT) {
+            dot1 = fma((double)of, (double)x1[tail_row], dot1);
+            if (x3 != nullptr) dot3 = fma((double)of, (double)x3[tail_row], dot3);
+        }
     }
-    if (NORM) {
+    if (LDOT) {
+        const double b0 = block_sum(nrm, red), b1 = block_sum(dot1, red), b3 = block_sum(dot3, red);
+        if (tid == 0) {
+            norm_partials[3 * (int64_t)blockIdx.x] = b0;
+            norm_partials[3 * (int64_t)blockIdx.x + 1] = b1;
+            norm_partials[3 * (int64_t)blockIdx.x + 2] = b3;
+        }
+    } else if (NORM) {
         const double b = block_sum(nrm, red);
         if (tid == 0) norm_partials[blockIdx.x] = b;
     }
@@ -254,7 +376,8 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
 // breakdown / non-finite detection, reciprocal for the normalisation.
 __global__ __launch_bounds__(kThreads) void k_lanczos_finalize(
     const double* __restrict__ norm_partials, int norm_slots, const double* __restrict__ coef_a,
-    const double* __restrict__ coef_b, int cols_a, int cols_b, int step, double tol, double* __restrict__ alpha,
+    const double* __restrict__ coef_b, int cols_a, int cols_b, const double* __restrict__ hh_ptr, int step,
+    double tol, double* __restrict__ alpha,
     double* __restrict__ beta, double* __restrict__ hnorm, double* __restrict__ scal, int* flags) {
     if (flags[0] != 0) return;
     __shared__ double red[4];
@@ -265,7 +388,8 @@ __global__ __launch_bounds__(kThreads) void k_lanczos_finalize(
         double a = coef_a[cols_a - 1];             // coefficient along the current vector, first pass
         if (cols_b > 0) a += coef_b[cols_b - 1];   // ... and second pass
         const double b = sqrt(s);
-        const double hn = sqrt(coef_a[cols_a]);    // ||H q_step|| before orthogonalisation
+        // ||H q_step||^2 before orthogonalisation: by-product of the first pass, or handed in
+        const double hn = sqrt(hh_ptr != nullptr ? hh_ptr[0] : coef_a[cols_a]);
         alpha[step] = a;
         beta[step] = b;
         hnorm[step] = hn;
@@ -274,6 +398,39 @@ __global__ __launch_bounds__(kThreads) void k_lanczos_finalize(
         if (!finite) flags[0] = 2;
         else if (!(b > tol * hn)) flags[0] = 1;
         scal[0] = 1.0 / b;
+    }
+}
+
+// Sums the {out^2, out.x1, out.x3} partials of the operator's expand sweep: loc = {alpha~, beta~, ||h||^2},
+// neg = {-alpha~, -beta~} (the scales with which q_i and q_{i-1} enter the vector of the full pass).
+__global__ __launch_bounds__(kThreads) void k_reduce_local(const double* __restrict__ parts, int nslots,
+                                                           double* __restrict__ loc, double* __restrict__ neg,
+                                                           const int* __restrict__ stop) {
+    if (stop != nullptr && *stop != 0) return;
+    __shared__ double red[4];
+    double s0 = 0.0, s1 = 0.0, s3 = 0.0;
+    for (int i = threadIdx.x; i < nslots; i += kThreads) {
+        s0 += parts[3 * (int64_t)i];
+        s1 += parts[3 * (int64_t)i + 1];
+        s3 += parts[3 * (int64_t)i + 2];
+    }
+    s0 = block_sum(s0, red);
+    s1 = block_sum(s1, red);
+    s3 = block_sum(s3, red);
+    if (threadIdx.x == 0) {
+        loc[0] = s1; loc[1] = s3; loc[2] = s0;
+        neg[0] = -s1; neg[1] = -s3;
+    }
+}
+
+// Same outputs from a transposed product against [q_{i-1}, q_i] (nc == 2) or [q_i] (nc == 1).
+__global__ void k_local_from_coef(const double* __restrict__ coef, int nc, double* __restrict__ loc,
+                                  double* __restrict__ neg, const int* __restrict__ stop) {
+    if (stop != nullptr && *stop != 0) return;
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        const double a = coef[nc - 1], b = nc > 1 ? coef[0] : 0.0;
+        loc[0] = a; loc[1] = b; loc[2] = coef[nc];
+        neg[0] = -a; neg[1] = -b;
     }
 }
 
@@ -394,69 +551,83 @@ int elementwise_grid(int64_t work_items) {
     return (int)g;
 }
 
-template <int JB>
-void dot_columns_jb(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const float* x, const float* x2,
-                    int64_t n, double* coef, const float* scale, int nscale, double gscale, const int* stop,
-                    int prof_cls, double prof_bytes) {
-    const int ncb = ncols > 0 ? (ncols + JB - 1) / JB : 1;
+void dot_columns_launch(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const float* x, const float* x2,
+                        const float* x3, const double* xs, int64_t n, double* coef, const float* scale, int nscale,
+                        double gscale, const double* add_last2, const int* stop, int prof_cls, double prof_bytes) {
+    constexpr int JB = 32;
+    const int nslots = ncols > 0 ? (ncols + JB - 1) / JB : 1;
+    const int S = nslots >= 3 ? 4 : nslots;             // waves of a block that share the same rows
+    const int gy = (nslots + S - 1) / S;
+    const int rows_per_block = 4 / S;
     const int64_t n4 = n >> 2;
-    int64_t gx = (n4 + kThreads - 1) / kThreads;
-    int64_t cap = ctx->tun.dot_target_blocks / ncb;
-    cap = cap / 8 * 8;                       // keep a row slot's column blocks on one XCD
-    if (cap < 8) cap = 8;
-    if (cap > kMaxDotSlots) cap = kMaxDotSlots;
+    // row slots: enough blocks to fill the chip a few times over, within the partials buffer
+    int64_t gx = (n4 + 64 * rows_per_block - 1) / (64 * rows_per_block);
+    int64_t cap = ctx->tun.dot_target_blocks / gy;
+    if (cap * rows_per_block > kMaxDotSlots) cap = kMaxDotSlots / rows_per_block;
+    if (cap < 1) cap = 1;
     if (gx > cap) gx = cap;
     if (gx < 1) gx = 1;
+    const int xcd_part = (ctx->tun.xcd_partition && gx >= 16) ? 1 : 0;
+    if (xcd_part) gx = gx / 8 * 8;
+    const int rowslots = (int)gx * rows_per_block;
     const int pstride = ncols + 1;
-    dim3 grid((unsigned)gx, (unsigned)ncb);
+    dim3 grid((unsigned)gx, (unsigned)gy);
     if (prof_cls >= 0) prof_begin(ctx, prof_cls, prof_bytes);
-    if (x2 != nullptr)
-        hipLaunchKernelGGL((k_dot_columns<JB, true>), grid, dim3(kThreads), 0, ctx->stream, A, lda, ncols, x, x2, n,
-                           ctx->s.partials, pstride, stop);
+    if (x2 != nullptr && xs == nullptr) xs = ctx->s.scal + 2;   // plain sum of the vectors: scales 1, 1
+    if (x3 != nullptr)
+        hipLaunchKernelGGL((k_dot_columns<JB, 3>), grid, dim3(kThreads), 0, ctx->stream, A, lda, ncols, x, x2, x3, xs, n,
+                           ctx->s.partials, pstride, S, xcd_part, stop);
+    else if (x2 != nullptr)
+        hipLaunchKernelGGL((k_dot_columns<JB, 2>), grid, dim3(kThreads), 0, ctx->stream, A, lda, ncols, x, x2, x3, xs, n,
+                           ctx->s.partials, pstride, S, xcd_part, stop);
     else
-        hipLaunchKernelGGL((k_dot_columns<JB, false>), grid, dim3(kThreads), 0, ctx->stream, A, lda, ncols, x, x2, n,
-                           ctx->s.partials, pstride, stop);
+        hipLaunchKernelGGL((k_dot_columns<JB, 1>), grid, dim3(kThreads), 0, ctx->stream, A, lda, ncols, x, x2, x3, xs, n,
+                           ctx->s.partials, pstride, S, xcd_part, stop);
     if (prof_cls >= 0) prof_end(ctx);
-    hipLaunchKernelGGL(k_reduce_columns, dim3(ncols + 1), dim3(64), 0, ctx->stream, ctx->s.partials, (int)gx, pstride,
-                       coef, scale, nscale, gscale, ncols, stop);
+    hipLaunchKernelGGL(k_reduce_columns, dim3(ncols + 1), dim3(64), 0, ctx->stream, ctx->s.partials, rowslots, pstride,
+                       coef, scale, nscale, gscale, ncols, add_last2, stop);
 }
 
 }  // namespace
 
 void launch_dot_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const float* x, const float* x2,
-                        int64_t n, double* coef, const float* scale, int nscale, double gscale, const int* stop,
-                        int prof_cls, double prof_bytes) {
-    switch (ctx->tun.dot_cols_per_block) {
-        case 8: dot_columns_jb<8>(ctx, A, lda, ncols, x, x2, n, coef, scale, nscale, gscale, stop, prof_cls, prof_bytes); break;
-        case 32: dot_columns_jb<32>(ctx, A, lda, ncols, x, x2, n, coef, scale, nscale, gscale, stop, prof_cls, prof_bytes); break;
-        default: dot_columns_jb<16>(ctx, A, lda, ncols, x, x2, n, coef, scale, nscale, gscale, stop, prof_cls, prof_bytes); break;
-    }
+                        const float* x3, const double* xs, int64_t n, double* coef, const float* scale, int nscale,
+                        double gscale, const double* add_last2, const int* stop, int prof_cls, double prof_bytes) {
+    dot_columns_launch(ctx, A, lda, ncols, x, x2, x3, xs, n, coef, scale, nscale, gscale, add_last2, stop, prof_cls,
+                       prof_bytes);
 }
 
 namespace {
 
 template <int RPT, int CU>
 int combine_columns_cfg(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const double* d, const float* y,
-                        double a0, const float* x1, double a1, const float* x2, double a2, double sa, float* out,
-                        int64_t n, bool want_norm, const int* stop, int prof_cls, double prof_bytes) {
+                        double a0, const float* x1, double a1, const float* x2, double a2, const float* x3,
+                        bool local_dots, double sa, float* out, int64_t n, bool want_norm, const int* stop,
+                        int prof_cls, double prof_bytes) {
     const int64_t n4 = n >> 2;
     const int64_t tile = (int64_t)kThreads * RPT;
     int64_t g = (n4 + tile - 1) / tile;
     if (g < 1) g = 1;
     if (g > kMaxNormSlots) g = kMaxNormSlots;
     if (ctx->tun.comb_max_blocks > 0 && g > ctx->tun.comb_max_blocks) g = ctx->tun.comb_max_blocks;
+    const int xcd_part = (ctx->tun.xcd_partition && g >= 16) ? 1 : 0;
+    if (xcd_part) {
+        g = (g + 7) / 8 * 8;
+        if (g > kMaxNormSlots) g = kMaxNormSlots;
+    }
     const int grid = (int)g;
     if (prof_cls >= 0) prof_begin(ctx, prof_cls, prof_bytes);
-#define FOSI_COMBINE(Y, X1, X2, NRM)                                                                              \
-    hipLaunchKernelGGL((k_combine_columns<Y, X1, X2, NRM, RPT, CU>), dim3(grid), dim3(kThreads), 0, ctx->stream, A, \
-                       lda, ncols, d, y, a0, x1, a1, x2, a2, sa, out, n, ctx->s.norm_partials, stop)
+#define FOSI_COMBINE(Y, X1, X2, NRM, LD)                                                                         \
+    hipLaunchKernelGGL((k_combine_columns<Y, X1, X2, NRM, LD, RPT, CU>), dim3(grid), dim3(kThreads), 0, ctx->stream, \
+                       A, lda, ncols, d, y, a0, x1, a1, x2, a2, x3, sa, out, n, ctx->s.norm_partials, xcd_part, stop)
     const bool hy = y != nullptr, h1 = x1 != nullptr, h2 = x2 != nullptr;
-    if (!hy && h1 && !h2 && !want_norm) FOSI_COMBINE(false, true, false, false);        // operator expand
-    else if (hy && !h1 && !h2 && want_norm) FOSI_COMBINE(true, false, false, true);     // Gram-Schmidt subtract
-    else if (hy && h1 && !h2 && !want_norm) FOSI_COMBINE(true, true, false, false);     // momentum / apply
-    else if (hy && h1 && h2 && !want_norm) FOSI_COMBINE(true, true, true, false);       // momentum with dual
-    else if (hy && !h1 && !h2 && !want_norm) FOSI_COMBINE(true, false, false, false);
-    else FOSI_COMBINE(true, true, true, true);  // not reached by the library; kept total
+    if (!hy && h1 && !h2 && !want_norm && local_dots) FOSI_COMBINE(false, true, false, false, true);   // expand + local dots
+    else if (!hy && h1 && !h2 && !want_norm) FOSI_COMBINE(false, true, false, false, false);     // operator expand
+    else if (hy && !h1 && !h2 && want_norm) FOSI_COMBINE(true, false, false, true, false);       // Gram-Schmidt subtract
+    else if (hy && h1 && !h2 && !want_norm) FOSI_COMBINE(true, true, false, false, false);       // momentum / apply
+    else if (hy && h1 && h2 && !want_norm) FOSI_COMBINE(true, true, true, false, false);         // momentum with dual
+    else if (hy && !h1 && !h2 && !want_norm) FOSI_COMBINE(true, false, false, false, false);
+    else FOSI_COMBINE(true, true, true, true, false);  // not reached by the library; kept total
 #undef FOSI_COMBINE
     if (prof_cls >= 0) prof_end(ctx);
     return grid;
@@ -465,11 +636,12 @@ int combine_columns_cfg(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, c
 }  // namespace
 
 int launch_combine_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const double* d, const float* y,
-                           double a0, const float* x1, double a1, const float* x2, double a2, double sa, float* out,
-                           int64_t n, bool want_norm, const int* stop, int prof_cls, double prof_bytes) {
-#define FOSI_CFG(R, C)                                                                                         \
-    return combine_columns_cfg<R, C>(ctx, A, lda, ncols, d, y, a0, x1, a1, x2, a2, sa, out, n, want_norm, stop, \
-                                     prof_cls, prof_bytes)
+                           double a0, const float* x1, double a1, const float* x2, double a2, const float* x3,
+                           bool local_dots, double sa, float* out, int64_t n, bool want_norm, const int* stop,
+                           int prof_cls, double prof_bytes) {
+#define FOSI_CFG(R, C)                                                                                            \
+    return combine_columns_cfg<R, C>(ctx, A, lda, ncols, d, y, a0, x1, a1, x2, a2, x3, local_dots, sa, out, n,     \
+                                     want_norm, stop, prof_cls, prof_bytes)
     switch (ctx->tun.comb_rows_per_thread * 100 + ctx->tun.comb_cols_unroll) {
         case 108: FOSI_CFG(1, 8);
         case 116: FOSI_CFG(1, 16);
@@ -484,10 +656,20 @@ int launch_combine_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols
 #undef FOSI_CFG
 }
 
-void launch_lanczos_finalize(fosi_ctx* ctx, int step, int norm_slots, int cols_a, int cols_b, double tol) {
+void launch_lanczos_finalize(fosi_ctx* ctx, int step, int norm_slots, const double* coef_a, int cols_a,
+                             const double* coef_b, int cols_b, const double* hh, double tol) {
     hipLaunchKernelGGL(k_lanczos_finalize, dim3(1), dim3(kThreads), 0, ctx->stream, ctx->s.norm_partials, norm_slots,
-                       ctx->s.coef_a, ctx->s.coef_b, cols_a, cols_b, step, tol, ctx->s.alpha, ctx->s.beta,
-                       ctx->s.hnorm, ctx->s.scal, ctx->s.flags);
+                       coef_a, coef_b, cols_a, cols_b, hh, step, tol, ctx->s.alpha, ctx->s.beta, ctx->s.hnorm,
+                       ctx->s.scal, ctx->s.flags);
+}
+
+void launch_reduce_local(fosi_ctx* ctx, int nslots, const int* stop) {
+    hipLaunchKernelGGL(k_reduce_local, dim3(1), dim3(kThreads), 0, ctx->stream, ctx->s.norm_partials, nslots,
+                       ctx->s.loc, ctx->s.scal + 4, stop);
+}
+
+void launch_local_from_coef(fosi_ctx* ctx, const double* coef, int nc, const int* stop) {
+    hipLaunchKernelGGL(k_local_from_coef, dim3(1), dim3(64), 0, ctx->stream, coef, nc, ctx->s.loc, ctx->s.scal + 4, stop);
 }
 
 void launch_inv_sqrt(fosi_ctx* ctx, const double* in, double* out) {
