@@ -138,38 +138,52 @@ __global__ __launch_bounds__(kThreads) void k_dot_columns(
         stride = (int64_t)gridDim.x * rows_per_block * 64;
     }
     const double s2 = NX >= 2 ? xs[0] : 0.0, s3 = NX >= 3 ? xs[1] : 0.0;
-    for (int64_t t = t_begin; t < r_end; t += stride) {
+    // The vector's row group for the NEXT tile is requested while the current tile's columns are in
+    // flight, so each trip of the loop costs one memory round trip, not two.
+    float4 nx1 = make_float4(0.f, 0.f, 0.f, 0.f), nx2 = nx1, nx3 = nx1;
+    uint32_t n_off = 0;
+    bool n_ok = false;
+    auto fetch_vector = [&](int64_t t) {
         // lanes past the end of a ragged last tile re-read its last row group and contribute zeros
         const int64_t rem = r_end - t;
-        const bool ok = lane < rem;
-        const uint32_t lane_off = (uint32_t)(ok ? lane : (int)rem - 1) << 2;
-        const float* xt = x + (t << 2);
-        const float4 xv = *reinterpret_cast<const float4*>(xt + lane_off);
-        double d0 = xv.x, d1 = xv.y, d2 = xv.z, d3 = xv.w;
-        if (NX >= 2) {
-            const float4 u = *reinterpret_cast<const float4*>(x2 + (t << 2) + lane_off);
-            d0 = fma(s2, (double)u.x, d0); d1 = fma(s2, (double)u.y, d1);
-            d2 = fma(s2, (double)u.z, d2); d3 = fma(s2, (double)u.w, d3);
-        }
-        if (NX >= 3) {
-            const float4 u = *reinterpret_cast<const float4*>(x3 + (t << 2) + lane_off);
-            d0 = fma(s3, (double)u.x, d0); d1 = fma(s3, (double)u.y, d1);
-            d2 = fma(s3, (double)u.z, d2); d3 = fma(s3, (double)u.w, d3);
-        }
-        if (!ok) d0 = d1 = d2 = d3 = 0.0;
-        if (do_xx) xx = fma(d0, d0, fma(d1, d1, fma(d2, d2, fma(d3, d3, xx))));
+        n_ok = lane < rem;
+        n_off = (uint32_t)(n_ok ? lane : (int)rem - 1) << 2;
+        nx1 = *reinterpret_cast<const float4*>(x + (t << 2) + n_off);
+        if (NX >= 2) nx2 = *reinterpret_cast<const float4*>(x2 + (t << 2) + n_off);
+        if (NX >= 3) nx3 = *reinterpret_cast<const float4*>(x3 + (t << 2) + n_off);
+    };
+    if (t_begin < r_end) fetch_vector(t_begin);
+    for (int64_t t = t_begin; t < r_end; t += stride) {
+        const float4 xv = nx1, u2 = nx2, u3 = nx3;
+        const uint32_t lane_off = n_off;
+        const bool ok = n_ok;
         const float* At = A + (t << 2);
         float4 a[JB];
         if (nc == JB) {
             dot_load<JB>(At + (int64_t)j0 * lda, lda, lane_off, a);
-            dot_fma<JB>(a, d0, d1, d2, d3, acc);
         } else {
-            // ragged slot: issue every load first, then multiply, so the sub-blocks share one memory round trip
+            // ragged slot: every load is issued before the first multiply, so the sub-blocks share one round trip
             if (nc & 16) dot_load<16>(At + (int64_t)o16 * lda, lda, lane_off, a);
             if (nc & 8) dot_load<8>(At + (int64_t)o8 * lda, lda, lane_off, a + 16);
             if (nc & 4) dot_load<4>(At + (int64_t)o4 * lda, lda, lane_off, a + 24);
             if (nc & 2) dot_load<2>(At + (int64_t)o2 * lda, lda, lane_off, a + 28);
             if (nc & 1) dot_load<1>(At + (int64_t)o1 * lda, lda, lane_off, a + 30);
+        }
+        if (t + stride < r_end) fetch_vector(t + stride);
+        double d0 = xv.x, d1 = xv.y, d2 = xv.z, d3 = xv.w;
+        if (NX >= 2) {
+            d0 = fma(s2, (double)u2.x, d0); d1 = fma(s2, (double)u2.y, d1);
+            d2 = fma(s2, (double)u2.z, d2); d3 = fma(s2, (double)u2.w, d3);
+        }
+        if (NX >= 3) {
+            d0 = fma(s3, (double)u3.x, d0); d1 = fma(s3, (double)u3.y, d1);
+            d2 = fma(s3, (double)u3.z, d2); d3 = fma(s3, (double)u3.w, d3);
+        }
+        if (!ok) d0 = d1 = d2 = d3 = 0.0;
+        if (do_xx) xx = fma(d0, d0, fma(d1, d1, fma(d2, d2, fma(d3, d3, xx))));
+        if (nc == JB) {
+            dot_fma<JB>(a, d0, d1, d2, d3, acc);
+        } else {
             if (nc & 16) dot_fma<16>(a, d0, d1, d2, d3, acc);
             if (nc & 8) dot_fma<8>(a + 16, d0, d1, d2, d3, acc + 16);
             if (nc & 4) dot_fma<4>(a + 24, d0, d1, d2, d3, acc + 24);
