@@ -288,6 +288,15 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
             r4[q] = t * tile + (int64_t)q * kThreads + tid;
             rc[q] = r4[q] < n4 ? r4[q] : n4 - 1;      // ragged last tile: re-read a valid row, discard below
         }
+        // the vector operands of the epilogue are requested now, so that they travel while the columns stream
+        float4 py[RPT], p1[RPT], p2[RPT], p3[RPT];
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            if (HAS_Y) py[q] = reinterpret_cast<const float4*>(y)[rc[q]];
+            if (HAS_X1) p1[q] = reinterpret_cast<const float4*>(x1)[rc[q]];
+            if (HAS_X2) p2[q] = reinterpret_cast<const float4*>(x2)[rc[q]];
+            if (LDOT && x3 != nullptr) p3[q] = reinterpret_cast<const float4*>(x3)[rc[q]];
+        }
         double s[RPT][4];
 #pragma unroll
         for (int q = 0; q < RPT; ++q) s[q][0] = s[q][1] = s[q][2] = s[q][3] = 0.0;
@@ -326,18 +335,18 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
             if (r4[q] >= n4) continue;
             double o0 = sa * s[q][0], o1 = sa * s[q][1], o2 = sa * s[q][2], o3 = sa * s[q][3];
             if (HAS_Y) {
-                const float4 v = reinterpret_cast<const float4*>(y)[r4[q]];
+                const float4 v = py[q];
                 o0 = fma(a0, (double)v.x, o0); o1 = fma(a0, (double)v.y, o1);
                 o2 = fma(a0, (double)v.z, o2); o3 = fma(a0, (double)v.w, o3);
             }
             float4 v1 = make_float4(0.f, 0.f, 0.f, 0.f);
             if (HAS_X1) {
-                v1 = reinterpret_cast<const float4*>(x1)[r4[q]];
+                v1 = p1[q];
                 o0 = fma(a1, (double)v1.x, o0); o1 = fma(a1, (double)v1.y, o1);
                 o2 = fma(a1, (double)v1.z, o2); o3 = fma(a1, (double)v1.w, o3);
             }
             if (HAS_X2) {
-                const float4 v = reinterpret_cast<const float4*>(x2)[r4[q]];
+                const float4 v = p2[q];
                 o0 = fma(a2, (double)v.x, o0); o1 = fma(a2, (double)v.y, o1);
                 o2 = fma(a2, (double)v.z, o2); o3 = fma(a2, (double)v.w, o3);
             }
@@ -349,7 +358,7 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
                 dot1 = fma((double)o.x, (double)v1.x, fma((double)o.y, (double)v1.y,
                        fma((double)o.z, (double)v1.z, fma((double)o.w, (double)v1.w, dot1))));
                 if (x3 != nullptr) {
-                    const float4 v3 = reinterpret_cast<const float4*>(x3)[r4[q]];
+                    const float4 v3 = p3[q];
                     dot3 = fma((double)o.x, (double)v3.x, fma((double)o.y, (double)v3.y,
                            fma((double)o.z, (double)v3.z, fma((double)o.w, (double)v3.w, dot3))));
                 }
