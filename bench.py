@@ -84,6 +84,62 @@ def cpu_baseline(cfg_id: int, n_sample: int) -> dict:
             "seconds": round(dt, 2)}
 
 
+def bench_ggn(args, fo, torch, np) -> int:
+    """Workload 3: softmax-GGN operator (the MFMA path), Lanczos m = 60 + Ritz k = 20, no update."""
+    import workloads as wl
+    g = wl.ggn_workload()
+    ctx = fo.Context(0)
+    X, W = torch.from_numpy(g.X).cuda(), torch.from_numpy(g.W).cuda()
+    op = ctx.hvp_softmax_ggn(X, W)
+    ld = wl.padded_ld(g.n)
+    Q = fo.ColMajor(g.n, g.m + 1, ld)
+    V = fo.ColMajor(g.n, g.k, ld)
+    v1 = torch.from_numpy(g.v1).cuda()
+    state = {}
+
+    def one_step():
+        Q.col(0).copy_(v1)
+        alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, g.m, reorth_mode=REORTH_MODES[args.reorth])
+        fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, g.k, 0, V)
+        state["m_eff"] = m_eff
+
+    for _ in range(args.warmup):
+        one_step()
+    ctx.profile_enable(True)
+    ctx.profile_reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ctx.profile_enable(False)
+    cnt, ms, flops = ctx.profile_read("hvp_ggn")
+    tf = flops / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+    phases = {}
+    for name in ("hvp_ggn", "reorth_dot", "reorth_sub", "normalise", "ritz_vectors"):
+        c, m_, by = ctx.profile_read(name)
+        if c:
+            phases[name] = {"launches": c, "ms_total": round(m_, 3), "avg_ms": round(m_ / c, 4)}
+            if name != "hvp_ggn":
+                phases[name]["GBps"] = round(by / (m_ * 1e-3) / 1e9, 1)
+    out = {"metric": "Lanczos+Ritz on the softmax-GGN operator: step time (ms); MFMA TFLOP/s of the operator",
+           "value": round(dt / args.steps * 1e3, 3), "unit": "ms", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 3), "higher_is_better": False,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"cfg3: softmax-GGN, X {g.B}x{g.d}, W {g.d}x{g.C} (n={g.n}), Lanczos m={g.m}, k={g.k}",
+                      "m_eff": state["m_eff"]},
+           "roofline": {"bound": "mfma", "kernel": "softmax-GGN apply (2 fp32-MFMA GEMMs + softmax Jacobian), whole apply",
+                        "achieved": round(tf, 2), "peak": 157.3, "unit": "TFLOP/s", "frac": round(tf / 157.3, 4),
+                        "traffic": None, "avg_launch_ms": round(ms / cnt, 4) if cnt else None,
+                        "flops_per_apply": 4.0 * g.B * g.d * g.C},
+           "phases": phases}
+    print(json.dumps(out))
+    op.close()
+    ctx.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -114,6 +170,8 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.config == 3:
+        return bench_ggn(args, fo, torch, np)
     w = planted_workload_device(args.config, args.n)
     ctx = fo.Context(0)
     U = fo.ColMajor(w.n, w.r, w.ld, buf=w.U)
@@ -180,8 +238,8 @@ def main() -> int:
         if cnt:
             phases[name] = {"launches": cnt, "ms_total": round(ms, 3), "avg_ms": round(ms / cnt, 4),
                             "GBps": round(by / (ms * 1e-3) / 1e9, 1) if ms > 0 else None}
-    # dominant kernel: the operator's expand sweep (k_combine_columns<false,true,false,false>),
-    # (r + 2) vectors per launch
+    # dominant kernel: the operator's expand sweep (k_combine_columns<false,true,false,false,LDOT,...>): U, the
+    # current and (from the second Lanczos step on, in 'local_full' mode) the previous Lanczos vector, one store
     cnt, ms, by = ctx.profile_read("hvp_expand")
     achieved = by / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
     traffic = None
@@ -190,11 +248,11 @@ def main() -> int:
         for line in open(tfile):
             if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
                 traffic = float(line.split("=", 1)[1])
-    roofline = {"bound": "hbm", "kernel": "k_combine_columns<false,true,false,false> (planted operator, expand sweep)",
+    roofline = {"bound": "hbm", "kernel": "k_combine_columns<false,true,false,false,...> (planted operator, expand sweep)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "avg_launch_ms": round(ms / cnt, 4) if cnt else None,
-                "algorithmic_bytes_per_launch": (w.r + 2) * vec_bytes, "launches": cnt}
+                "algorithmic_bytes_per_launch": round(by / cnt) if cnt else None, "launches": cnt}
 
     out = {
         "metric": "Lanczos+FOSI step: achieved algorithmic HBM GB/s (step time in ms_per_step)",
