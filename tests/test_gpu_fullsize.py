@@ -96,9 +96,9 @@ def _gram_f64(M: torch.Tensor, n: int, extra: torch.Tensor, chunk: int = 1 << 20
     return G.cpu().numpy()
 
 
-def test_workload4_full_size(fo, ctx):
+def _full_size_planted(fo, ctx, cfg_id):
     from workloads.device import planted_workload_device
-    w = planted_workload_device(4)
+    w = planted_workload_device(cfg_id)
     n, m, r = w.n, w.m, w.r
     U = fo.ColMajor(n, r, w.ld, buf=w.U)
     op = ctx.hvp_planted(U, w.lam, w.shift)
@@ -118,14 +118,19 @@ def test_workload4_full_size(fo, ctx):
     a_ref, b_ref = reduced_tridiagonal_from_gram(G, lam, w.shift)
     assert np.max(np.abs(alpha[:40] - a_ref[:40])) < 1e-5 * scale
     assert np.max(np.abs(beta[:40] - b_ref[:40])) < 1e-5 * scale
-    u_ref = np.linalg.eigvalsh(tridiagonal(a_ref, b_ref, m))
-    ref_vals = np.concatenate([u_ref[::-1][: w.k], u_ref[: w.l]])
-    assert np.max(np.abs(evals - ref_vals) / np.abs(ref_vals)) <= 1e-4, (evals, ref_vals)
-
-    # (a') Ritz subspaces against the reference Ritz vectors V_ref = [U, v1] C (C from the same independent
-    # route): the cross products V^T [U, v1] are library float64 matmuls
+    # Ritz values and the reference Ritz vectors V_ref = [U, v1] C from the same independent route.  Pairs the
+    # fp64 reference has resolved (residual estimate <= 1e-2 |theta|) must agree to 1e-4 relative.  For the
+    # others the bar follows from the arithmetic: storing the basis in fp32 perturbs the operator by about
+    # u32 ||H|| per step, and an unresolved Ritz value can move by that much (4 u32 ||H|| allowed).
+    u32 = 2.0 ** -24
     ev_ref, Cmat, resid_ref, all_ref = reduced_ritz_coefficients(G, lam, w.shift, m, w.k, w.l)
-    assert np.max(np.abs(evals - ev_ref) / np.abs(ev_ref)) <= 1e-4
+    resolved_all = resid_ref <= 1e-2 * np.abs(ev_ref)
+    err = np.abs(evals - ev_ref)
+    print(f"[workload {cfg_id}] Ritz value relative errors {np.array2string(err / np.abs(ev_ref), precision=1)}; "
+          f"resolved by the reference: {resolved_all.sum()} of {r_v}")
+    assert resolved_all.sum() >= w.k
+    assert np.max(err[resolved_all] / np.abs(ev_ref[resolved_all])) <= 1e-4
+    assert np.max(err) <= max(1e-4 * np.abs(ev_ref).min(), 4 * u32 * scale)
     Vm_ = V.buf[: r_v * w.ld].view(r_v, w.ld)
     Um_ = w.U.view(r, w.ld)
     cross = torch.zeros(r_v, r + 1, dtype=torch.float64, device="cuda")
@@ -134,14 +139,13 @@ def test_workload4_full_size(fo, ctx):
         basis = torch.cat([Um_[:, lo:hi].double(), w.v1[lo:hi].double()[None, :]], dim=0)
         cross += Vm_[:, lo:hi].double() @ basis.T
     overlap = cross.cpu().numpy() @ Cmat                       # V_gpu^T V_ref, r_v x r_v
-    u32 = 2.0 ** -24
     for name, blk, outside in (("top", slice(0, w.k), all_ref[m - 1 - w.k]), ("bottom", slice(w.k, r_v), all_ref[w.l])):
         sv = np.linalg.svd(overlap[blk, blk], compute_uv=False)
         sines = np.sqrt(np.maximum(0.0, 1.0 - np.minimum(sv, 1.0) ** 2))
         # per pair: how far the GPU's Ritz vector leaves the reference block
         leave = np.sqrt(np.maximum(0.0, 1.0 - np.sum(overlap[blk, blk] ** 2, axis=1)))
         gap = np.min(np.abs(ev_ref[blk] - outside))
-        print(f"[workload 4] {name} block: max sin(angle) {sines.max():.2e}; per pair {np.array2string(leave, precision=1)}; "
+        print(f"[workload {cfg_id}] {name} block: max sin(angle) {sines.max():.2e}; per pair {np.array2string(leave, precision=1)}; "
               f"reference residuals {np.array2string(resid_ref[blk], precision=1)}; gap to the next Ritz value {gap:.3f}")
         resolved = resid_ref[blk] <= 1e-2 * np.abs(ev_ref[blk])
         # pairs the fp64 reference has resolved: the 1e-3 rad bar
@@ -201,3 +205,15 @@ def test_workload4_full_size(fo, ctx):
     assert rel_l2(mom[rows].cpu().numpy(), b_s) <= 1e-5
     assert rel_l2(wa[rows].cpu().numpy(), w_s) <= 1e-5
     op.close()
+
+
+def test_workload4_full_size(fo, ctx):
+    """n = 25.6 M, r = 128, m = 80, k = 20, l = 10: the configuration bench.py times."""
+    _full_size_planted(fo, ctx, 4)
+
+
+def test_workload5_full_size(fo, ctx):
+    """n = 125 M, r = 128, m = 100, k = 20, l = 20: the largest block (138 GB of the 288 GB HBM)."""
+    torch.cuda.empty_cache()
+    _full_size_planted(fo, ctx, 5)
+    torch.cuda.empty_cache()
