@@ -149,6 +149,9 @@ def main() -> int:
     ap.add_argument("--n", type=int, default=None, help="override the row count (debugging)")
     ap.add_argument("--reorth", choices=sorted(REORTH_MODES), default="local_full",
                     help="Gram-Schmidt scheme of the Lanczos run (library default: local_full)")
+    ap.add_argument("--m", type=int, default=None, help="override the number of Lanczos steps")
+    ap.add_argument("--accuracy", action="store_true",
+                    help="also report max|Q^T Q - I| of the last Lanczos basis (library float64 matmuls, untimed)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=1_600_000)
     ap.add_argument("--pmc-probe", action="store_true",
@@ -173,6 +176,8 @@ def main() -> int:
     if args.config == 3:
         return bench_ggn(args, fo, torch, np)
     w = planted_workload_device(args.config, args.n)
+    if args.m is not None:
+        w.m = args.m
     ctx = fo.Context(0)
     U = fo.ColMajor(w.n, w.r, w.ld, buf=w.U)
     op = ctx.hvp_planted(U, w.lam, w.shift)
@@ -268,6 +273,16 @@ def main() -> int:
         "roofline": roofline,
         "phases": phases,
     }
+    if args.accuracy:
+        me = state["m_eff"]
+        Qm = Q.buf[: me * w.ld].view(me, w.ld)
+        gram = torch.zeros(me, me, dtype=torch.float64, device="cuda")
+        for lo in range(0, w.n, 1 << 20):
+            blk = Qm[:, lo:min(w.n, lo + (1 << 20))].double()
+            gram += blk @ blk.T
+        out["accuracy"] = {"max_abs_QtQ_minus_I": float((gram - torch.eye(me, dtype=torch.float64, device="cuda")).abs().max()),
+                           "ritz_values": [float(x) for x in state["evals"]],
+                           "ritz_residual_estimates": [float(x) for x in state["resid"]]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_sample_rows)
     print(json.dumps(out))

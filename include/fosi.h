@@ -106,6 +106,10 @@ typedef struct {
     double breakdown_tol;
 } fosi_lanczos_opts;
 
+/* The paper's rule for the number of Lanczos steps (paragraph introducing Algorithm 1):
+ * m = max{4 (k + l), 2 ln n}, rounded up.  Host-only; returns 0 for invalid arguments. */
+int32_t fosi_lanczos_steps(int64_t n, int k, int l);
+
 /* Q_dev: n x (m+1) column-major (ldq).  On entry column 0 holds the start
  * vector (any non-zero vector: it is normalised in place); on exit columns
  * 0..m_eff-1 are the orthonormal Lanczos vectors and column m_eff (if

@@ -327,6 +327,12 @@ fosi_status hvp_destroy(fosi_hvp* op) {
 
 /* ------------------------------------------------------------- Algorithm 1 */
 
+int32_t fosi_lanczos_steps(int64_t n, int k, int l) {
+    if (n < 1 || k < 0 || l < 0 || k + l < 1) return 0;
+    const double by_pairs = 4.0 * (k + l), by_size = 2.0 * std::log((double)n);
+    return (int32_t)std::ceil(by_pairs > by_size ? by_pairs : by_size);
+}
+
 fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q_dev, int64_t ldq,
                          double* alpha_host, double* beta_host, int32_t* m_eff, const fosi_lanczos_opts* opts) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;

@@ -23,7 +23,7 @@ def fo():
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "fosi.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"\b(?:fosi_status|const char\*)\s+((?:fosi|hvp)_[a-z0-9_]+)\s*\(", text)
+    names = re.findall(r"\b(?:fosi_status|const char\*|int32_t)\s+((?:fosi|hvp)_[a-z0-9_]+)\s*\(", text)
     return sorted(set(names))
 
 
@@ -104,3 +104,11 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode == 2 and "one GPU" in r.stderr
+
+
+def test_lanczos_length_rule(fo):
+    # m = max{4 (k + l), 2 ln n}
+    assert fo.fosi_lanczos_steps(4096, 10, 0) == 40
+    assert fo.fosi_lanczos_steps(25_600_000, 20, 10) == 120
+    assert fo.fosi_lanczos_steps(10 ** 9, 1, 0) == int(np.ceil(2 * np.log(1e9)))      # the size term wins: 42
+    assert fo.fosi_lanczos_steps(0, 1, 0) == 0 and fo.fosi_lanczos_steps(10, 0, 0) == 0
