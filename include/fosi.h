@@ -163,6 +163,24 @@ fosi_status fosi_step(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int
                       const double* evals_host, const float* g_dev, const float* pi_dev,
                       float* mom_dev, float* w_dev, const fosi_step_params* p);
 
+/* Same update with AdamW as the base first-order optimiser (the optimiser of the paper's experiments,
+ * Section IV hyper-parameter paragraph).  The optimiser's descent vector is
+ *   o = -lr ( m^ / (sqrt(v^) + eps) + weight_decay w ),
+ * m, v the running moments of x = g~ - V c with bias corrections for step_index (1-based), and
+ *   Delta_2 = o - V (V^T o)   (the decoupled decay is part of the vector that is re-projected).
+ * exp_avg_dev, exp_avg_sq_dev: n fp32 moments, updated in place; work_dev: n fp32 scratch owned by the
+ * caller (receives o); w_dev updated in place.  With r_v = 0 this is textbook AdamW. */
+typedef struct {
+    float alpha;          /* Newton scale */
+    float lr, beta1, beta2, eps, weight_decay;
+    float sigma;          /* ADMM penalty; ignored when pi_dev is NULL */
+    int32_t curv_mode;
+} fosi_adamw_params;
+fosi_status fosi_step_adamw(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int64_t ldv,
+                            const double* evals_host, const float* g_dev, const float* pi_dev,
+                            float* exp_avg_dev, float* exp_avg_sq_dev, float* work_dev, float* w_dev,
+                            int64_t step_index, const fosi_adamw_params* p);
+
 /* ---- Algorithm 3 / Eq. 11: outer multiplier rule ---------------------------- */
 
 /* Start of an outer iteration: w_anchor = w_a + pi / sigma; w_a = w_anchor. */

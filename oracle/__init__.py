@@ -17,5 +17,5 @@ products, closed forms).  No function is "parity unpinned".
 from .hvp import hvp_planted, hvp_diag, hvp_softmax_ggn, softmax_rows  # noqa: F401
 from .lanczos import lanczos, LanczosResult  # noqa: F401
 from .ritz import ritz, RitzResult  # noqa: F401
-from .step import fosi_step  # noqa: F401
+from .step import fosi_step, fosi_step_adamw  # noqa: F401
 from .admm import admm_begin, admm_end  # noqa: F401

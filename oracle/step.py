@@ -53,3 +53,35 @@ def fosi_step(w: np.ndarray, g: np.ndarray, V: np.ndarray, evals: np.ndarray, mo
     delta2 = o - V @ (V.T @ o)
 
     return w + delta1 + delta2, b_new
+
+
+def fosi_step_adamw(w: np.ndarray, g: np.ndarray, V: np.ndarray, evals: np.ndarray, exp_avg: np.ndarray,
+                    exp_avg_sq: np.ndarray, step_index: int, alpha: float, lr: float, beta1: float, beta2: float,
+                    eps: float, weight_decay: float, sigma: float = 0.0, pi: Optional[np.ndarray] = None,
+                    curv_mode: str = "signed") -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """The same update with AdamW as the base optimiser (the optimiser of the paper's experiments, Section IV).
+    Returns (w_new, exp_avg_new, exp_avg_sq_new).
+
+    Reading: the optimiser is handed x = g~ - g_1 and returns its whole descent vector
+        o = -lr ( m_hat / (sqrt(v_hat) + eps) + weight_decay * w ),
+    decoupled decay included, with the usual bias corrections for `step_index` (1-based); Eq. 12 / Eq. 14
+    then re-project it: Delta_2 = o - V (V^T o).  With no columns in V this is textbook AdamW."""
+    w = np.asarray(w, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    a_hat = np.asarray(evals, dtype=np.float64)
+    if pi is None:
+        g_tilde, sig = g, 0.0
+    else:
+        g_tilde, sig = g + np.asarray(pi, dtype=np.float64), float(sigma)
+    c = V.T @ g_tilde
+    denom = a_hat + sig if curv_mode == "signed" else np.abs(a_hat) + sig
+    delta1 = -alpha * (V @ (c / denom))
+    x = g_tilde - V @ c
+    m_new = beta1 * np.asarray(exp_avg, dtype=np.float64) + (1.0 - beta1) * x
+    v_new = beta2 * np.asarray(exp_avg_sq, dtype=np.float64) + (1.0 - beta2) * x * x
+    m_hat = m_new / (1.0 - beta1 ** step_index)
+    v_hat = v_new / (1.0 - beta2 ** step_index)
+    o = -lr * (m_hat / (np.sqrt(v_hat) + eps) + weight_decay * w)
+    delta2 = o - V @ (V.T @ o)
+    return w + delta1 + delta2, m_new, v_new

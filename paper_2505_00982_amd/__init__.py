@@ -17,6 +17,8 @@ from .binding import (  # noqa: F401
     REORTH_LOCAL_FULL,
     fosi_ritz,
     fosi_step,
+    fosi_step_adamw,
+    AdamwParams,
     fosi_admm_begin,
     fosi_admm_end,
     fosi_tridiag_eigh,

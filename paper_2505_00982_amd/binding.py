@@ -26,7 +26,7 @@ PROF = {"hvp_project": 0, "hvp_expand": 1, "reorth_dot": 2, "reorth_sub": 3, "no
 EXPORTS = [
     "fosi_ctx_create", "fosi_ctx_destroy", "fosi_ctx_synchronize", "fosi_last_error", "fosi_status_string",
     "hvp_planted_create", "hvp_diag_create", "hvp_softmax_ggn_create", "hvp_callback_create", "hvp_apply",
-    "hvp_destroy", "fosi_lanczos", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_admm_begin",
+    "hvp_destroy", "fosi_lanczos", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_step_adamw", "fosi_admm_begin",
     "fosi_admm_end", "fosi_profile_enable", "fosi_profile_reset", "fosi_profile_read",
 ]
 
@@ -44,6 +44,11 @@ class _LanczosOpts(C.Structure):
 class _StepParams(C.Structure):
     _fields_ = [("alpha", C.c_float), ("lr", C.c_float), ("momentum", C.c_float), ("sigma", C.c_float),
                 ("curv_mode", C.c_int32)]
+
+
+class _AdamwParams(C.Structure):
+    _fields_ = [("alpha", C.c_float), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("weight_decay", C.c_float), ("sigma", C.c_float), ("curv_mode", C.c_int32)]
 
 
 HVP_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p)
@@ -81,6 +86,7 @@ def load_library() -> C.CDLL:
     lib.fosi_tridiag_eigh.argtypes = [C.c_int, dp, dp, dp, dp]
     lib.fosi_ritz.argtypes = [vp, i64, C.c_int, vp, i64, dp, dp, C.c_int, C.c_int, vp, i64, dp, dp]
     lib.fosi_step.argtypes = [vp, i64, C.c_int, vp, i64, dp, vp, vp, vp, vp, C.POINTER(_StepParams)]
+    lib.fosi_step_adamw.argtypes = [vp, i64, C.c_int, vp, i64, dp, vp, vp, vp, vp, vp, vp, i64, C.POINTER(_AdamwParams)]
     lib.fosi_admm_begin.argtypes = [vp, i64, C.c_float, vp, vp, vp]
     lib.fosi_admm_end.argtypes = [vp, i64, C.c_float, vp, vp, vp]
     lib.fosi_profile_enable.argtypes = [vp, C.c_int]
@@ -285,6 +291,29 @@ def fosi_step(ctx: Context, V: Optional[ColMajor], r_v: int, evals: Optional[np.
     sp = _StepParams(p.alpha, p.lr, p.momentum, p.sigma, p.curv_mode)
     ctx.check(ctx.lib.fosi_step(ctx.handle, n, r_v, V.ptr if r_v > 0 else None, V.ld if r_v > 0 else 0, _dptr(ev),
                                 _ptr(g), _ptr(pi), _ptr(mom), _ptr(w), C.byref(sp)))
+
+
+@dataclass
+class AdamwParams:
+    alpha: float = 0.1
+    lr: float = 1e-3
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    weight_decay: float = 0.05
+    sigma: float = 5e-4
+    curv_mode: int = 0
+
+
+def fosi_step_adamw(ctx: Context, V: Optional[ColMajor], r_v: int, evals: Optional[np.ndarray], g: torch.Tensor,
+                    pi: Optional[torch.Tensor], exp_avg: torch.Tensor, exp_avg_sq: torch.Tensor, work: torch.Tensor,
+                    w: torch.Tensor, step_index: int, p: AdamwParams):
+    n = w.numel()
+    ev = np.ascontiguousarray(evals, dtype=np.float64) if r_v > 0 else np.zeros(1)
+    ap = _AdamwParams(p.alpha, p.lr, p.beta1, p.beta2, p.eps, p.weight_decay, p.sigma, p.curv_mode)
+    ctx.check(ctx.lib.fosi_step_adamw(ctx.handle, n, r_v, V.ptr if r_v > 0 else None, V.ld if r_v > 0 else 0, _dptr(ev),
+                                      _ptr(g), _ptr(pi), _ptr(exp_avg), _ptr(exp_avg_sq), _ptr(work), _ptr(w),
+                                      int(step_index), C.byref(ap)))
 
 
 def fosi_admm_begin(ctx: Context, sigma: float, pi: torch.Tensor, w_anchor: torch.Tensor, wa: torch.Tensor):

@@ -470,6 +470,29 @@ fosi_status fosi_ritz(fosi_ctx* ctx, int64_t n, int m_eff, const float* Q_dev, i
 
 /* ------------------------------------------------- Eq. 4 / Eq. 12 / Eq. 14 */
 
+/* alpha / (a_j + sigma) (or with |a_j|) to device memory; unchanged between curvature refreshes, so it is
+ * uploaded only when it differs from what the device already holds. */
+static fosi_status upload_newton(fosi_ctx* ctx, int r_v, const double* evals_host, int curv_mode, double sigma,
+                                 double alpha) {
+    if (r_v <= 0) return FOSI_OK;
+    std::vector<double> newton(r_v);
+    for (int j = 0; j < r_v; ++j) {
+        const double a = curv_mode == FOSI_CURV_ABS ? std::fabs(evals_host[j]) : evals_host[j];
+        const double den = a + sigma;
+        if (!(std::fabs(den) >= 1e-30) || !std::isfinite(den))
+            return fail(ctx, FOSI_ERR_NONFINITE, "Newton divisor a_j + sigma is zero or non-finite");
+        newton[j] = alpha / den;
+    }
+    if (newton != ctx->newton_cache) {
+        if (fosi_status s = check_hip(ctx, hipMemcpyAsync(ctx->s.newton, newton.data(), sizeof(double) * r_v,
+                                                          hipMemcpyHostToDevice, ctx->stream), "upload divisors"))
+            return s;
+        if (fosi_status s = check_hip(ctx, hipStreamSynchronize(ctx->stream), "upload divisors sync")) return s;
+        ctx->newton_cache = newton;
+    }
+    return FOSI_OK;
+}
+
 fosi_status fosi_step(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int64_t ldv, const double* evals_host,
                       const float* g_dev, const float* pi_dev, float* mom_dev, float* w_dev, const fosi_step_params* p) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
@@ -487,23 +510,7 @@ fosi_status fosi_step(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int
 
     const double sigma = pi_dev != nullptr ? (double)p->sigma : 0.0;
     const double alpha = p->alpha, lr = p->lr, mu = p->momentum;
-    if (r_v > 0) {
-        std::vector<double> newton(r_v);
-        for (int j = 0; j < r_v; ++j) {
-            const double a = p->curv_mode == FOSI_CURV_ABS ? std::fabs(evals_host[j]) : evals_host[j];
-            const double den = a + sigma;
-            if (!(std::fabs(den) >= 1e-30) || !std::isfinite(den))
-                return fail(ctx, FOSI_ERR_NONFINITE, "Newton divisor a_j + sigma is zero or non-finite");
-            newton[j] = alpha / den;
-        }
-        if (newton != ctx->newton_cache) {   // unchanged between curvature refreshes: upload once
-            if (fosi_status s = check_hip(ctx, hipMemcpyAsync(ctx->s.newton, newton.data(), sizeof(double) * r_v,
-                                                              hipMemcpyHostToDevice, ctx->stream), "upload divisors"))
-                return s;
-            if (fosi_status s = check_hip(ctx, hipStreamSynchronize(ctx->stream), "upload divisors sync")) return s;
-            ctx->newton_cache = newton;
-        }
-    }
+    if (fosi_status st = upload_newton(ctx, r_v, evals_host, p->curv_mode, sigma, alpha)) return st;
     const double vec = kVec * (double)n;
     const int extra = pi_dev != nullptr ? 1 : 0;
     ProfScope ps(ctx, FOSI_PROF_STEP, r_v > 0 ? (4.0 * r_v + 8 + 2 * extra) * vec : (6.0 + extra) * vec);
@@ -522,6 +529,51 @@ fosi_status fosi_step(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int
     launch_combine_columns(ctx, V_dev, ldv, r_v, ctx->s.coef_c, w_dev, 1.0, mom_dev, -lr, nullptr, 0.0, nullptr, false,
                            -1.0, w_dev, n, false, nullptr, -1, 0.0);
     return launch_status(ctx, "fosi_step");
+}
+
+fosi_status fosi_step_adamw(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int64_t ldv,
+                            const double* evals_host, const float* g_dev, const float* pi_dev, float* exp_avg_dev,
+                            float* exp_avg_sq_dev, float* work_dev, float* w_dev, int64_t step_index,
+                            const fosi_adamw_params* p) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (p == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "params is null");
+    if (n < 1 || r_v < 0 || step_index < 1) return fail(ctx, FOSI_ERR_INVALID_ARG, "bad sizes or step index");
+    if (r_v > kMaxCols) return fail(ctx, FOSI_ERR_LIMIT, "k + l exceeds FOSI_MAX_COLS");
+    if (p->curv_mode != FOSI_CURV_SIGNED && p->curv_mode != FOSI_CURV_ABS)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "unknown curv_mode");
+    if (!(p->beta1 >= 0.f && p->beta1 < 1.f && p->beta2 >= 0.f && p->beta2 < 1.f))
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "beta1, beta2 must lie in [0, 1)");
+    if (fosi_status s = check_matrix(ctx, "V_dev", V_dev, n, ldv, r_v)) return s;
+    if (r_v > 0 && evals_host == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "evals_host is null");
+    if (fosi_status s = check_vector(ctx, "g_dev", g_dev)) return s;
+    if (fosi_status s = check_vector(ctx, "pi_dev", pi_dev, true)) return s;
+    if (fosi_status s = check_vector(ctx, "exp_avg_dev", exp_avg_dev)) return s;
+    if (fosi_status s = check_vector(ctx, "exp_avg_sq_dev", exp_avg_sq_dev)) return s;
+    if (fosi_status s = check_vector(ctx, "work_dev", work_dev)) return s;
+    if (fosi_status s = check_vector(ctx, "w_dev", w_dev)) return s;
+    const double sigma = pi_dev != nullptr ? (double)p->sigma : 0.0;
+    if (fosi_status st = upload_newton(ctx, r_v, evals_host, p->curv_mode, sigma, (double)p->alpha)) return st;
+    const double b1 = p->beta1, b2 = p->beta2;
+    const double inv_bc1 = 1.0 / (1.0 - std::pow(b1, (double)step_index));
+    const double inv_bc2 = 1.0 / (1.0 - std::pow(b2, (double)step_index));
+    const double vec = kVec * (double)n;
+    const int extra = pi_dev != nullptr ? 1 : 0;
+    ProfScope ps(ctx, FOSI_PROF_STEP, r_v > 0 ? (4.0 * r_v + 13 + 2 * extra) * vec : (9.0 + extra) * vec);
+    if (r_v > 0)   // c = V^T (g + pi)
+        launch_dot_columns(ctx, V_dev, ldv, r_v, g_dev, pi_dev, nullptr, nullptr, n, ctx->s.coef_a, nullptr, 0, 1.0,
+                           nullptr, nullptr, -1, 0.0);
+    // moments of x = g + pi - V c, and the optimiser's descent vector o
+    launch_adamw_moments(ctx, V_dev, ldv, r_v, ctx->s.coef_a, g_dev, pi_dev, w_dev, exp_avg_dev, exp_avg_sq_dev, work_dev,
+                         n, b1, b2, inv_bc1, inv_bc2, (double)p->eps, (double)p->lr, (double)p->weight_decay);
+    if (r_v > 0) {   // e = V^T o ;  d = newton . c + e
+        launch_dot_columns(ctx, V_dev, ldv, r_v, work_dev, nullptr, nullptr, nullptr, n, ctx->s.coef_b, nullptr, 0, 1.0,
+                           nullptr, nullptr, -1, 0.0);
+        launch_step_coefficients_plus(ctx, r_v);
+    }
+    // w <- w + o - V d   ( = w + Delta_1 + Delta_2 )
+    launch_combine_columns(ctx, V_dev, ldv, r_v, ctx->s.coef_c, w_dev, 1.0, work_dev, 1.0, nullptr, 0.0, nullptr, false,
+                           -1.0, w_dev, n, false, nullptr, -1, 0.0);
+    return launch_status(ctx, "fosi_step_adamw");
 }
 
 /* ------------------------------------------------------ Algorithm 3 / Eq. 11 */

@@ -135,6 +135,11 @@ void launch_diag_apply(fosi_ctx* ctx, const float* d, const float* v, float* out
 void launch_ritz_vectors(fosi_ctx* ctx, const float* Q, int64_t ldq, int m, const float* S_dev, int rv_pad,
                          int rv, float* V, int64_t ldv, int64_t n);
 void launch_step_coefficients(fosi_ctx* ctx, int rv, double lr);
+// AdamW base optimiser: moments + descent vector o (second sweep), and d = newton . c + e for the last sweep
+void launch_adamw_moments(fosi_ctx* ctx, const float* V, int64_t ldv, int rv, const double* c, const float* g,
+                          const float* pi, const float* w, float* m, float* v, float* o_out, int64_t n, double b1,
+                          double b2, double inv_bc1, double inv_bc2, double eps, double lr, double wd);
+void launch_step_coefficients_plus(fosi_ctx* ctx, int rv);
 void launch_admm_begin(fosi_ctx* ctx, int64_t n, double inv_sigma, const float* pi, float* anchor, float* wa);
 void launch_admm_end(fosi_ctx* ctx, int64_t n, double sigma, const float* anchor, const float* wa, float* pi);
 

@@ -249,6 +249,45 @@ __global__ __launch_bounds__(64) void k_reduce_columns(
     }
 }
 
+// s[q][0..3] = sum_j A[4 rows of row group rc[q], j] * d[j]  for the RPT row groups of one thread:
+// columns in the outer loop, CU at a time, RPT*CU independent 16-byte streaming loads in flight.
+template <int RPT, int CU>
+__device__ __forceinline__ void accumulate_columns(const float* __restrict__ A, int64_t lda, int ncols,
+                                                   const double* __restrict__ d, const int64_t* rc, double (*s)[4]) {
+#pragma unroll
+    for (int q = 0; q < RPT; ++q) s[q][0] = s[q][1] = s[q][2] = s[q][3] = 0.0;
+    int j = 0;
+    for (; j + CU <= ncols; j += CU) {
+        float4 a[CU][RPT];
+#pragma unroll
+        for (int u = 0; u < CU; ++u)
+#pragma unroll
+            for (int q = 0; q < RPT; ++q) a[u][q] = load_stream4(A + (int64_t)(j + u) * lda + (rc[q] << 2));
+#pragma unroll
+        for (int u = 0; u < CU; ++u) {
+            const double dj = d[j + u];
+#pragma unroll
+            for (int q = 0; q < RPT; ++q) {
+                s[q][0] = fma((double)a[u][q].x, dj, s[q][0]);
+                s[q][1] = fma((double)a[u][q].y, dj, s[q][1]);
+                s[q][2] = fma((double)a[u][q].z, dj, s[q][2]);
+                s[q][3] = fma((double)a[u][q].w, dj, s[q][3]);
+            }
+        }
+    }
+    for (; j < ncols; ++j) {
+        const double dj = d[j];
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            const float4 av = load_stream4(A + (int64_t)j * lda + (rc[q] << 2));
+            s[q][0] = fma((double)av.x, dj, s[q][0]);
+            s[q][1] = fma((double)av.y, dj, s[q][1]);
+            s[q][2] = fma((double)av.z, dj, s[q][2]);
+            s[q][3] = fma((double)av.w, dj, s[q][3]);
+        }
+    }
+}
+
 // ------------------------------------------------------------ combine_columns
 // out[row] = a0*y[row] + a1*x1[row] + a2*x2[row] + sa * sum_j A[row,j] d[j].
 // A block owns RPT*1024 consecutive rows per iteration: every thread keeps RPT float4 row groups
@@ -298,38 +337,7 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
             if (LDOT && x3 != nullptr) p3[q] = reinterpret_cast<const float4*>(x3)[rc[q]];
         }
         double s[RPT][4];
-#pragma unroll
-        for (int q = 0; q < RPT; ++q) s[q][0] = s[q][1] = s[q][2] = s[q][3] = 0.0;
-        int j = 0;
-        for (; j + CU <= ncols; j += CU) {
-            float4 a[CU][RPT];
-#pragma unroll
-            for (int u = 0; u < CU; ++u)
-#pragma unroll
-                for (int q = 0; q < RPT; ++q) a[u][q] = load_stream4(A + (int64_t)(j + u) * lda + (rc[q] << 2));
-#pragma unroll
-            for (int u = 0; u < CU; ++u) {
-                const double dj = d[j + u];
-#pragma unroll
-                for (int q = 0; q < RPT; ++q) {
-                    s[q][0] = fma((double)a[u][q].x, dj, s[q][0]);
-                    s[q][1] = fma((double)a[u][q].y, dj, s[q][1]);
-                    s[q][2] = fma((double)a[u][q].z, dj, s[q][2]);
-                    s[q][3] = fma((double)a[u][q].w, dj, s[q][3]);
-                }
-            }
-        }
-        for (; j < ncols; ++j) {
-            const double dj = d[j];
-#pragma unroll
-            for (int q = 0; q < RPT; ++q) {
-                const float4 av = load_stream4(A + (int64_t)j * lda + (rc[q] << 2));
-                s[q][0] = fma((double)av.x, dj, s[q][0]);
-                s[q][1] = fma((double)av.y, dj, s[q][1]);
-                s[q][2] = fma((double)av.z, dj, s[q][2]);
-                s[q][3] = fma((double)av.w, dj, s[q][3]);
-            }
-        }
+        accumulate_columns<RPT, CU>(A, lda, ncols, d, rc, s);
 #pragma unroll
         for (int q = 0; q < RPT; ++q) {
             if (r4[q] >= n4) continue;
@@ -392,6 +400,84 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
         const double b = block_sum(nrm, red);
         if (tid == 0) norm_partials[blockIdx.x] = b;
     }
+}
+
+// AdamW as the base optimiser of Eq. 12 / Eq. 14, second sweep of the update:
+//   x = g (+ pi) - V c ;  m <- b1 m + (1-b1) x ;  v <- b2 v + (1-b2) x^2 ;
+//   o = -lr ( (m / bc1) / (sqrt(v / bc2) + eps) + wd w )        (bc1, bc2: bias corrections of step t)
+// m, v are updated in place, o (the optimiser's descent vector, before re-projection) is written out.
+struct AdamwScalars {
+    double b1, b2, inv_bc1, inv_bc2, eps, lr, wd;
+};
+
+template <bool HAS_PI, int RPT, int CU>
+__global__ __launch_bounds__(kThreads) void k_adamw_moments(
+    const float* __restrict__ V, int64_t ldv, int ncols, const double* __restrict__ c, const float* __restrict__ g,
+    const float* __restrict__ pi, const float* __restrict__ w, float* m, float* v, float* __restrict__ o_out, int64_t n,
+    AdamwScalars p) {
+    const int tid = threadIdx.x;
+    const int64_t n4 = n >> 2;
+    const int64_t tile = (int64_t)kThreads * RPT;
+    const int64_t ntiles = (n4 + tile - 1) / tile;
+    auto one = [&](double x, double w_, float& m_, float& v_) -> float {
+        const double mn = p.b1 * (double)m_ + (1.0 - p.b1) * x;
+        const double vn = p.b2 * (double)v_ + (1.0 - p.b2) * x * x;
+        m_ = (float)mn;
+        v_ = (float)vn;
+        return (float)(-p.lr * ((mn * p.inv_bc1) / (sqrt(vn * p.inv_bc2) + p.eps) + p.wd * w_));
+    };
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        int64_t r4[RPT], rc[RPT];
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            r4[q] = t * tile + (int64_t)q * kThreads + tid;
+            rc[q] = r4[q] < n4 ? r4[q] : n4 - 1;
+        }
+        float4 pg[RPT], pp[RPT], pw[RPT], pm[RPT], pv[RPT];
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            pg[q] = reinterpret_cast<const float4*>(g)[rc[q]];
+            if (HAS_PI) pp[q] = reinterpret_cast<const float4*>(pi)[rc[q]];
+            pw[q] = reinterpret_cast<const float4*>(w)[rc[q]];
+            pm[q] = reinterpret_cast<const float4*>(m)[rc[q]];
+            pv[q] = reinterpret_cast<const float4*>(v)[rc[q]];
+        }
+        double s[RPT][4];
+        accumulate_columns<RPT, CU>(V, ldv, ncols, c, rc, s);
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            if (r4[q] >= n4) continue;
+            double x0 = (double)pg[q].x - s[q][0], x1 = (double)pg[q].y - s[q][1];
+            double x2 = (double)pg[q].z - s[q][2], x3 = (double)pg[q].w - s[q][3];
+            if (HAS_PI) { x0 += (double)pp[q].x; x1 += (double)pp[q].y; x2 += (double)pp[q].z; x3 += (double)pp[q].w; }
+            float4 mm = pm[q], vv = pv[q], oo;
+            oo.x = one(x0, (double)pw[q].x, mm.x, vv.x);
+            oo.y = one(x1, (double)pw[q].y, mm.y, vv.y);
+            oo.z = one(x2, (double)pw[q].z, mm.z, vv.z);
+            oo.w = one(x3, (double)pw[q].w, mm.w, vv.w);
+            reinterpret_cast<float4*>(m)[r4[q]] = mm;
+            reinterpret_cast<float4*>(v)[r4[q]] = vv;
+            store_stream4(o_out + (r4[q] << 2), oo);
+        }
+    }
+    const int64_t tail_row = (n4 << 2) + tid;
+    if (blockIdx.x == 0 && tid < 3 && tail_row < n) {
+        double sacc = 0.0;
+        for (int j = 0; j < ncols; ++j) sacc = fma((double)V[(int64_t)j * ldv + tail_row], c[j], sacc);
+        double x = (double)g[tail_row] - sacc;
+        if (HAS_PI) x += (double)pi[tail_row];
+        float mm = m[tail_row], vv = v[tail_row];
+        o_out[tail_row] = one(x, (double)w[tail_row], mm, vv);
+        m[tail_row] = mm;
+        v[tail_row] = vv;
+    }
+}
+
+// d_j = newton_j c_j + e_j  (AdamW variant of the last sweep's coefficients: w += o - V d)
+__global__ void k_step_coefficients_plus(const double* __restrict__ c, const double* __restrict__ e,
+                                         const double* __restrict__ newton, int rv, double* __restrict__ dcoef) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < rv) dcoef[j] = newton[j] * c[j] + e[j];
 }
 
 // ---------------------------------------------------------------- small kernels
@@ -737,6 +823,29 @@ void launch_admm_begin(fosi_ctx* ctx, int64_t n, double inv_sigma, const float* 
 void launch_admm_end(fosi_ctx* ctx, int64_t n, double sigma, const float* anchor, const float* wa, float* pi) {
     hipLaunchKernelGGL(k_admm_end, dim3(elementwise_grid(n)), dim3(kThreads), 0, ctx->stream, n, sigma, anchor, wa,
                        pi);
+}
+
+void launch_adamw_moments(fosi_ctx* ctx, const float* V, int64_t ldv, int rv, const double* c, const float* g,
+                          const float* pi, const float* w, float* m, float* v, float* o_out, int64_t n, double b1,
+                          double b2, double inv_bc1, double inv_bc2, double eps, double lr, double wd) {
+    constexpr int RPT = 2, CU = 8;
+    const int64_t n4 = n >> 2;
+    int64_t g_ = (n4 + kThreads * RPT - 1) / (kThreads * RPT);
+    if (g_ < 1) g_ = 1;
+    if (g_ > kMaxNormSlots) g_ = kMaxNormSlots;
+    AdamwScalars p{b1, b2, inv_bc1, inv_bc2, eps, lr, wd};
+    if (pi != nullptr)
+        hipLaunchKernelGGL((k_adamw_moments<true, RPT, CU>), dim3((unsigned)g_), dim3(kThreads), 0, ctx->stream, V, ldv, rv,
+                           c, g, pi, w, m, v, o_out, n, p);
+    else
+        hipLaunchKernelGGL((k_adamw_moments<false, RPT, CU>), dim3((unsigned)g_), dim3(kThreads), 0, ctx->stream, V, ldv, rv,
+                           c, g, pi, w, m, v, o_out, n, p);
+}
+
+void launch_step_coefficients_plus(fosi_ctx* ctx, int rv) {
+    if (rv <= 0) return;
+    hipLaunchKernelGGL(k_step_coefficients_plus, dim3((rv + 63) / 64), dim3(64), 0, ctx->stream, ctx->s.coef_a,
+                       ctx->s.coef_b, ctx->s.newton, rv, ctx->s.coef_c);
 }
 
 }  // namespace fosi

@@ -243,6 +243,32 @@ def test_update_step_against_oracle(fo, ctx, n, r, with_pi):
     assert rel_l2(md.cpu().numpy(), b_ref) <= STEP_RTOL
 
 
+@pytest.mark.parametrize("n,r", [(5, 1), (1025, 0), (50003, 15)])
+@pytest.mark.parametrize("with_pi", [False, True])
+def test_adamw_update_against_oracle(fo, ctx, n, r, with_pi):
+    rng = np.random.default_rng(100 + n + r)
+    Vh = _random_basis(n, r, 8) if r else np.zeros((n, 0), dtype=np.float32)
+    ev = np.concatenate([rng.uniform(1, 50, r - r // 3), -rng.uniform(0.5, 5, r // 3)]) if r else np.zeros(0)
+    w0, g = (rng.standard_normal(n).astype(np.float32) for _ in range(2))
+    pi = (0.1 * rng.standard_normal(n)).astype(np.float32) if with_pi else None
+    V = fo.ColMajor.from_numpy(Vh, wl.padded_ld(n)) if r else None
+    wd, md, vd, work = dev(w0), torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda")
+    ap = fo.AdamwParams(0.1, 1e-3, 0.9, 0.999, 1e-8, 0.05, 5e-4, 0)
+    f32 = lambda x: float(np.float32(x))
+    w_ref, m_ref, v_ref = w0, np.zeros(n), np.zeros(n)
+    for t in (1, 2, 3):
+        gt = (g * (1.0 + 0.1 * t)).astype(np.float32)
+        fo.fosi_step_adamw(ctx, V, r, ev, dev(gt), dev(pi) if with_pi else None, md, vd, work, wd, t, ap)
+        w_ref, m_ref, v_ref = oracle.fosi_step_adamw(w_ref, gt, Vh, ev, m_ref, v_ref, t, f32(0.1), f32(1e-3), f32(0.9),
+                                                     f32(0.999), f32(1e-8), f32(0.05), f32(5e-4), pi=pi)
+    ctx.synchronize()
+    assert rel_l2(wd.cpu().numpy(), w_ref) <= STEP_RTOL
+    assert rel_l2(md.cpu().numpy(), m_ref) <= STEP_RTOL
+    assert rel_l2(vd.cpu().numpy(), v_ref) <= STEP_RTOL
+    # the update itself (three steps of size ~lr): fp32 storage of w limits its relative accuracy
+    assert rel_l2(wd.cpu().numpy().astype(np.float64) - w0, w_ref - w0) <= 1e-3
+
+
 def test_abs_curvature_mode(fo, ctx):
     n, r = 3001, 6
     rng = np.random.default_rng(3)

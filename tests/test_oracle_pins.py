@@ -276,6 +276,44 @@ def test_step_with_dual_closed_form_and_g1_readings():
     assert not np.allclose(b1, b2, atol=1e-6)         # ... but not the same momentum buffer
 
 
+def test_adamw_step_without_subspace_is_library_adamw():
+    import torch
+    n = 64
+    rng = np.random.default_rng(12)
+    w = rng.standard_normal(n)
+    p = torch.nn.Parameter(torch.tensor(w, dtype=torch.float64))
+    opt = torch.optim.AdamW([p], lr=1e-3, betas=(0.9, 0.999), eps=1e-8, weight_decay=0.05)
+    m, v = np.zeros(n), np.zeros(n)
+    V = np.zeros((n, 0))
+    for t in range(1, 6):
+        g = rng.standard_normal(n)
+        w, m, v = oracle.fosi_step_adamw(w, g, V, np.zeros(0), m, v, t, 0.1, 1e-3, 0.9, 0.999, 1e-8, 0.05)
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        assert np.allclose(w, p.detach().numpy(), rtol=0, atol=1e-13)
+
+
+def test_adamw_step_structure():
+    n, r = 150, 5
+    V = _orthonormal(n, r, 13)
+    rng = np.random.default_rng(14)
+    a = rng.uniform(1, 8, r)
+    w, g, pi = rng.standard_normal(n), rng.standard_normal(n), 0.1 * rng.standard_normal(n)
+    w1, m1, v1 = oracle.fosi_step_adamw(w, g, V, a, np.zeros(n), np.zeros(n), 1, 0.2, 1e-3, 0.9, 0.999, 1e-8, 0.05,
+                                        sigma=0.05, pi=pi)
+    d1 = -0.2 * V @ ((V.T @ (g + pi)) / (a + 0.05))
+    # everything besides the Newton part is orthogonal to V; the moments only see the complement of g + pi
+    assert np.abs(V.T @ (w1 - w - d1)).max() < 1e-15
+    x = (g + pi) - V @ (V.T @ (g + pi))
+    assert np.allclose(m1, 0.1 * x, atol=1e-15) and np.allclose(v1, 0.001 * x * x, atol=1e-15)
+    # first step, no decay: the optimiser's vector is -lr sign(x) up to eps, re-projected
+    w2, _, _ = oracle.fosi_step_adamw(w, g, V, a, np.zeros(n), np.zeros(n), 1, 0.2, 1e-3, 0.9, 0.999, 1e-12, 0.0)
+    x0 = g - V @ (V.T @ g)
+    o = -1e-3 * np.sign(x0)
+    d1b = -0.2 * V @ ((V.T @ g) / a)
+    assert np.allclose(w2 - w - d1b, o - V @ (V.T @ o), atol=1e-9)
+
+
 # ---------------------------------------------------------------- ADMM outer
 def test_admm_outer_rules():
     n = 50
