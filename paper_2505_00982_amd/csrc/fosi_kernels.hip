@@ -12,6 +12,8 @@
 // in fp64 (the product of two fp32 values is exact there) and round once when
 // a vector is stored.  Cross-block sums are two-stage and in a fixed order, so
 // results do not depend on scheduling.
+#include <type_traits>
+
 #include "fosi_internal.h"
 
 namespace fosi {
@@ -52,43 +54,65 @@ __device__ __forceinline__ double block_sum(double v, double* lds4) {
 }
 
 // ---------------------------------------------------------------- dot_columns
-// Work is split per wavefront: a wave owns a "slot" of up to JB consecutive columns and sweeps
+// Work is split per wavefront: a wave owns a "slot" of up to 32 consecutive columns and sweeps
 // float4 row groups (64 lanes x 4 rows) with a grid stride, keeping one fp64 accumulator per
 // column.  The S (= 1, 2 or 4) waves of a block that own different slots walk the SAME rows, so
 // the vector x is fetched from HBM once and re-read from the CU's L1; the remaining 4/S waves of
-// the block take other rows.  A slot with fewer than JB columns is processed as 16 + 8 + 4 + 2 + 1
-// sub-blocks, so no column is ever loaded twice.  partials[rowslot * pstride + column] receives
-// the wave's sums, column index `ncols` the partial of sum(x^2) (from the waves of slot 0).
-// Loads the tile's float4 of NB consecutive columns.  `tile` points at the tile's first row in column
-// col0 and is the same for all lanes, `lane_off` (in floats) is the only per-lane part of the address:
-// the loads can then use a scalar base register pair plus one shared 32-bit offset register instead of
-// a 64-bit address per column.
-template <int NB>
-__device__ __forceinline__ void dot_load(const float* __restrict__ tile, int64_t lda, uint32_t lane_off, float4* a) {
-#pragma unroll
-    for (int j = 0; j < NB; ++j) a[j] = load_stream4(tile + (int64_t)j * lda + lane_off);
-}
+// the block take other rows.  The sweep is compiled for 4, 8, ..., 32 columns; a slot whose width
+// is not a multiple of 4 re-reads its last column for the (at most 3) padding positions, which hit
+// in cache and are discarded.  partials[rowslot * pstride + column] receives the wave's sums,
+// column index `ncols` the partial of sum(x^2) (from the waves of slot 0).
 
-template <int NB>
-__device__ __forceinline__ void dot_fma(const float4* a, double d0, double d1, double d2, double d3, double* acc) {
+// One sweep of a slot compiled for NCOL columns (nc <= NCOL of them real).  `Aj0` points at row 0 of
+// the slot's first column.  Everything but `lane` is uniform across the wave, so the column bases
+// live in scalar registers and every load is "scalar base + one shared 32-bit lane offset".
+template <int NCOL, int NX>
+__device__ __forceinline__ void dot_sweep(const float* __restrict__ Aj0, int64_t lda, int nc,
+                                          const float* __restrict__ x, const float* __restrict__ x2,
+                                          const float* __restrict__ x3, double s2, double s3, int64_t t_begin,
+                                          int64_t r_end, int64_t stride, int lane, bool do_xx, double* acc, double& xx) {
+    // The vector's row group for the NEXT tile is requested while the current tile's columns are in
+    // flight, so each trip of the loop costs one memory round trip, not two.
+    float4 nx1 = make_float4(0.f, 0.f, 0.f, 0.f), nx2 = nx1, nx3 = nx1;
+    uint32_t n_off = 0;
+    bool n_ok = false;
+    auto fetch_vector = [&](int64_t t) {
+        // lanes past the end of a ragged last tile re-read its last row group and contribute zeros
+        const int64_t rem = r_end - t;
+        n_ok = lane < rem;
+        n_off = (uint32_t)(n_ok ? lane : (int)rem - 1) << 4;      // bytes
+        nx1 = *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(x + (t << 2)) + n_off);
+        if (NX >= 2) nx2 = *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(x2 + (t << 2)) + n_off);
+        if (NX >= 3) nx3 = *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(x3 + (t << 2)) + n_off);
+    };
+    if (t_begin < r_end) fetch_vector(t_begin);
+    for (int64_t t = t_begin; t < r_end; t += stride) {
+        const float4 xv = nx1, u2 = nx2, u3 = nx3;
+        const uint32_t lane_bytes = n_off;
+        const bool ok = n_ok;
+        const float* At = Aj0 + (t << 2);
+        float4 a[NCOL];
 #pragma unroll
-    for (int j = 0; j < NB; ++j)
-        acc[j] = fma((double)a[j].x, d0, fma((double)a[j].y, d1, fma((double)a[j].z, d2, fma((double)a[j].w, d3, acc[j]))));
-}
-
-template <int NB>
-__device__ __forceinline__ void dot_tail_row(const float* __restrict__ A, int64_t lda, int col0, int64_t row, double dx,
-                                             double* acc) {
+        for (int j = 0; j < NCOL; ++j) {
+            const int col = j < nc ? j : nc - 1;
+            a[j] = load_stream4(reinterpret_cast<const float*>(
+                reinterpret_cast<const char*>(At + (int64_t)col * lda) + lane_bytes));
+        }
+        if (t + stride < r_end) fetch_vector(t + stride);
+        double d0 = xv.x, d1 = xv.y, d2 = xv.z, d3 = xv.w;
+        if (NX >= 2) {
+            d0 = fma(s2, (double)u2.x, d0); d1 = fma(s2, (double)u2.y, d1);
+            d2 = fma(s2, (double)u2.z, d2); d3 = fma(s2, (double)u2.w, d3);
+        }
+        if (NX >= 3) {
+            d0 = fma(s3, (double)u3.x, d0); d1 = fma(s3, (double)u3.y, d1);
+            d2 = fma(s3, (double)u3.z, d2); d3 = fma(s3, (double)u3.w, d3);
+        }
+        if (!ok) d0 = d1 = d2 = d3 = 0.0;
+        if (do_xx) xx = fma(d0, d0, fma(d1, d1, fma(d2, d2, fma(d3, d3, xx))));
 #pragma unroll
-    for (int j = 0; j < NB; ++j) acc[j] = fma((double)A[(int64_t)(col0 + j) * lda + row], dx, acc[j]);
-}
-
-template <int NB>
-__device__ __forceinline__ void dot_emit(const double* acc, double* prow, int col0, int lane) {
-#pragma unroll
-    for (int j = 0; j < NB; ++j) {
-        const double v = wave_sum(acc[j]);
-        if (lane == 0) prow[col0 + j] = v;
+        for (int j = 0; j < NCOL; ++j)
+            acc[j] = fma((double)a[j].x, d0, fma((double)a[j].y, d1, fma((double)a[j].z, d2, fma((double)a[j].w, d3, acc[j]))));
     }
 }
 
@@ -99,11 +123,11 @@ __global__ __launch_bounds__(kThreads) void k_dot_columns(
     const float* __restrict__ A, int64_t lda, int ncols, const float* __restrict__ x,
     const float* __restrict__ x2, const float* __restrict__ x3, const double* __restrict__ xs, int64_t n,
     double* __restrict__ partials, int pstride, int S, int xcd_part, const int* __restrict__ stop) {
-    static_assert(JB == 32, "sub-block decomposition below is written for 32-column slots");
+    static_assert(JB == 32, "the sweep variants below cover slots of up to 32 columns");
     if (stop != nullptr && *stop != 0) return;
     const int lane = threadIdx.x & 63;
-    // the wave index is the same for all 64 lanes: tell the compiler, so that the slot, its column bases and
-    // the sub-block tests below live in scalar registers
+    // the wave index is the same for all 64 lanes: tell the compiler, so that the slot and its column
+    // bases live in scalar registers
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int slot = blockIdx.y * S + (wave % S);       // column slot of this wave
     const int rowlane = wave / S;                       // which of the block's 4/S row groups
@@ -117,13 +141,10 @@ __global__ __launch_bounds__(kThreads) void k_dot_columns(
 #pragma unroll
     for (int j = 0; j < JB; ++j) acc[j] = 0.0;
     double xx = 0.0;
-    // sub-block layout of a ragged slot: 16 columns in acc[0..15], then 8 in acc[16..23], 4, 2, 1
-    const int o16 = j0, o8 = o16 + (nc & 16), o4 = o8 + (nc & 8), o2 = o4 + (nc & 4), o1 = o2 + (nc & 2);
 
     const int64_t n4 = n >> 2;
     // Row ranges.  Workgroups are handed to the 8 XCDs round-robin, so with xcd_part every XCD is given
-    // one contiguous eighth of the rows: its address-translation cache then only ever sees an eighth of
-    // the pages of the matrix.  (Correctness does not depend on how the hardware places workgroups.)
+    // one contiguous eighth of the rows.  (Correctness does not depend on how the hardware places workgroups.)
     int64_t t_begin, r_end, stride;          // all uniform across the wave (float4 units)
     if (xcd_part) {
         const int nx = gridDim.x >> 3;                                     // gridDim.x is a multiple of 8
@@ -138,59 +159,39 @@ __global__ __launch_bounds__(kThreads) void k_dot_columns(
         stride = (int64_t)gridDim.x * rows_per_block * 64;
     }
     const double s2 = NX >= 2 ? xs[0] : 0.0, s3 = NX >= 3 ? xs[1] : 0.0;
-    // The vector's row group for the NEXT tile is requested while the current tile's columns are in
-    // flight, so each trip of the loop costs one memory round trip, not two.
-    float4 nx1 = make_float4(0.f, 0.f, 0.f, 0.f), nx2 = nx1, nx3 = nx1;
-    uint32_t n_off = 0;
-    bool n_ok = false;
-    auto fetch_vector = [&](int64_t t) {
-        // lanes past the end of a ragged last tile re-read its last row group and contribute zeros
-        const int64_t rem = r_end - t;
-        n_ok = lane < rem;
-        n_off = (uint32_t)(n_ok ? lane : (int)rem - 1) << 2;
-        nx1 = *reinterpret_cast<const float4*>(x + (t << 2) + n_off);
-        if (NX >= 2) nx2 = *reinterpret_cast<const float4*>(x2 + (t << 2) + n_off);
-        if (NX >= 3) nx3 = *reinterpret_cast<const float4*>(x3 + (t << 2) + n_off);
-    };
-    if (t_begin < r_end) fetch_vector(t_begin);
-    for (int64_t t = t_begin; t < r_end; t += stride) {
-        const float4 xv = nx1, u2 = nx2, u3 = nx3;
-        const uint32_t lane_off = n_off;
-        const bool ok = n_ok;
-        const float* At = A + (t << 2);
-        float4 a[JB];
-        if (nc == JB) {
-            dot_load<JB>(At + (int64_t)j0 * lda, lda, lane_off, a);
-        } else {
-            // ragged slot: every load is issued before the first multiply, so the sub-blocks share one round trip
-            if (nc & 16) dot_load<16>(At + (int64_t)o16 * lda, lda, lane_off, a);
-            if (nc & 8) dot_load<8>(At + (int64_t)o8 * lda, lda, lane_off, a + 16);
-            if (nc & 4) dot_load<4>(At + (int64_t)o4 * lda, lda, lane_off, a + 24);
-            if (nc & 2) dot_load<2>(At + (int64_t)o2 * lda, lda, lane_off, a + 28);
-            if (nc & 1) dot_load<1>(At + (int64_t)o1 * lda, lda, lane_off, a + 30);
+    const float* Aj0 = A + (int64_t)j0 * lda;
+#define FOSI_SWEEP(NC_) dot_sweep<NC_, NX>(Aj0, lda, nc, x, x2, x3, s2, s3, t_begin, r_end, stride, lane, do_xx, acc, xx)
+    switch ((nc + 3) >> 2) {
+        case 0: {   // no columns (only reached by slot 0 when ncols == 0): just the sum of squares
+            for (int64_t t = t_begin; t < r_end; t += stride) {
+                if (t + lane < r_end) {
+                    const float4 xv = reinterpret_cast<const float4*>(x)[t + lane];
+                    double d0 = xv.x, d1 = xv.y, d2 = xv.z, d3 = xv.w;
+                    if (NX >= 2) {
+                        const float4 u = reinterpret_cast<const float4*>(x2)[t + lane];
+                        d0 = fma(s2, (double)u.x, d0); d1 = fma(s2, (double)u.y, d1);
+                        d2 = fma(s2, (double)u.z, d2); d3 = fma(s2, (double)u.w, d3);
+                    }
+                    if (NX >= 3) {
+                        const float4 u = reinterpret_cast<const float4*>(x3)[t + lane];
+                        d0 = fma(s3, (double)u.x, d0); d1 = fma(s3, (double)u.y, d1);
+                        d2 = fma(s3, (double)u.z, d2); d3 = fma(s3, (double)u.w, d3);
+                    }
+                    xx = fma(d0, d0, fma(d1, d1, fma(d2, d2, fma(d3, d3, xx))));
+                }
+            }
+            break;
         }
-        if (t + stride < r_end) fetch_vector(t + stride);
-        double d0 = xv.x, d1 = xv.y, d2 = xv.z, d3 = xv.w;
-        if (NX >= 2) {
-            d0 = fma(s2, (double)u2.x, d0); d1 = fma(s2, (double)u2.y, d1);
-            d2 = fma(s2, (double)u2.z, d2); d3 = fma(s2, (double)u2.w, d3);
-        }
-        if (NX >= 3) {
-            d0 = fma(s3, (double)u3.x, d0); d1 = fma(s3, (double)u3.y, d1);
-            d2 = fma(s3, (double)u3.z, d2); d3 = fma(s3, (double)u3.w, d3);
-        }
-        if (!ok) d0 = d1 = d2 = d3 = 0.0;
-        if (do_xx) xx = fma(d0, d0, fma(d1, d1, fma(d2, d2, fma(d3, d3, xx))));
-        if (nc == JB) {
-            dot_fma<JB>(a, d0, d1, d2, d3, acc);
-        } else {
-            if (nc & 16) dot_fma<16>(a, d0, d1, d2, d3, acc);
-            if (nc & 8) dot_fma<8>(a + 16, d0, d1, d2, d3, acc + 16);
-            if (nc & 4) dot_fma<4>(a + 24, d0, d1, d2, d3, acc + 24);
-            if (nc & 2) dot_fma<2>(a + 28, d0, d1, d2, d3, acc + 28);
-            if (nc & 1) dot_fma<1>(a + 30, d0, d1, d2, d3, acc + 30);
-        }
+        case 1: FOSI_SWEEP(4); break;
+        case 2: FOSI_SWEEP(8); break;
+        case 3: FOSI_SWEEP(12); break;
+        case 4: FOSI_SWEEP(16); break;
+        case 5: FOSI_SWEEP(20); break;
+        case 6: FOSI_SWEEP(24); break;
+        case 7: FOSI_SWEEP(28); break;
+        default: FOSI_SWEEP(32); break;
     }
+#undef FOSI_SWEEP
     // the last (n mod 4) rows: one scalar row per lane of the first row group
     const int64_t tail_row = (n4 << 2) + lane;
     if (blockIdx.x == 0 && rowlane == 0 && lane < 3 && tail_row < n) {
@@ -198,26 +199,18 @@ __global__ __launch_bounds__(kThreads) void k_dot_columns(
         if (NX >= 2) dx = fma(s2, (double)x2[tail_row], dx);
         if (NX >= 3) dx = fma(s3, (double)x3[tail_row], dx);
         if (do_xx) xx = fma(dx, dx, xx);
-        if (nc == JB) {
-            dot_tail_row<JB>(A, lda, j0, tail_row, dx, acc);
-        } else {
-            if (nc & 16) dot_tail_row<16>(A, lda, o16, tail_row, dx, acc);
-            if (nc & 8) dot_tail_row<8>(A, lda, o8, tail_row, dx, acc + 16);
-            if (nc & 4) dot_tail_row<4>(A, lda, o4, tail_row, dx, acc + 24);
-            if (nc & 2) dot_tail_row<2>(A, lda, o2, tail_row, dx, acc + 28);
-            if (nc & 1) dot_tail_row<1>(A, lda, o1, tail_row, dx, acc + 30);
-        }
+#pragma unroll
+        for (int j = 0; j < JB; ++j)
+            if (j < nc) acc[j] = fma((double)Aj0[(int64_t)j * lda + tail_row], dx, acc[j]);
     }
 
     double* prow = partials + ((int64_t)blockIdx.x * rows_per_block + rowlane) * pstride;
-    if (nc == JB) {
-        dot_emit<JB>(acc, prow, j0, lane);
-    } else {
-        if (nc & 16) dot_emit<16>(acc, prow, o16, lane);
-        if (nc & 8) dot_emit<8>(acc + 16, prow, o8, lane);
-        if (nc & 4) dot_emit<4>(acc + 24, prow, o4, lane);
-        if (nc & 2) dot_emit<2>(acc + 28, prow, o2, lane);
-        if (nc & 1) dot_emit<1>(acc + 30, prow, o1, lane);
+#pragma unroll
+    for (int j = 0; j < JB; ++j) {
+        if (j < nc) {                                   // uniform test: whole waves skip the padding columns
+            const double v = wave_sum(acc[j]);
+            if (lane == 0) prow[j0 + j] = v;
+        }
     }
     if (do_xx) {
         const double v = wave_sum(xx);
