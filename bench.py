@@ -37,7 +37,7 @@ def algorithmic_vectors(m_eff: int, r: int, r_v: int, reorth: str, with_pi: bool
     expand sweep (+1 vector, q_{i-1}, when i > 0), the full pass reads h, q_i and
     q_{i-1} to form its vector (c + 2 + [i > 0]) and one subtraction follows
     (c+2); normalisation 2.  Start vector 3.  Ritz vectors m_eff + r_v.  Update:
-    4 sweeps of V-hat plus 8 vector accesses (+2 with a dual variable)."""
+    3 sweeps of V-hat plus 7 vector accesses (+2 with a dual variable)."""
     hvp = m_eff * (2 * r + 3)
     if reorth == "local_full":
         hvp += max(0, m_eff - 1)
@@ -50,7 +50,7 @@ def algorithmic_vectors(m_eff: int, r: int, r_v: int, reorth: str, with_pi: bool
     reorth = sum(gs(i + 1) for i in range(m_eff))
     norm = 2 * m_eff + 3
     ritz = m_eff + r_v
-    step = 4 * r_v + 8 + (2 if with_pi else 0)
+    step = 3 * r_v + 7 + (2 if with_pi else 0)
     return dict(hvp=hvp, reorth=reorth, normalise=norm, ritz=ritz, step=step,
                 total=hvp + reorth + norm + ritz + step)
 

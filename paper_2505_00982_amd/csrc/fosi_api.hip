@@ -113,6 +113,8 @@ fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
     ctx->tun.comb_rows_per_thread = env_int("FOSI_COMB_ROWS", 4);
     ctx->tun.comb_cols_unroll = env_int("FOSI_COMB_COLS", 8);
     ctx->tun.comb_max_blocks = env_int("FOSI_COMB_BLOCKS", 0);
+    ctx->tun.step_waves_per_cu = env_int("FOSI_STEP_WAVES", 12);
+    if (ctx->tun.step_waves_per_cu < 1) ctx->tun.step_waves_per_cu = 1;
     ctx->tun.xcd_partition = env_int("FOSI_XCD_PARTITION", 0);
 
     const size_t cols1 = kMaxCols + 1;
@@ -513,17 +515,21 @@ fosi_status fosi_step(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int
     if (fosi_status st = upload_newton(ctx, r_v, evals_host, p->curv_mode, sigma, alpha)) return st;
     const double vec = kVec * (double)n;
     const int extra = pi_dev != nullptr ? 1 : 0;
-    ProfScope ps(ctx, FOSI_PROF_STEP, r_v > 0 ? (4.0 * r_v + 8 + 2 * extra) * vec : (6.0 + extra) * vec);
-    if (r_v > 0)   // c = V^T (g + pi)
+    // three sweeps of V: r_v + 1 (+1), r_v + 3 (+1), r_v + 3 vectors
+    ProfScope ps(ctx, FOSI_PROF_STEP, r_v > 0 ? (3.0 * r_v + 7 + 2 * extra) * vec : (6.0 + extra) * vec);
+    if (r_v > 0) {
+        // c = V^T (g + pi)
         launch_dot_columns(ctx, V_dev, ldv, r_v, g_dev, pi_dev, nullptr, nullptr, n, ctx->s.coef_a, nullptr, 0, 1.0,
                            nullptr, nullptr, -1, 0.0);
-    // b <- momentum b + (g + pi) - V c
-    launch_combine_columns(ctx, V_dev, ldv, r_v, ctx->s.coef_a, mom_dev, mu, g_dev, 1.0, pi_dev, 1.0, nullptr, false,
-                           -1.0, mom_dev, n, false, nullptr, -1, 0.0);
-    if (r_v > 0) {   // e = V^T b ;  d = newton . c - lr e
-        launch_dot_columns(ctx, V_dev, ldv, r_v, mom_dev, nullptr, nullptr, nullptr, n, ctx->s.coef_b, nullptr, 0, 1.0,
-                           nullptr, nullptr, -1, 0.0);
+        // b <- momentum b + (g + pi) - V c ;  e = V^T b
+        launch_complement_reproject(ctx, 0, V_dev, ldv, r_v, ctx->s.coef_a, g_dev, pi_dev, nullptr, mom_dev, nullptr,
+                                    nullptr, n, mu, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, ctx->s.coef_b);
+        // d = newton . c - lr e
         launch_step_coefficients(ctx, r_v, lr);
+    } else {
+        // b <- momentum b + (g + pi)
+        launch_combine_columns(ctx, V_dev, ldv, 0, ctx->s.coef_a, mom_dev, mu, g_dev, 1.0, pi_dev, 1.0, nullptr, false,
+                               -1.0, mom_dev, n, false, nullptr, -1, 0.0);
     }
     // w <- w - lr b - V d   ( = w + Delta_1 + Delta_2 )
     launch_combine_columns(ctx, V_dev, ldv, r_v, ctx->s.coef_c, w_dev, 1.0, mom_dev, -lr, nullptr, 0.0, nullptr, false,
@@ -558,18 +564,16 @@ fosi_status fosi_step_adamw(fosi_ctx* ctx, int64_t n, int r_v, const float* V_de
     const double inv_bc2 = 1.0 / (1.0 - std::pow(b2, (double)step_index));
     const double vec = kVec * (double)n;
     const int extra = pi_dev != nullptr ? 1 : 0;
-    ProfScope ps(ctx, FOSI_PROF_STEP, r_v > 0 ? (4.0 * r_v + 13 + 2 * extra) * vec : (9.0 + extra) * vec);
+    // three sweeps of V: r_v + 1 (+1), r_v + 7 (+1), r_v + 3 vectors
+    ProfScope ps(ctx, FOSI_PROF_STEP, r_v > 0 ? (3.0 * r_v + 11 + 2 * extra) * vec : (10.0 + extra) * vec);
     if (r_v > 0)   // c = V^T (g + pi)
         launch_dot_columns(ctx, V_dev, ldv, r_v, g_dev, pi_dev, nullptr, nullptr, n, ctx->s.coef_a, nullptr, 0, 1.0,
                            nullptr, nullptr, -1, 0.0);
-    // moments of x = g + pi - V c, and the optimiser's descent vector o
-    launch_adamw_moments(ctx, V_dev, ldv, r_v, ctx->s.coef_a, g_dev, pi_dev, w_dev, exp_avg_dev, exp_avg_sq_dev, work_dev,
-                         n, b1, b2, inv_bc1, inv_bc2, (double)p->eps, (double)p->lr, (double)p->weight_decay);
-    if (r_v > 0) {   // e = V^T o ;  d = newton . c + e
-        launch_dot_columns(ctx, V_dev, ldv, r_v, work_dev, nullptr, nullptr, nullptr, n, ctx->s.coef_b, nullptr, 0, 1.0,
-                           nullptr, nullptr, -1, 0.0);
-        launch_step_coefficients_plus(ctx, r_v);
-    }
+    // moments of x = g + pi - V c, the optimiser's descent vector o, and e = V^T o
+    launch_complement_reproject(ctx, 1, V_dev, ldv, r_v, ctx->s.coef_a, g_dev, pi_dev, w_dev, exp_avg_dev, exp_avg_sq_dev,
+                                work_dev, n, 0.0, b1, b2, inv_bc1, inv_bc2, (double)p->eps, (double)p->lr,
+                                (double)p->weight_decay, ctx->s.coef_b);
+    if (r_v > 0) launch_step_coefficients_plus(ctx, r_v);   // d = newton . c + e
     // w <- w + o - V d   ( = w + Delta_1 + Delta_2 )
     launch_combine_columns(ctx, V_dev, ldv, r_v, ctx->s.coef_c, w_dev, 1.0, work_dev, 1.0, nullptr, 0.0, nullptr, false,
                            -1.0, w_dev, n, false, nullptr, -1, 0.0);

@@ -29,6 +29,7 @@ struct Tunables {
     int comb_cols_unroll;     // CU: columns loaded together in that kernel
     int xcd_partition;        // give each XCD a contiguous eighth of the rows (1) or interleave rows over all XCDs (0)
     int comb_max_blocks;      // cap on that kernel's grid (it grid-strides over row tiles); 0 = no cap
+    int step_waves_per_cu;    // resident wavefronts per CU aimed at by the fused second sweep of the update
 };
 
 // Device scratch layout (one allocation per context).
@@ -135,10 +136,14 @@ void launch_diag_apply(fosi_ctx* ctx, const float* d, const float* v, float* out
 void launch_ritz_vectors(fosi_ctx* ctx, const float* Q, int64_t ldq, int m, const float* S_dev, int rv_pad,
                          int rv, float* V, int64_t ldv, int64_t n);
 void launch_step_coefficients(fosi_ctx* ctx, int rv, double lr);
-// AdamW base optimiser: moments + descent vector o (second sweep), and d = newton . c + e for the last sweep
-void launch_adamw_moments(fosi_ctx* ctx, const float* V, int64_t ldv, int rv, const double* c, const float* g,
-                          const float* pi, const float* w, float* m, float* v, float* o_out, int64_t n, double b1,
-                          double b2, double inv_bc1, double inv_bc2, double eps, double lr, double wd);
+// Second sweep of the update fused with the transposed product of its result: x = g (+ pi) - V c, base optimiser
+// (opt 0: heavy ball on m with factor mu; opt 1: AdamW on m, v with decay against w, descent vector to o_out),
+// e_out[j] = sum_rows V[row, j] z[row] with z the new momentum (opt 0) or the descent vector (opt 1).
+void launch_complement_reproject(fosi_ctx* ctx, int opt, const float* V, int64_t ldv, int rv, const double* c,
+                                 const float* g, const float* pi, const float* w, float* m, float* v, float* o_out,
+                                 int64_t n, double mu, double b1, double b2, double inv_bc1, double inv_bc2, double eps,
+                                 double lr, double wd, double* e_out);
+// d = newton . c + e for the last sweep of the AdamW variant
 void launch_step_coefficients_plus(fosi_ctx* ctx, int rv);
 void launch_admm_begin(fosi_ctx* ctx, int64_t n, double inv_sigma, const float* pi, float* anchor, float* wa);
 void launch_admm_end(fosi_ctx* ctx, int64_t n, double sigma, const float* anchor, const float* wa, float* pi);

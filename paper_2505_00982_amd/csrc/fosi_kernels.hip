@@ -395,75 +395,187 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
     }
 }
 
-// AdamW as the base optimiser of Eq. 12 / Eq. 14, second sweep of the update:
-//   x = g (+ pi) - V c ;  m <- b1 m + (1-b1) x ;  v <- b2 v + (1-b2) x^2 ;
-//   o = -lr ( (m / bc1) / (sqrt(v / bc2) + eps) + wd w )        (bc1, bc2: bias corrections of step t)
-// m, v are updated in place, o (the optimiser's descent vector, before re-projection) is written out.
-struct AdamwScalars {
-    double b1, b2, inv_bc1, inv_bc2, eps, lr, wd;
+// ------------------------------------------------- complement + base optimiser + re-projection
+// Second sweep of the update (Eq. 12 / Eq. 14), fused with the transposed product that the last sweep
+// needs, so that V is streamed three times per update and not four:
+//   x = g (+ pi) - V c                         (c = V^T (g + pi) from the first sweep)
+//   heavy ball (OPT == 0):  b <- mu b + x ;                               z = b
+//   AdamW      (OPT == 1):  m <- b1 m + (1-b1) x ;  v <- b2 v + (1-b2) x^2 ;
+//                           o = -lr ( (m / bc1) / (sqrt(v / bc2) + eps) + wd w ) ;   z = o
+//   e_j = sum_rows V[row, j] z[row]            (z as stored, i.e. rounded to fp32)
+// A row of z needs every column of that row, and e_j needs that z again.  The S waves of a block
+// therefore share one tile of 64 float4 row groups and split the columns: wave s keeps its (at most
+// MAXC) columns of the tile in registers, the partial sums of V c are exchanged through LDS (added in a
+// fixed order, so all waves hold identical values), every wave evaluates the optimiser for the tile and
+// wave 0 stores its state, then each wave accumulates the e_j of its own columns from the registers.
+// partials[block * pstride + j] receives the block's part of e_j.
+struct OptScalars {
+    double mu;                                   // heavy ball
+    double b1, b2, inv_bc1, inv_bc2, eps, lr, wd;   // AdamW (bc1, bc2: bias corrections of this step)
 };
 
-template <bool HAS_PI, int RPT, int CU>
-__global__ __launch_bounds__(kThreads) void k_adamw_moments(
-    const float* __restrict__ V, int64_t ldv, int ncols, const double* __restrict__ c, const float* __restrict__ g,
-    const float* __restrict__ pi, const float* __restrict__ w, float* m, float* v, float* __restrict__ o_out, int64_t n,
-    AdamwScalars p) {
-    const int tid = threadIdx.x;
+// The optimiser state of a row is read by every wave of the block and overwritten by wave 0: the reads
+// must have returned before the block's barrier.  An empty volatile statement that consumes the loaded
+// value cannot move across the barrier and forces the wait in front of it.
+__device__ __forceinline__ void consume_before_barrier(float v) { asm volatile("" : : "v"(v)); }
+
+template <int OPT>
+__device__ __forceinline__ float optimiser_row(const OptScalars& p, double x, double w_, float& m_, float& v_) {
+    if (OPT == 0) {
+        m_ = (float)fma(p.mu, (double)m_, x);
+        return m_;
+    }
+    const double mn = p.b1 * (double)m_ + (1.0 - p.b1) * x;
+    const double vn = p.b2 * (double)v_ + (1.0 - p.b2) * x * x;
+    m_ = (float)mn;
+    v_ = (float)vn;
+    return (float)(-p.lr * ((mn * p.inv_bc1) / (sqrt(vn * p.inv_bc2) + p.eps) + p.wd * w_));
+}
+
+// All waves of a block run the same width NCOL >= cw (columns per wave); positions past a wave's last
+// real column re-read that column (cache hits) and are discarded.  pi may be null.
+template <int OPT, int NCOL>
+__global__ __launch_bounds__(512) void k_complement_reproject(
+    const float* __restrict__ V, int64_t ldv, int ncols, int cw, const double* __restrict__ c,
+    const float* __restrict__ g, const float* __restrict__ pi, const float* __restrict__ w, float* m, float* v,
+    float* __restrict__ o_out, int64_t n, OptScalars p, double* __restrict__ partials, int pstride) {
+    extern __shared__ double exch[];             // [2][S][4][64]: partial sums of V c, double buffered
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int S = (int)(blockDim.x >> 6);
+    const int j0 = wave * cw;                    // this wave's columns: [j0, j0 + nc), nc >= 1 unless ncols == 0
+    const int nc = max(0, min(cw, ncols - j0));
+    const float* Vj0 = V + (int64_t)j0 * ldv;
     const int64_t n4 = n >> 2;
-    const int64_t tile = (int64_t)kThreads * RPT;
-    const int64_t ntiles = (n4 + tile - 1) / tile;
-    auto one = [&](double x, double w_, float& m_, float& v_) -> float {
-        const double mn = p.b1 * (double)m_ + (1.0 - p.b1) * x;
-        const double vn = p.b2 * (double)v_ + (1.0 - p.b2) * x * x;
-        m_ = (float)mn;
-        v_ = (float)vn;
-        return (float)(-p.lr * ((mn * p.inv_bc1) / (sqrt(vn * p.inv_bc2) + p.eps) + p.wd * w_));
-    };
+    const int64_t ntiles = (n4 + 63) >> 6;
+    const bool has_pi = pi != nullptr;
+
+    double acc[NCOL];
+    double cj[NCOL];                             // this wave's coefficients (uniform), zero for the padding
+#pragma unroll
+    for (int j = 0; j < NCOL; ++j) {
+        acc[j] = 0.0;
+        cj[j] = j < nc ? c[j0 + j] : 0.0;
+    }
+    int par = 0;
+
     for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        int64_t r4[RPT], rc[RPT];
-#pragma unroll
-        for (int q = 0; q < RPT; ++q) {
-            r4[q] = t * tile + (int64_t)q * kThreads + tid;
-            rc[q] = r4[q] < n4 ? r4[q] : n4 - 1;
+        // everything but `lane` is uniform: tile base in scalar registers, one 32-bit lane offset for all loads
+        const int64_t base = t << 8;             // first row of the tile
+        const int64_t rem = n4 - (t << 6);       // row groups left (> 0)
+        const bool ok = lane < rem;              // ragged last tile: other lanes re-read its last group, add zeros
+        const uint32_t lane_bytes = (uint32_t)(ok ? lane : (int)(rem < 64 ? rem : 64) - 1) << 4;
+        auto vec4 = [&](const float* x) {
+            return *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(x + base) + lane_bytes);
+        };
+        const float4 pg = vec4(g);
+        float4 pp = make_float4(0.f, 0.f, 0.f, 0.f), pw = pp, pv = pp;
+        if (has_pi) pp = vec4(pi);
+        float4 pm = vec4(m);
+        if (OPT == 1) {
+            pw = vec4(w);
+            pv = vec4(v);
         }
-        float4 pg[RPT], pp[RPT], pw[RPT], pm[RPT], pv[RPT];
+        float4 a[NCOL];
+        const float* Vt = Vj0 + base;
+        if (nc > 0) {                            // uniform; with no columns at all (ncols == 0) V may be null
 #pragma unroll
-        for (int q = 0; q < RPT; ++q) {
-            pg[q] = reinterpret_cast<const float4*>(g)[rc[q]];
-            if (HAS_PI) pp[q] = reinterpret_cast<const float4*>(pi)[rc[q]];
-            pw[q] = reinterpret_cast<const float4*>(w)[rc[q]];
-            pm[q] = reinterpret_cast<const float4*>(m)[rc[q]];
-            pv[q] = reinterpret_cast<const float4*>(v)[rc[q]];
+            for (int j = 0; j < NCOL; ++j) {
+                const int col = j < nc ? j : nc - 1;
+                a[j] = load_stream4(reinterpret_cast<const float*>(
+                    reinterpret_cast<const char*>(Vt + (int64_t)col * ldv) + lane_bytes));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NCOL; ++j) a[j] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        double s[RPT][4];
-        accumulate_columns<RPT, CU>(V, ldv, ncols, c, rc, s);
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
 #pragma unroll
-        for (int q = 0; q < RPT; ++q) {
-            if (r4[q] >= n4) continue;
-            double x0 = (double)pg[q].x - s[q][0], x1 = (double)pg[q].y - s[q][1];
-            double x2 = (double)pg[q].z - s[q][2], x3 = (double)pg[q].w - s[q][3];
-            if (HAS_PI) { x0 += (double)pp[q].x; x1 += (double)pp[q].y; x2 += (double)pp[q].z; x3 += (double)pp[q].w; }
-            float4 mm = pm[q], vv = pv[q], oo;
-            oo.x = one(x0, (double)pw[q].x, mm.x, vv.x);
-            oo.y = one(x1, (double)pw[q].y, mm.y, vv.y);
-            oo.z = one(x2, (double)pw[q].z, mm.z, vv.z);
-            oo.w = one(x3, (double)pw[q].w, mm.w, vv.w);
-            reinterpret_cast<float4*>(m)[r4[q]] = mm;
-            reinterpret_cast<float4*>(v)[r4[q]] = vv;
-            store_stream4(o_out + (r4[q] << 2), oo);
+        for (int j = 0; j < NCOL; ++j) {
+            s0 = fma((double)a[j].x, cj[j], s0); s1 = fma((double)a[j].y, cj[j], s1);
+            s2 = fma((double)a[j].z, cj[j], s2); s3 = fma((double)a[j].w, cj[j], s3);
+        }
+        // keep the tile as fp32 across the exchange: without this the compiler holds the fp64 conversions of
+        // all columns (twice the registers) for the second use below
+#pragma unroll
+        for (int j = 0; j < NCOL; ++j)
+            asm volatile("" : "+v"(a[j].x), "+v"(a[j].y), "+v"(a[j].z), "+v"(a[j].w));
+        if (S > 1) {
+            double* mine = exch + (((par * S + wave) << 2) << 6) + lane;
+            mine[0] = s0; mine[64] = s1; mine[128] = s2; mine[192] = s3;
+            consume_before_barrier(pm.x);
+            if (OPT == 1) consume_before_barrier(pv.x);
+            __syncthreads();
+            s0 = s1 = s2 = s3 = 0.0;
+            for (int q = 0; q < S; ++q) {
+                const double* o = exch + (((par * S + q) << 2) << 6) + lane;
+                s0 += o[0]; s1 += o[64]; s2 += o[128]; s3 += o[192];
+            }
+            par ^= 1;                            // the next tile writes the other half: one barrier per tile suffices
+        }
+        double x0 = (double)pg.x - s0, x1 = (double)pg.y - s1, x2 = (double)pg.z - s2, x3 = (double)pg.w - s3;
+        if (has_pi) { x0 += (double)pp.x; x1 += (double)pp.y; x2 += (double)pp.z; x3 += (double)pp.w; }
+        float4 z;
+        z.x = optimiser_row<OPT>(p, x0, (double)pw.x, pm.x, pv.x);
+        z.y = optimiser_row<OPT>(p, x1, (double)pw.y, pm.y, pv.y);
+        z.z = optimiser_row<OPT>(p, x2, (double)pw.z, pm.z, pv.z);
+        z.w = optimiser_row<OPT>(p, x3, (double)pw.w, pm.w, pv.w);
+        if (wave == 0 && ok) {
+            float* mo = reinterpret_cast<float*>(reinterpret_cast<char*>(m + base) + lane_bytes);
+            if (OPT == 0) {
+                store_stream4(mo, pm);
+            } else {
+                *reinterpret_cast<float4*>(mo) = pm;
+                *reinterpret_cast<float4*>(reinterpret_cast<char*>(v + base) + lane_bytes) = pv;
+                store_stream4(reinterpret_cast<float*>(reinterpret_cast<char*>(o_out + base) + lane_bytes), z);
+            }
+        }
+        const double z0 = ok ? (double)z.x : 0.0, z1 = ok ? (double)z.y : 0.0;
+        const double z2 = ok ? (double)z.z : 0.0, z3 = ok ? (double)z.w : 0.0;
+#pragma unroll
+        for (int j = 0; j < NCOL; ++j)
+            acc[j] = fma((double)a[j].x, z0, fma((double)a[j].y, z1, fma((double)a[j].z, z2,
+                     fma((double)a[j].w, z3, acc[j]))));
+    }
+
+    // the last (n mod 4) rows: block 0, one row per lane; every wave evaluates them, wave 0 stores
+    if (blockIdx.x == 0) {
+        const int64_t tail_row = (n4 << 2) + lane;
+        const bool tl = lane < 3 && tail_row < n;
+        float mm = 0.f, vv = 0.f, zz = 0.f;
+        if (tl) {
+            double sacc = 0.0;
+            for (int j = 0; j < ncols; ++j) sacc = fma((double)V[(int64_t)j * ldv + tail_row], c[j], sacc);
+            double x = (double)g[tail_row] - sacc;
+            if (has_pi) x += (double)pi[tail_row];
+            mm = m[tail_row];
+            if (OPT == 1) vv = v[tail_row];
+            zz = optimiser_row<OPT>(p, x, OPT == 1 ? (double)w[tail_row] : 0.0, mm, vv);
+        }
+        if (S > 1) {
+            consume_before_barrier(zz);
+            __syncthreads();
+        }
+        if (tl) {
+            if (wave == 0) {
+                m[tail_row] = mm;
+                if (OPT == 1) { v[tail_row] = vv; o_out[tail_row] = zz; }
+            }
+#pragma unroll
+            for (int j = 0; j < NCOL; ++j)
+                if (j < nc) acc[j] = fma((double)Vj0[(int64_t)j * ldv + tail_row], (double)zz, acc[j]);
         }
     }
-    const int64_t tail_row = (n4 << 2) + tid;
-    if (blockIdx.x == 0 && tid < 3 && tail_row < n) {
-        double sacc = 0.0;
-        for (int j = 0; j < ncols; ++j) sacc = fma((double)V[(int64_t)j * ldv + tail_row], c[j], sacc);
-        double x = (double)g[tail_row] - sacc;
-        if (HAS_PI) x += (double)pi[tail_row];
-        float mm = m[tail_row], vv = v[tail_row];
-        o_out[tail_row] = one(x, (double)w[tail_row], mm, vv);
-        m[tail_row] = mm;
-        v[tail_row] = vv;
+
+    double* prow = partials + (int64_t)blockIdx.x * pstride;
+#pragma unroll
+    for (int j = 0; j < NCOL; ++j) {
+        if (j < nc) {                            // uniform test
+            const double e = wave_sum(acc[j]);
+            if (lane == 0) prow[j0 + j] = e;
+        }
     }
+    if (wave == 0 && lane == 0) prow[ncols] = 0.0;   // the reduction kernel also sums this (unused) slot
 }
 
 // d_j = newton_j c_j + e_j  (AdamW variant of the last sweep's coefficients: w += o - V d)
@@ -818,21 +930,43 @@ void launch_admm_end(fosi_ctx* ctx, int64_t n, double sigma, const float* anchor
                        pi);
 }
 
-void launch_adamw_moments(fosi_ctx* ctx, const float* V, int64_t ldv, int rv, const double* c, const float* g,
-                          const float* pi, const float* w, float* m, float* v, float* o_out, int64_t n, double b1,
-                          double b2, double inv_bc1, double inv_bc2, double eps, double lr, double wd) {
-    constexpr int RPT = 2, CU = 8;
-    const int64_t n4 = n >> 2;
-    int64_t g_ = (n4 + kThreads * RPT - 1) / (kThreads * RPT);
-    if (g_ < 1) g_ = 1;
-    if (g_ > kMaxNormSlots) g_ = kMaxNormSlots;
-    AdamwScalars p{b1, b2, inv_bc1, inv_bc2, eps, lr, wd};
-    if (pi != nullptr)
-        hipLaunchKernelGGL((k_adamw_moments<true, RPT, CU>), dim3((unsigned)g_), dim3(kThreads), 0, ctx->stream, V, ldv, rv,
-                           c, g, pi, w, m, v, o_out, n, p);
-    else
-        hipLaunchKernelGGL((k_adamw_moments<false, RPT, CU>), dim3((unsigned)g_), dim3(kThreads), 0, ctx->stream, V, ldv, rv,
-                           c, g, pi, w, m, v, o_out, n, p);
+void launch_complement_reproject(fosi_ctx* ctx, int opt, const float* V, int64_t ldv, int rv, const double* c,
+                                 const float* g, const float* pi, const float* w, float* m, float* v, float* o_out,
+                                 int64_t n, double mu, double b1, double b2, double inv_bc1, double inv_bc2, double eps,
+                                 double lr, double wd, double* e_out) {
+    // columns per wave: at most 16 up to 128 columns, at most 32 beyond; no empty wave
+    int S = (rv + 15) / 16;
+    if (S < 1) S = 1;
+    if (S > 8) S = 8;
+    const int cw = rv > 0 ? (rv + S - 1) / S : 1;
+    S = rv > 0 ? (rv + cw - 1) / cw : 1;
+    const int64_t ntiles = ((n >> 2) + 63) >> 6;
+    int64_t blocks = (int64_t)ctx->sm_count * ctx->tun.step_waves_per_cu / S;
+    if (blocks > kMaxDotSlots) blocks = kMaxDotSlots;
+    if (blocks > ntiles) blocks = ntiles;
+    if (blocks < 1) blocks = 1;
+    const size_t lds = S > 1 ? sizeof(double) * 2 * S * 4 * 64 : 0;
+    const int pstride = rv + 1;
+    OptScalars p{mu, b1, b2, inv_bc1, inv_bc2, eps, lr, wd};
+#define FOSI_CR(NCOL)                                                                                              \
+    do {                                                                                                           \
+        if (opt == 0)                                                                                              \
+            hipLaunchKernelGGL((k_complement_reproject<0, NCOL>), dim3((unsigned)blocks), dim3(64 * S), lds,        \
+                               ctx->stream, V, ldv, rv, cw, c, g, pi, w, m, v, o_out, n, p, ctx->s.partials, pstride); \
+        else                                                                                                       \
+            hipLaunchKernelGGL((k_complement_reproject<1, NCOL>), dim3((unsigned)blocks), dim3(64 * S), lds,        \
+                               ctx->stream, V, ldv, rv, cw, c, g, pi, w, m, v, o_out, n, p, ctx->s.partials, pstride); \
+    } while (0)
+    if (cw <= 4) FOSI_CR(4);
+    else if (cw <= 8) FOSI_CR(8);
+    else if (cw <= 12) FOSI_CR(12);
+    else if (cw <= 16) FOSI_CR(16);
+    else if (cw <= 24) FOSI_CR(24);
+    else FOSI_CR(32);
+#undef FOSI_CR
+    if (rv > 0)
+        hipLaunchKernelGGL(k_reduce_columns, dim3(rv + 1), dim3(64), 0, ctx->stream, ctx->s.partials, (int)blocks, pstride,
+                           e_out, (const float*)nullptr, 0, 1.0, rv, (const double*)nullptr, (const int*)nullptr);
 }
 
 void launch_step_coefficients_plus(fosi_ctx* ctx, int rv) {

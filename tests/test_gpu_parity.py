@@ -221,7 +221,10 @@ def _random_basis(n, r, seed):
     return np.linalg.qr(np.random.default_rng(seed).standard_normal((n, r)))[0].astype(np.float32)
 
 
-@pytest.mark.parametrize("n,r", [(7, 2), (1025, 0), (1025, 1), (50003, 15), (50003, 40)])
+# r = 15: one wave per block owns all columns; 30, 40: two / three waves split them; 130, 256: eight waves, wide slots;
+# n = 3: only the scalar tail rows exist
+@pytest.mark.parametrize("n,r", [(3, 2), (7, 2), (1025, 0), (1025, 1), (50003, 15), (70001, 30), (50003, 40), (20010, 130),
+                                 (9999, 256)])
 @pytest.mark.parametrize("with_pi", [False, True])
 def test_update_step_against_oracle(fo, ctx, n, r, with_pi):
     rng = np.random.default_rng(n + r)
@@ -243,7 +246,7 @@ def test_update_step_against_oracle(fo, ctx, n, r, with_pi):
     assert rel_l2(md.cpu().numpy(), b_ref) <= STEP_RTOL
 
 
-@pytest.mark.parametrize("n,r", [(5, 1), (1025, 0), (50003, 15)])
+@pytest.mark.parametrize("n,r", [(5, 1), (1025, 0), (50003, 15), (50003, 40), (9999, 200)])
 @pytest.mark.parametrize("with_pi", [False, True])
 def test_adamw_update_against_oracle(fo, ctx, n, r, with_pi):
     rng = np.random.default_rng(100 + n + r)
