@@ -121,6 +121,20 @@ fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q
                          double* alpha_host, double* beta_host, int32_t* m_eff,
                          const fosi_lanczos_opts* opts);
 
+/* Algorithm 2 (row-sharded Lanczos) emulated on one GPU: the n rows are cut into `shards` contiguous
+ * blocks ("virtual devices", boundaries at multiples of 64 rows).  Every sweep runs once per block on
+ * that block's rows of Q (and of U for the planted operator) and leaves its partial sums in one row of
+ * an exchange buffer; a separate small kernel adds the rows in rank order -- the place an all-reduce
+ * takes in the distributed algorithm -- and every block continues from the summed values.  Operators
+ * other than the planted one are applied to the whole vector (the algorithm's all-gather of v_i is the
+ * identity when all blocks live in one memory).  Same arguments, outputs and error behaviour as
+ * fosi_lanczos; 1 <= shards <= FOSI_MAX_SHARDS.  Results agree with fosi_lanczos up to the summation
+ * order of the partial sums.  Meant for validating the sharded scheme, not for speed. */
+#define FOSI_MAX_SHARDS 64
+fosi_status fosi_lanczos_row_sharded(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, int shards, float* Q_dev,
+                                     int64_t ldq, double* alpha_host, double* beta_host, int32_t* m_eff,
+                                     const fosi_lanczos_opts* opts);
+
 /* ---- Eq. 8: Ritz extraction ------------------------------------------------ */
 
 /* Host-only helper: eigen-decomposition of the symmetric tridiagonal matrix

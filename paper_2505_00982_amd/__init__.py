@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     ColMajor,
     StepParams,
     fosi_lanczos,
+    fosi_lanczos_row_sharded,
     fosi_lanczos_steps,
     REORTH_SINGLE,
     REORTH_TWICE,

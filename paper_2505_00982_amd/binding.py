@@ -26,7 +26,7 @@ PROF = {"hvp_project": 0, "hvp_expand": 1, "reorth_dot": 2, "reorth_sub": 3, "no
 EXPORTS = [
     "fosi_ctx_create", "fosi_ctx_destroy", "fosi_ctx_synchronize", "fosi_last_error", "fosi_status_string",
     "hvp_planted_create", "hvp_diag_create", "hvp_softmax_ggn_create", "hvp_callback_create", "hvp_apply",
-    "hvp_destroy", "fosi_lanczos", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_step_adamw", "fosi_admm_begin",
+    "hvp_destroy", "fosi_lanczos", "fosi_lanczos_row_sharded", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_step_adamw", "fosi_admm_begin",
     "fosi_admm_end", "fosi_profile_enable", "fosi_profile_reset", "fosi_profile_read",
 ]
 
@@ -82,6 +82,8 @@ def load_library() -> C.CDLL:
     lib.hvp_apply.argtypes = [vp, vp, vp]
     lib.hvp_destroy.argtypes = [vp]
     lib.fosi_lanczos.argtypes = [vp, vp, i64, C.c_int, vp, i64, dp, dp, C.POINTER(i32), C.POINTER(_LanczosOpts)]
+    lib.fosi_lanczos_row_sharded.argtypes = [vp, vp, i64, C.c_int, C.c_int, vp, i64, dp, dp, C.POINTER(i32),
+                                             C.POINTER(_LanczosOpts)]
     lib.fosi_lanczos_steps.argtypes = [i64, C.c_int, C.c_int]
     lib.fosi_tridiag_eigh.argtypes = [C.c_int, dp, dp, dp, dp]
     lib.fosi_ritz.argtypes = [vp, i64, C.c_int, vp, i64, dp, dp, C.c_int, C.c_int, vp, i64, dp, dp]
@@ -252,6 +254,17 @@ def fosi_lanczos(ctx: Context, op: Hvp, Q: ColMajor, m: int, reorth_mode: int = 
     opts = _LanczosOpts(reorth_mode, breakdown_tol)
     ctx.check(ctx.lib.fosi_lanczos(ctx.handle, op.handle, Q.n, m, Q.ptr, Q.ld, _dptr(alpha), _dptr(beta),
                                    C.byref(m_eff), C.byref(opts)))
+    return alpha, beta, int(m_eff.value)
+
+
+def fosi_lanczos_row_sharded(ctx: Context, op: Hvp, Q: ColMajor, m: int, shards: int, reorth_mode: int = 0,
+                             breakdown_tol: float = 1e-6) -> Tuple[np.ndarray, np.ndarray, int]:
+    """Algorithm 2 emulated on one GPU with `shards` row blocks.  Same contract as fosi_lanczos."""
+    alpha, beta = np.zeros(m), np.zeros(m)
+    m_eff = C.c_int32(0)
+    opts = _LanczosOpts(reorth_mode, breakdown_tol)
+    ctx.check(ctx.lib.fosi_lanczos_row_sharded(ctx.handle, op.handle, Q.n, m, shards, Q.ptr, Q.ld, _dptr(alpha),
+                                               _dptr(beta), C.byref(m_eff), C.byref(opts)))
     return alpha, beta, int(m_eff.value)
 
 

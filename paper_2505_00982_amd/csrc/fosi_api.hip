@@ -130,6 +130,7 @@ fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
     const size_t o_hn = take(sizeof(double) * kMaxCols), o_nw = take(sizeof(double) * kMaxCols);
     const size_t o_S = take(sizeof(float) * kMaxCols * kMaxCols);
     const size_t o_fl = take(sizeof(int) * 8);
+    const size_t o_x = take(sizeof(double) * kMaxShards * cols1), o_x3 = take(sizeof(double) * kMaxShards * 3);
     if (hipMalloc(&ctx->scratch_base, off) != hipSuccess) {
         delete ctx;
         return FOSI_ERR_NOMEM;
@@ -149,6 +150,8 @@ fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
     ctx->s.newton = reinterpret_cast<double*>(b + o_nw);
     ctx->s.S = reinterpret_cast<float*>(b + o_S);
     ctx->s.flags = reinterpret_cast<int*>(b + o_fl);
+    ctx->s.xchg = reinterpret_cast<double*>(b + o_x);
+    ctx->s.xchg3 = reinterpret_cast<double*>(b + o_x3);
     const double ones[2] = {1.0, 1.0};
     if (hipMemsetAsync(ctx->scratch_base, 0, off, ctx->stream) != hipSuccess ||
         hipMemcpyAsync(ctx->s.scal + 2, ones, sizeof(ones), hipMemcpyHostToDevice, ctx->stream) != hipSuccess ||
@@ -413,6 +416,159 @@ fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q
                                   "copy flags")) return s;
     if (fosi_status s = check_hip(ctx, hipStreamSynchronize(ctx->stream), "lanczos synchronize")) return s;
     // leave the stop flag clear so that later operator applications run
+    if (fosi_status s = check_hip(ctx, hipMemsetAsync(flags, 0, 8 * sizeof(int), ctx->stream), "clear flags")) return s;
+    *m_eff = hflags[1];
+    if (hflags[0] == 2) return fail(ctx, FOSI_ERR_NONFINITE, "non-finite value in the Lanczos recurrence");
+    return FOSI_OK;
+}
+
+/* ------------------------------------------------- Algorithm 2 on one GPU */
+
+struct Shards {
+    int count = 0;
+    int64_t begin[kMaxShards + 1] = {0};
+    int64_t rows(int c) const { return begin[c + 1] - begin[c]; }
+};
+
+// Contiguous row blocks with boundaries at multiples of 64 rows (so that every block starts 256-byte
+// aligned); blocks that would be empty are dropped.
+static Shards make_shards(int64_t n, int want) {
+    Shards sh;
+    const int64_t per = ((n + want - 1) / want + 63) / 64 * 64;
+    int64_t s = 0;
+    while (s < n && sh.count < want) {
+        sh.begin[sh.count] = s;
+        s = s + per < n ? s + per : n;
+        sh.begin[++sh.count] = s;
+    }
+    return sh;
+}
+
+// c = A^T (x [+ xs0 x2 + xs1 x3]) with the rows cut into blocks: one sweep per block into its row of the
+// exchange buffer, then the sum over blocks (where the distributed algorithm has its all-reduce).
+static void sharded_dot(fosi_ctx* ctx, const Shards& sh, const float* A, int64_t lda, int ncols, const float* x,
+                 const float* x2, const float* x3, const double* xs, double* coef, const float* scale, int nscale,
+                 const double* add_last2, const int* stop, int prof_cls) {
+    for (int c = 0; c < sh.count; ++c) {
+        const int64_t o = sh.begin[c], nr = sh.rows(c);
+        const int nx = 1 + (x2 != nullptr) + (x3 != nullptr);
+        launch_dot_columns(ctx, A != nullptr ? A + o : nullptr, lda, ncols, x + o, x2 != nullptr ? x2 + o : nullptr,
+                           x3 != nullptr ? x3 + o : nullptr, xs, nr, ctx->s.xchg + (size_t)c * (kMaxCols + 1), nullptr, 0,
+                           1.0, nullptr, stop, prof_cls, (ncols + nx) * kVec * (double)nr);
+    }
+    launch_reduce_shards(ctx, sh.count, ncols, coef, scale, nscale, 1.0, add_last2, stop);
+}
+
+// h <- h - Q c on every block; the blocks' parts of ||h||^2 go to xchg3[c].
+static void sharded_subtract(fosi_ctx* ctx, const Shards& sh, const float* Q, int64_t ldq, int ncols, const double* coef,
+                      float* h, const int* stop) {
+    for (int c = 0; c < sh.count; ++c) {
+        const int64_t o = sh.begin[c], nr = sh.rows(c);
+        const int slots = launch_combine_columns(ctx, Q + o, ldq, ncols, coef, h + o, 1.0, nullptr, 0.0, nullptr, 0.0,
+                                                 nullptr, false, -1.0, h + o, nr, true, stop, FOSI_PROF_REORTH_SUB,
+                                                 (ncols + 2) * kVec * (double)nr);
+        launch_fold_partials(ctx, slots, 1, ctx->s.xchg3 + c, stop);
+    }
+}
+
+static fosi_status sharded_operator(fosi_hvp* op, const Shards& sh, const float* v, float* hv, const float* vprev,
+                             bool want_local) {
+    fosi_ctx* ctx = op->ctx;
+    const int* stop = ctx->s.flags;
+    if (op->kind == fosi_hvp::PLANTED) {
+        sharded_dot(ctx, sh, op->U, op->ldu, op->r, v, nullptr, nullptr, nullptr, ctx->s.coef_h, op->lam, op->r, nullptr,
+                    stop, FOSI_PROF_HVP_PROJECT);
+        for (int c = 0; c < sh.count; ++c) {
+            const int64_t o = sh.begin[c], nr = sh.rows(c);
+            const int extra = (want_local && vprev != nullptr) ? 1 : 0;
+            const int slots = launch_combine_columns(ctx, op->U + o, op->ldu, op->r, ctx->s.coef_h, nullptr, 0.0, v + o,
+                                                     (double)op->shift, nullptr, 0.0, vprev != nullptr ? vprev + o : nullptr,
+                                                     want_local, 1.0, hv + o, nr, false, stop, FOSI_PROF_HVP_EXPAND,
+                                                     (op->r + 2 + extra) * kVec * (double)nr);
+            if (want_local) launch_fold_partials(ctx, slots, 3, ctx->s.xchg3 + 3 * c, stop);
+        }
+        if (want_local) launch_reduce_local(ctx, sh.count, stop, ctx->s.xchg3);
+        return launch_status(ctx, "sharded hvp");
+    }
+    // other operators see the whole vector; only the local products are taken block by block
+    if (fosi_status s = apply_operator(op, v, hv, nullptr, false)) return s;
+    if (want_local) {
+        const int nc = vprev != nullptr ? 2 : 1;
+        const float* base = vprev != nullptr ? vprev : v;
+        const int64_t ld = vprev != nullptr ? (int64_t)(v - vprev) : 0;
+        sharded_dot(ctx, sh, base, ld, nc, hv, nullptr, nullptr, nullptr, ctx->s.coef_a, nullptr, 0, nullptr, stop,
+                    FOSI_PROF_REORTH_DOT);
+        launch_local_from_coef(ctx, ctx->s.coef_a, nc, stop);
+    }
+    return launch_status(ctx, "sharded hvp");
+}
+
+fosi_status fosi_lanczos_row_sharded(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, int shards, float* Q_dev,
+                                     int64_t ldq, double* alpha_host, double* beta_host, int32_t* m_eff,
+                                     const fosi_lanczos_opts* opts) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (op == nullptr || alpha_host == nullptr || beta_host == nullptr || m_eff == nullptr)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "null argument");
+    if (op->ctx != ctx) return fail(ctx, FOSI_ERR_INVALID_ARG, "operator belongs to another context");
+    if (n < 1 || m < 1) return fail(ctx, FOSI_ERR_INVALID_ARG, "n and m must be positive");
+    if (shards < 1) return fail(ctx, FOSI_ERR_INVALID_ARG, "shards must be positive");
+    if (shards > kMaxShards) return fail(ctx, FOSI_ERR_LIMIT, "shards exceeds FOSI_MAX_SHARDS");
+    if (op->n != n) return fail(ctx, FOSI_ERR_INVALID_ARG, "operator size differs from n");
+    if (m + 1 > kMaxCols) return fail(ctx, FOSI_ERR_LIMIT, "m + 1 exceeds FOSI_MAX_COLS");
+    if (fosi_status s = check_matrix(ctx, "Q_dev", Q_dev, n, ldq, m + 1)) return s;
+    int mode = FOSI_REORTH_LOCAL_FULL;
+    double tol = 1e-6;
+    if (opts != nullptr) {
+        if (opts->reorth_mode != 0) mode = opts->reorth_mode;
+        if (opts->breakdown_tol > 0.0) tol = opts->breakdown_tol;
+    }
+    if (mode != FOSI_REORTH_SINGLE && mode != FOSI_REORTH_TWICE && mode != FOSI_REORTH_LOCAL_FULL)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "unknown reorth_mode");
+    const int passes = mode == FOSI_REORTH_SINGLE ? 1 : 2;
+    *m_eff = 0;
+    const Shards sh = make_shards(n, shards);
+    int* flags = ctx->s.flags;
+    if (fosi_status s = check_hip(ctx, hipMemsetAsync(flags, 0, 8 * sizeof(int), ctx->stream), "clear flags")) return s;
+
+    // first column: every block scales its rows by the same 1 / ||v||
+    sharded_dot(ctx, sh, nullptr, 0, 0, Q_dev, nullptr, nullptr, nullptr, ctx->s.coef_a, nullptr, 0, nullptr, nullptr, -1);
+    launch_inv_sqrt(ctx, ctx->s.coef_a, ctx->s.scal + 1);
+    for (int c = 0; c < sh.count; ++c) launch_scale(ctx, Q_dev + sh.begin[c], ctx->s.scal + 1, sh.rows(c), nullptr);
+
+    for (int i = 0; i < m; ++i) {
+        const float* q = Q_dev + (int64_t)i * ldq;
+        float* h = Q_dev + (int64_t)(i + 1) * ldq;
+        const int ncols = i + 1;
+        if (mode == FOSI_REORTH_LOCAL_FULL) {
+            const float* qprev = i > 0 ? q - ldq : nullptr;
+            if (fosi_status s = sharded_operator(op, sh, q, h, qprev, true)) return s;
+            sharded_dot(ctx, sh, Q_dev, ldq, ncols, h, q, qprev, ctx->s.scal + 4, ctx->s.coef_b, nullptr, 0, ctx->s.loc,
+                        flags, FOSI_PROF_REORTH_DOT);
+            sharded_subtract(ctx, sh, Q_dev, ldq, ncols, ctx->s.coef_b, h, flags);
+            launch_lanczos_finalize(ctx, i, sh.count, ctx->s.coef_b, ncols, nullptr, 0, ctx->s.loc + 2, tol, ctx->s.xchg3);
+        } else {
+            if (fosi_status s = sharded_operator(op, sh, q, h, nullptr, false)) return s;
+            double* coef[2] = {ctx->s.coef_a, ctx->s.coef_b};
+            for (int p = 0; p < passes; ++p) {
+                sharded_dot(ctx, sh, Q_dev, ldq, ncols, h, nullptr, nullptr, nullptr, coef[p], nullptr, 0, nullptr, flags,
+                            FOSI_PROF_REORTH_DOT);
+                sharded_subtract(ctx, sh, Q_dev, ldq, ncols, coef[p], h, flags);
+            }
+            launch_lanczos_finalize(ctx, i, sh.count, ctx->s.coef_a, ncols, passes == 2 ? ctx->s.coef_b : nullptr,
+                                    passes == 2 ? ncols : 0, nullptr, tol, ctx->s.xchg3);
+        }
+        for (int c = 0; c < sh.count; ++c) launch_scale(ctx, h + sh.begin[c], ctx->s.scal, sh.rows(c), flags);
+        if (fosi_status s = launch_status(ctx, "sharded lanczos step")) return s;
+    }
+
+    int hflags[2] = {0, 0};
+    if (fosi_status s = check_hip(ctx, hipMemcpyAsync(alpha_host, ctx->s.alpha, sizeof(double) * m, hipMemcpyDeviceToHost,
+                                                      ctx->stream), "copy alpha")) return s;
+    if (fosi_status s = check_hip(ctx, hipMemcpyAsync(beta_host, ctx->s.beta, sizeof(double) * m, hipMemcpyDeviceToHost,
+                                                      ctx->stream), "copy beta")) return s;
+    if (fosi_status s = check_hip(ctx, hipMemcpyAsync(hflags, flags, sizeof(hflags), hipMemcpyDeviceToHost, ctx->stream),
+                                  "copy flags")) return s;
+    if (fosi_status s = check_hip(ctx, hipStreamSynchronize(ctx->stream), "lanczos synchronize")) return s;
     if (fosi_status s = check_hip(ctx, hipMemsetAsync(flags, 0, 8 * sizeof(int), ctx->stream), "clear flags")) return s;
     *m_eff = hflags[1];
     if (hflags[0] == 2) return fail(ctx, FOSI_ERR_NONFINITE, "non-finite value in the Lanczos recurrence");

@@ -15,6 +15,7 @@ namespace fosi {
 constexpr int kThreads = 256;          // every streaming kernel uses 4 wavefronts of 64 lanes
 constexpr int kMaxCols = FOSI_MAX_COLS;
 constexpr int kMaxDotSlots = 4096;     // row slots (gridDim.x) of the transposed product
+constexpr int kMaxShards = FOSI_MAX_SHARDS;
 constexpr int kMaxNormSlots = 32768;   // blocks of the column-combination kernel that emit ||.||^2 partials
 
 struct ProfRecord {
@@ -48,6 +49,8 @@ struct Scratch {
     double* newton;        // kMaxCols: alpha / (a_j + sigma)
     float* S;              // kMaxCols x kMaxCols Ritz coefficient block
     int* flags;            // [0] stop flag (1 = breakdown, 2 = non-finite), [1] completed steps
+    double* xchg;          // kMaxShards x (kMaxCols + 1): per-shard coefficient partials (row-sharded emulation)
+    double* xchg3;         // kMaxShards x 3: per-shard {||.||^2, local dots}
 };
 
 }  // namespace fosi
@@ -124,11 +127,19 @@ int launch_combine_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols
 
 // cols_a / cols_b: number of columns of the first / second Gram-Schmidt pass (cols_b == 0: single pass);
 // in both the current Lanczos vector is the last column of the range.
+// norm_parts == null: the partial sums the last column-combination kernel left in ctx->s.norm_partials.
 void launch_lanczos_finalize(fosi_ctx* ctx, int step, int norm_slots, const double* coef_a, int cols_a,
-                             const double* coef_b, int cols_b, const double* hh, double tol);
+                             const double* coef_b, int cols_b, const double* hh, double tol,
+                             const double* norm_parts = nullptr);
 // local_dots variant of launch_combine_columns leaves {out^2, out.x1, out.x3} partials (3 per block);
 // this sums them into ctx->s.loc = {alpha~, beta~, ||h||^2} and ctx->s.scal[4..5] = {-alpha~, -beta~}.
-void launch_reduce_local(fosi_ctx* ctx, int nslots, const int* stop);
+void launch_reduce_local(fosi_ctx* ctx, int nslots, const int* stop, const double* parts = nullptr);
+// Row-sharded emulation: dst[0..width) = sums over the nslots x width partials in ctx->s.norm_partials.
+void launch_fold_partials(fosi_ctx* ctx, int nslots, int width, double* dst, const int* stop);
+// ... and the sum over shards of the coefficient rows in ctx->s.xchg (the emulated all-reduce), with the
+// post-processing of launch_dot_columns (per-column scale, gscale, add_last2).
+void launch_reduce_shards(fosi_ctx* ctx, int shards, int ncols, double* coef, const float* scale, int nscale,
+                          double gscale, const double* add_last2, const int* stop);
 void launch_local_from_coef(fosi_ctx* ctx, const double* coef, int nc, const int* stop);
 void launch_inv_sqrt(fosi_ctx* ctx, const double* in, double* out);
 void launch_scale(fosi_ctx* ctx, float* x, const double* factor, int64_t n, const int* stop);

@@ -637,6 +637,19 @@ __global__ __launch_bounds__(kThreads) void k_reduce_local(const double* __restr
     }
 }
 
+// dst[w] = sum over slots of parts[slot * width + w], w < width <= 3 (fixed order).
+__global__ __launch_bounds__(kThreads) void k_fold_partials(const double* __restrict__ parts, int nslots, int width,
+                                                            double* __restrict__ dst, const int* __restrict__ stop) {
+    if (stop != nullptr && *stop != 0) return;
+    __shared__ double red[4];
+    for (int w = 0; w < width; ++w) {
+        double s = 0.0;
+        for (int i = threadIdx.x; i < nslots; i += kThreads) s += parts[(int64_t)i * width + w];
+        s = block_sum(s, red);
+        if (threadIdx.x == 0) dst[w] = s;
+    }
+}
+
 // Same outputs from a transposed product against [q_{i-1}, q_i] (nc == 2) or [q_i] (nc == 1).
 __global__ void k_local_from_coef(const double* __restrict__ coef, int nc, double* __restrict__ loc,
                                   double* __restrict__ neg, const int* __restrict__ stop) {
@@ -871,15 +884,27 @@ int launch_combine_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols
 }
 
 void launch_lanczos_finalize(fosi_ctx* ctx, int step, int norm_slots, const double* coef_a, int cols_a,
-                             const double* coef_b, int cols_b, const double* hh, double tol) {
-    hipLaunchKernelGGL(k_lanczos_finalize, dim3(1), dim3(kThreads), 0, ctx->stream, ctx->s.norm_partials, norm_slots,
+                             const double* coef_b, int cols_b, const double* hh, double tol, const double* norm_parts) {
+    hipLaunchKernelGGL(k_lanczos_finalize, dim3(1), dim3(kThreads), 0, ctx->stream,
+                       norm_parts != nullptr ? norm_parts : ctx->s.norm_partials, norm_slots,
                        coef_a, coef_b, cols_a, cols_b, hh, step, tol, ctx->s.alpha, ctx->s.beta, ctx->s.hnorm,
                        ctx->s.scal, ctx->s.flags);
 }
 
-void launch_reduce_local(fosi_ctx* ctx, int nslots, const int* stop) {
-    hipLaunchKernelGGL(k_reduce_local, dim3(1), dim3(kThreads), 0, ctx->stream, ctx->s.norm_partials, nslots,
-                       ctx->s.loc, ctx->s.scal + 4, stop);
+void launch_reduce_local(fosi_ctx* ctx, int nslots, const int* stop, const double* parts) {
+    hipLaunchKernelGGL(k_reduce_local, dim3(1), dim3(kThreads), 0, ctx->stream,
+                       parts != nullptr ? parts : ctx->s.norm_partials, nslots, ctx->s.loc, ctx->s.scal + 4, stop);
+}
+
+void launch_fold_partials(fosi_ctx* ctx, int nslots, int width, double* dst, const int* stop) {
+    hipLaunchKernelGGL(k_fold_partials, dim3(1), dim3(kThreads), 0, ctx->stream, ctx->s.norm_partials, nslots, width,
+                       dst, stop);
+}
+
+void launch_reduce_shards(fosi_ctx* ctx, int shards, int ncols, double* coef, const float* scale, int nscale,
+                          double gscale, const double* add_last2, const int* stop) {
+    hipLaunchKernelGGL(k_reduce_columns, dim3(ncols + 1), dim3(64), 0, ctx->stream, ctx->s.xchg, shards, kMaxCols + 1,
+                       coef, scale, nscale, gscale, ncols, add_last2, stop);
 }
 
 void launch_local_from_coef(fosi_ctx* ctx, const double* coef, int nc, const int* stop) {
