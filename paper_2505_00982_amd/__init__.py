@@ -16,6 +16,8 @@ from .binding import (  # noqa: F401
     REORTH_SINGLE,
     REORTH_TWICE,
     REORTH_LOCAL_FULL,
+    GRAPH_OFF,
+    GRAPH_ON,
     fosi_ritz,
     fosi_step,
     fosi_step_adamw,

@@ -26,7 +26,7 @@ PROF = {"hvp_project": 0, "hvp_expand": 1, "reorth_dot": 2, "reorth_sub": 3, "no
 EXPORTS = [
     "fosi_ctx_create", "fosi_ctx_destroy", "fosi_ctx_synchronize", "fosi_last_error", "fosi_status_string",
     "hvp_planted_create", "hvp_diag_create", "hvp_softmax_ggn_create", "hvp_callback_create", "hvp_apply",
-    "hvp_destroy", "fosi_lanczos", "fosi_lanczos_row_sharded", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_step_adamw", "fosi_admm_begin",
+    "hvp_destroy", "fosi_lanczos", "fosi_graph_stats", "fosi_lanczos_row_sharded", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_step_adamw", "fosi_admm_begin",
     "fosi_admm_end", "fosi_profile_enable", "fosi_profile_reset", "fosi_profile_read",
 ]
 
@@ -38,7 +38,7 @@ class FosiError(RuntimeError):
 
 
 class _LanczosOpts(C.Structure):
-    _fields_ = [("reorth_mode", C.c_int32), ("breakdown_tol", C.c_double)]
+    _fields_ = [("reorth_mode", C.c_int32), ("breakdown_tol", C.c_double), ("graph_mode", C.c_int32)]
 
 
 class _StepParams(C.Structure):
@@ -84,6 +84,7 @@ def load_library() -> C.CDLL:
     lib.fosi_lanczos.argtypes = [vp, vp, i64, C.c_int, vp, i64, dp, dp, C.POINTER(i32), C.POINTER(_LanczosOpts)]
     lib.fosi_lanczos_row_sharded.argtypes = [vp, vp, i64, C.c_int, C.c_int, vp, i64, dp, dp, C.POINTER(i32),
                                              C.POINTER(_LanczosOpts)]
+    lib.fosi_graph_stats.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.fosi_lanczos_steps.argtypes = [i64, C.c_int, C.c_int]
     lib.fosi_tridiag_eigh.argtypes = [C.c_int, dp, dp, dp, dp]
     lib.fosi_ritz.argtypes = [vp, i64, C.c_int, vp, i64, dp, dp, C.c_int, C.c_int, vp, i64, dp, dp]
@@ -229,6 +230,12 @@ class Context:
         self.check(self.lib.fosi_profile_read(self.handle, cls, C.byref(n), C.byref(ms), C.byref(by)))
         return n.value, ms.value, by.value
 
+    def graph_stats(self) -> Tuple[int, int]:
+        """(captures, replays) of HIP graphs by fosi_lanczos on this context."""
+        c, r = C.c_int64(), C.c_int64()
+        self.check(self.lib.fosi_graph_stats(self.handle, C.byref(c), C.byref(r)))
+        return c.value, r.value
+
 
 class Hvp:
     def __init__(self, ctx: Context, handle, n: int, keep=()):
@@ -244,14 +251,16 @@ class Hvp:
 
 
 REORTH_SINGLE, REORTH_TWICE, REORTH_LOCAL_FULL = 1, 2, 3
+GRAPH_OFF, GRAPH_ON = 0, 1
 
 
 def fosi_lanczos(ctx: Context, op: Hvp, Q: ColMajor, m: int, reorth_mode: int = 0,
-                 breakdown_tol: float = 1e-6) -> Tuple[np.ndarray, np.ndarray, int]:
-    """Q.col(0) holds the start vector.  reorth_mode 0 = library default.  Returns (alpha, beta, m_eff)."""
+                 breakdown_tol: float = 1e-6, graph_mode: int = 0) -> Tuple[np.ndarray, np.ndarray, int]:
+    """Q.col(0) holds the start vector.  reorth_mode 0 = library default; graph_mode 1 = capture the
+    run into a HIP graph and replay it (0, default: eager launches).  Returns (alpha, beta, m_eff)."""
     alpha, beta = np.zeros(m), np.zeros(m)
     m_eff = C.c_int32(0)
-    opts = _LanczosOpts(reorth_mode, breakdown_tol)
+    opts = _LanczosOpts(reorth_mode, breakdown_tol, graph_mode)
     ctx.check(ctx.lib.fosi_lanczos(ctx.handle, op.handle, Q.n, m, Q.ptr, Q.ld, _dptr(alpha), _dptr(beta),
                                    C.byref(m_eff), C.byref(opts)))
     return alpha, beta, int(m_eff.value)
@@ -262,7 +271,7 @@ def fosi_lanczos_row_sharded(ctx: Context, op: Hvp, Q: ColMajor, m: int, shards:
     """Algorithm 2 emulated on one GPU with `shards` row blocks.  Same contract as fosi_lanczos."""
     alpha, beta = np.zeros(m), np.zeros(m)
     m_eff = C.c_int32(0)
-    opts = _LanczosOpts(reorth_mode, breakdown_tol)
+    opts = _LanczosOpts(reorth_mode, breakdown_tol, 0)
     ctx.check(ctx.lib.fosi_lanczos_row_sharded(ctx.handle, op.handle, Q.n, m, shards, Q.ptr, Q.ld, _dptr(alpha),
                                                _dptr(beta), C.byref(m_eff), C.byref(opts)))
     return alpha, beta, int(m_eff.value)

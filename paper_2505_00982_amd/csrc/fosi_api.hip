@@ -172,6 +172,7 @@ fosi_status fosi_ctx_destroy(fosi_ctx* ctx) {
         (void)hipEventDestroy(r.stop);
     }
     for (auto& e : ctx->event_pool) (void)hipEventDestroy(e);
+    if (ctx->graph_exec != nullptr) (void)hipGraphExecDestroy(ctx->graph_exec);
     (void)hipFree(ctx->scratch_base);
     delete ctx;
     return FOSI_OK;
@@ -320,8 +321,14 @@ fosi_status hvp_apply(fosi_hvp* op, const float* v_dev, float* hv_dev) {
     return apply_operator(op, v_dev, hv_dev, nullptr, false);
 }
 
+static void drop_graph(fosi_ctx* ctx);
+
 fosi_status hvp_destroy(fosi_hvp* op) {
     if (op == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (op->ctx->graph_key.op == op) {      // a captured run refers to this operator's buffers
+        (void)hipStreamSynchronize(op->ctx->stream);
+        drop_graph(op->ctx);
+    }
     if (op->kind == fosi_hvp::GGN) {
         (void)hipStreamSynchronize(op->ctx->stream);
         ggn_release(op);
@@ -338,31 +345,13 @@ int32_t fosi_lanczos_steps(int64_t n, int k, int l) {
     return (int32_t)std::ceil(by_pairs > by_size ? by_pairs : by_size);
 }
 
-fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q_dev, int64_t ldq,
-                         double* alpha_host, double* beta_host, int32_t* m_eff, const fosi_lanczos_opts* opts) {
-    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
-    if (op == nullptr || alpha_host == nullptr || beta_host == nullptr || m_eff == nullptr)
-        return fail(ctx, FOSI_ERR_INVALID_ARG, "null argument");
-    if (op->ctx != ctx) return fail(ctx, FOSI_ERR_INVALID_ARG, "operator belongs to another context");
-    if (n < 1 || m < 1) return fail(ctx, FOSI_ERR_INVALID_ARG, "n and m must be positive");
-    if (op->n != n) return fail(ctx, FOSI_ERR_INVALID_ARG, "operator size differs from n");
-    if (m + 1 > kMaxCols) return fail(ctx, FOSI_ERR_LIMIT, "m + 1 exceeds FOSI_MAX_COLS");
-    if (fosi_status s = check_matrix(ctx, "Q_dev", Q_dev, n, ldq, m + 1)) return s;
-    int mode = FOSI_REORTH_LOCAL_FULL;
-    double tol = 1e-6;
-    if (opts != nullptr) {
-        if (opts->reorth_mode != 0) mode = opts->reorth_mode;
-        if (opts->breakdown_tol > 0.0) tol = opts->breakdown_tol;
-    }
-    if (mode != FOSI_REORTH_SINGLE && mode != FOSI_REORTH_TWICE && mode != FOSI_REORTH_LOCAL_FULL)
-        return fail(ctx, FOSI_ERR_INVALID_ARG, "unknown reorth_mode");
+// Enqueues the start-vector normalisation and the m steps of Algorithm 1 on the context's stream; nothing
+// here waits for the device, so the same sequence can be recorded into a graph.
+static fosi_status enqueue_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q_dev, int64_t ldq, int mode,
+                                   double tol) {
     const int passes = mode == FOSI_REORTH_SINGLE ? 1 : 2;
-    *m_eff = 0;
-
     const double vec = kVec * (double)n;
     int* flags = ctx->s.flags;
-    if (fosi_status s = check_hip(ctx, hipMemsetAsync(flags, 0, 8 * sizeof(int), ctx->stream), "clear flags")) return s;
-
     // first column: the caller's vector, normalised in place
     launch_dot_columns(ctx, nullptr, 0, 0, Q_dev, nullptr, nullptr, nullptr, n, ctx->s.coef_a, nullptr, 0, 1.0, nullptr,
                        nullptr, -1, 0.0);
@@ -406,6 +395,92 @@ fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q
         }
         if (fosi_status s = launch_status(ctx, "lanczos step")) return s;
     }
+    return FOSI_OK;
+}
+
+static void drop_graph(fosi_ctx* ctx) {
+    if (ctx->graph_exec != nullptr) (void)hipGraphExecDestroy(ctx->graph_exec);
+    ctx->graph_exec = nullptr;
+    ctx->graph_key = fosi_ctx::GraphKey{};
+}
+
+// Replays the cached graph of this run, capturing it first when the key differs.  Returns false when the
+// stream cannot be captured (the caller then launches eagerly); *st carries an error from the enqueue itself.
+static bool lanczos_by_graph(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q_dev, int64_t ldq, int mode,
+                             double tol, fosi_status* st) {
+    *st = FOSI_OK;
+    fosi_ctx::GraphKey key;
+    key.op = op; key.Q = Q_dev; key.n = n; key.ldq = ldq; key.m = m; key.mode = mode; key.tol = tol;
+    if (ctx->graph_exec == nullptr || !(ctx->graph_key == key)) {
+        drop_graph(ctx);
+        if (hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeRelaxed) != hipSuccess) {
+            (void)hipGetLastError();
+            ctx->graph_unavailable = true;
+            return false;
+        }
+        const fosi_status es = enqueue_lanczos(ctx, op, n, m, Q_dev, ldq, mode, tol);
+        hipGraph_t graph = nullptr;
+        const hipError_t ee = hipStreamEndCapture(ctx->stream, &graph);
+        if (es != FOSI_OK || ee != hipSuccess || graph == nullptr) {
+            if (graph != nullptr) (void)hipGraphDestroy(graph);
+            (void)hipGetLastError();
+            if (es != FOSI_OK) { *st = es; return true; }
+            ctx->graph_unavailable = true;
+            return false;
+        }
+        const hipError_t ie = hipGraphInstantiate(&ctx->graph_exec, graph, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(graph);
+        if (ie != hipSuccess) {
+            (void)hipGetLastError();
+            ctx->graph_exec = nullptr;
+            ctx->graph_unavailable = true;
+            return false;
+        }
+        ctx->graph_key = key;
+        ++ctx->graph_captures;
+    }
+    *st = check_hip(ctx, hipGraphLaunch(ctx->graph_exec, ctx->stream), "hipGraphLaunch");
+    if (*st == FOSI_OK) ++ctx->graph_replays;
+    return true;
+}
+
+fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q_dev, int64_t ldq,
+                         double* alpha_host, double* beta_host, int32_t* m_eff, const fosi_lanczos_opts* opts) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (op == nullptr || alpha_host == nullptr || beta_host == nullptr || m_eff == nullptr)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "null argument");
+    if (op->ctx != ctx) return fail(ctx, FOSI_ERR_INVALID_ARG, "operator belongs to another context");
+    if (n < 1 || m < 1) return fail(ctx, FOSI_ERR_INVALID_ARG, "n and m must be positive");
+    if (op->n != n) return fail(ctx, FOSI_ERR_INVALID_ARG, "operator size differs from n");
+    if (m + 1 > kMaxCols) return fail(ctx, FOSI_ERR_LIMIT, "m + 1 exceeds FOSI_MAX_COLS");
+    if (fosi_status s = check_matrix(ctx, "Q_dev", Q_dev, n, ldq, m + 1)) return s;
+    int mode = FOSI_REORTH_LOCAL_FULL, graph_mode = FOSI_GRAPH_OFF;
+    double tol = 1e-6;
+    if (opts != nullptr) {
+        if (opts->reorth_mode != 0) mode = opts->reorth_mode;
+        if (opts->breakdown_tol > 0.0) tol = opts->breakdown_tol;
+        graph_mode = opts->graph_mode;
+    }
+    if (mode != FOSI_REORTH_SINGLE && mode != FOSI_REORTH_TWICE && mode != FOSI_REORTH_LOCAL_FULL)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "unknown reorth_mode");
+    if (graph_mode != FOSI_GRAPH_OFF && graph_mode != FOSI_GRAPH_ON)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "unknown graph_mode");
+    *m_eff = 0;
+
+    int* flags = ctx->s.flags;
+    // (cleared outside the graph: memset nodes are kept out of captured work)
+    if (fosi_status s = check_hip(ctx, hipMemsetAsync(flags, 0, 8 * sizeof(int), ctx->stream), "clear flags")) return s;
+
+    const bool graph_wanted = graph_mode == FOSI_GRAPH_ON && ctx->stream != nullptr && !ctx->graph_unavailable &&
+                              !ctx->prof_on && op->kind != fosi_hvp::CALLBACK;
+    bool done = false;
+    if (graph_wanted) {
+        fosi_status gs = FOSI_OK;
+        done = lanczos_by_graph(ctx, op, n, m, Q_dev, ldq, mode, tol, &gs);
+        if (done && gs != FOSI_OK) return gs;
+    }
+    if (!done)
+        if (fosi_status s = enqueue_lanczos(ctx, op, n, m, Q_dev, ldq, mode, tol)) return s;
 
     int hflags[2] = {0, 0};
     if (fosi_status s = check_hip(ctx, hipMemcpyAsync(alpha_host, ctx->s.alpha, sizeof(double) * m, hipMemcpyDeviceToHost,
@@ -419,6 +494,14 @@ fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q
     if (fosi_status s = check_hip(ctx, hipMemsetAsync(flags, 0, 8 * sizeof(int), ctx->stream), "clear flags")) return s;
     *m_eff = hflags[1];
     if (hflags[0] == 2) return fail(ctx, FOSI_ERR_NONFINITE, "non-finite value in the Lanczos recurrence");
+    return FOSI_OK;
+}
+
+/* Number of graph captures and replays of this context so far (for tests and diagnostics). */
+fosi_status fosi_graph_stats(fosi_ctx* ctx, int64_t* captures, int64_t* replays) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (captures != nullptr) *captures = ctx->graph_captures;
+    if (replays != nullptr) *replays = ctx->graph_replays;
     return FOSI_OK;
 }
 

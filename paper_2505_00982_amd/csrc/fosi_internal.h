@@ -66,6 +66,20 @@ struct fosi_ctx {
     std::vector<fosi::ProfRecord> prof;
     std::vector<hipEvent_t> event_pool;
     std::vector<double> newton_cache;   // host copy of what `s.newton` holds
+    // HIP graph of the last captured Lanczos run and what it was captured for
+    struct GraphKey {
+        const void* op = nullptr;
+        const void* Q = nullptr;
+        int64_t n = 0, ldq = 0;
+        int m = 0, mode = 0;
+        double tol = 0.0;
+        bool operator==(const GraphKey& o) const {
+            return op == o.op && Q == o.Q && n == o.n && ldq == o.ldq && m == o.m && mode == o.mode && tol == o.tol;
+        }
+    } graph_key;
+    hipGraphExec_t graph_exec = nullptr;
+    bool graph_unavailable = false;     // the stream refused capture once: do not try again
+    int64_t graph_replays = 0, graph_captures = 0;
     int sm_count = 256;
 };
 
