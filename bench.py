@@ -85,12 +85,20 @@ def cpu_baseline(cfg_id: int, n_sample: int) -> dict:
 
 
 def bench_ggn(args, fo, torch, np) -> int:
-    """Workload 3: softmax-GGN operator (the MFMA path), Lanczos m = 60 + Ritz k = 20, no update."""
+    """Workloads 3 and 6: softmax-GGN operator (the MFMA path), Lanczos m = 60 + Ritz k = 20, no update.
+    3: batch 512, fp32 data, fp32 matrix cores.  6: batch 8192, bf16 data, bf16 matrix cores with the fp32
+    operand split in two bf16 parts (two matrix instructions per product)."""
     import workloads as wl
-    g = wl.ggn_workload()
+    bf16 = args.config == 6
+    g = wl.ggn_workload(cfg_id=args.config)
     ctx = fo.Context(0)
-    X, W = torch.from_numpy(g.X).cuda(), torch.from_numpy(g.W).cuda()
-    op = ctx.hvp_softmax_ggn(X, W)
+    W = torch.from_numpy(g.W).cuda()
+    if bf16:
+        X = torch.from_numpy(g.X).cuda().to(torch.bfloat16).contiguous()
+        op = ctx.hvp_softmax_ggn_bf16(X, W)
+    else:
+        X = torch.from_numpy(g.X).cuda()
+        op = ctx.hvp_softmax_ggn(X, W)
     ld = wl.padded_ld(g.n)
     Q = fo.ColMajor(g.n, g.m + 1, ld)
     V = fo.ColMajor(g.n, g.k, ld)
@@ -116,6 +124,7 @@ def bench_ggn(args, fo, torch, np) -> int:
     ctx.profile_enable(False)
     cnt, ms, flops = ctx.profile_read("hvp_ggn")
     tf = flops / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+    peak = 2500.0 if bf16 else 157.3
     phases = {}
     for name in ("hvp_ggn", "reorth_dot", "reorth_sub", "normalise", "ritz_vectors"):
         c, m_, by = ctx.profile_read(name)
@@ -126,11 +135,15 @@ def bench_ggn(args, fo, torch, np) -> int:
     out = {"metric": "Lanczos+Ritz on the softmax-GGN operator: step time (ms); MFMA TFLOP/s of the operator",
            "value": round(dt / args.steps * 1e3, 3), "unit": "ms", "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 3), "higher_is_better": False,
-           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": f"cfg3: softmax-GGN, X {g.B}x{g.d}, W {g.d}x{g.C} (n={g.n}), Lanczos m={g.m}, k={g.k}",
-                      "m_eff": state["m_eff"]},
-           "roofline": {"bound": "mfma", "kernel": "softmax-GGN apply (2 fp32-MFMA GEMMs + softmax Jacobian), whole apply",
-                        "achieved": round(tf, 2), "peak": 157.3, "unit": "TFLOP/s", "frac": round(tf / 157.3, 4),
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16 x2 (split fp32 operand), f32 accumulate" if bf16 else "f32",
+           "data": "synthetic",
+           "config": {"workload": f"cfg{args.config}: softmax-GGN, X {g.B}x{g.d}{' bf16' if bf16 else ''}, W {g.d}x{g.C} "
+                                  f"(n={g.n}), Lanczos m={g.m}, k={g.k}", "m_eff": state["m_eff"]},
+           "roofline": {"bound": "mfma",
+                        "kernel": ("softmax-GGN apply (2 split-operand bf16-MFMA GEMMs + softmax Jacobian), whole apply; "
+                                   "achieved counts the 4*B*d*C algorithmic flops, the matrix cores execute twice that")
+                        if bf16 else "softmax-GGN apply (2 fp32-MFMA GEMMs + softmax Jacobian), whole apply",
+                        "achieved": round(tf, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(tf / peak, 4),
                         "traffic": None, "avg_launch_ms": round(ms / cnt, 4) if cnt else None,
                         "flops_per_apply": 4.0 * g.B * g.d * g.C},
            "phases": phases}
@@ -145,7 +158,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=4, help="workload id (4 = n 25.6M headline; 2 = n 1M; 5 = n 125M)")
+    ap.add_argument("--config", type=int, default=4, help="workload id (4 = n 25.6M headline; 2 = n 1M; 5 = n 125M; 3 = softmax-GGN batch 512 fp32; "
+                         "6 = softmax-GGN batch 8192, bf16 data)")
     ap.add_argument("--n", type=int, default=None, help="override the row count (debugging)")
     ap.add_argument("--reorth", choices=sorted(REORTH_MODES), default="local_full",
                     help="Gram-Schmidt scheme of the Lanczos run (library default: local_full)")
@@ -173,7 +187,7 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    if args.config == 3:
+    if args.config in (3, 6):
         return bench_ggn(args, fo, torch, np)
     w = planted_workload_device(args.config, args.n)
     if args.m is not None:

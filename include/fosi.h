@@ -80,6 +80,14 @@ fosi_status hvp_diag_create(fosi_ctx* ctx, int64_t n, const float* d_dev, fosi_h
  * matrices in device memory it allocates (freed by hvp_destroy). */
 fosi_status hvp_softmax_ggn_create(fosi_ctx* ctx, int B, int d, int C, const float* X_dev,
                                    const float* W_dev, fosi_hvp** out);
+/* The same operator for a data matrix stored in bf16 (X_bf16_dev: B x d row-major, raw 16-bit
+ * patterns; the operator is defined by exactly these values).  The two products run on the bf16 matrix
+ * cores with fp32 accumulation; the fp32 operand of each product (V, then the softmax-Jacobian rows)
+ * is split on the fly into two bf16 parts that together keep ~17 bits of it, so one application is
+ * accurate to a few 1e-6 relative.  The operator additionally owns a transposed bf16 copy of X and
+ * the partial results of the second product. */
+fosi_status hvp_softmax_ggn_bf16_create(fosi_ctx* ctx, int B, int d, int C, const uint16_t* X_bf16_dev,
+                                        const float* W_dev, fosi_hvp** out);
 /* User operator (for instance a double-backward pass).  fn must enqueue its
  * work on `stream` (a hipStream_t) and return 0 on success. */
 typedef int (*fosi_hvp_fn)(void* user, const float* v_dev, float* hv_dev, void* stream);

@@ -25,7 +25,7 @@ PROF = {"hvp_project": 0, "hvp_expand": 1, "reorth_dot": 2, "reorth_sub": 3, "no
 
 EXPORTS = [
     "fosi_ctx_create", "fosi_ctx_destroy", "fosi_ctx_synchronize", "fosi_last_error", "fosi_status_string",
-    "hvp_planted_create", "hvp_diag_create", "hvp_softmax_ggn_create", "hvp_callback_create", "hvp_apply",
+    "hvp_planted_create", "hvp_diag_create", "hvp_softmax_ggn_create", "hvp_softmax_ggn_bf16_create", "hvp_callback_create", "hvp_apply",
     "hvp_destroy", "fosi_lanczos", "fosi_graph_stats", "fosi_lanczos_row_sharded", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_step_adamw", "fosi_admm_begin",
     "fosi_admm_end", "fosi_profile_enable", "fosi_profile_reset", "fosi_profile_read",
 ]
@@ -78,6 +78,7 @@ def load_library() -> C.CDLL:
     lib.hvp_planted_create.argtypes = [vp, i64, C.c_int, vp, i64, vp, C.c_float, C.POINTER(vp)]
     lib.hvp_diag_create.argtypes = [vp, i64, vp, C.POINTER(vp)]
     lib.hvp_softmax_ggn_create.argtypes = [vp, C.c_int, C.c_int, C.c_int, vp, vp, C.POINTER(vp)]
+    lib.hvp_softmax_ggn_bf16_create.argtypes = [vp, C.c_int, C.c_int, C.c_int, vp, vp, C.POINTER(vp)]
     lib.hvp_callback_create.argtypes = [vp, i64, HVP_FN, vp, C.POINTER(vp)]
     lib.hvp_apply.argtypes = [vp, vp, vp]
     lib.hvp_destroy.argtypes = [vp]
@@ -202,6 +203,17 @@ class Context:
         assert d == d2 and X.is_contiguous() and W.is_contiguous()
         h = C.c_void_p()
         self.check(self.lib.hvp_softmax_ggn_create(self.handle, B, d, Cc, _ptr(X), _ptr(W), C.byref(h)))
+        return Hvp(self, h, d * Cc, keep=(X, W))
+
+    def hvp_softmax_ggn_bf16(self, X: torch.Tensor, W: torch.Tensor) -> "Hvp":
+        """X: B x d torch.bfloat16 (the operator is defined by exactly these values), W: d x C float32."""
+        B, d = X.shape
+        d2, Cc = W.shape
+        assert X.dtype == torch.bfloat16 and W.dtype == torch.float32
+        assert d == d2 and X.is_contiguous() and W.is_contiguous()
+        h = C.c_void_p()
+        assert X.is_cuda
+        self.check(self.lib.hvp_softmax_ggn_bf16_create(self.handle, B, d, Cc, X.data_ptr(), _ptr(W), C.byref(h)))
         return Hvp(self, h, d * Cc, keep=(X, W))
 
     def hvp_callback(self, n: int, fn: Callable[[int, int, int], int]) -> "Hvp":

@@ -250,6 +250,31 @@ fosi_status hvp_softmax_ggn_create(fosi_ctx* ctx, int B, int d, int C, const flo
     return FOSI_OK;
 }
 
+fosi_status hvp_softmax_ggn_bf16_create(fosi_ctx* ctx, int B, int d, int C, const uint16_t* X_bf16_dev,
+                                        const float* W_dev, fosi_hvp** out) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (out != nullptr) *out = nullptr;
+    if (B < 1 || d < 1 || C < 1) return fail(ctx, FOSI_ERR_INVALID_ARG, "B, d, C must be positive");
+    if (X_bf16_dev == nullptr || W_dev == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "X_bf16_dev or W_dev is null");
+    if (!aligned16(X_bf16_dev) || !aligned16(W_dev))
+        return fail(ctx, FOSI_ERR_BAD_LAYOUT, "X_bf16_dev/W_dev not 16-byte aligned");
+    if (fosi_status s = new_op(ctx, fosi_hvp::GGN, (int64_t)d * C, out)) return s;
+    fosi_hvp* op = *out;
+    op->B = B;
+    op->dim = d;
+    op->C = C;
+    op->bf16 = true;
+    op->Xb = X_bf16_dev;
+    op->W = W_dev;
+    if (fosi_status s = ggn_prepare(op)) {
+        ggn_release(op);
+        delete op;
+        *out = nullptr;
+        return s;
+    }
+    return FOSI_OK;
+}
+
 fosi_status hvp_callback_create(fosi_ctx* ctx, int64_t n, fosi_hvp_fn fn, void* user, fosi_hvp** out) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
     if (out != nullptr) *out = nullptr;

@@ -101,6 +101,10 @@ struct fosi_hvp {
     const float* W = nullptr;
     float* P = nullptr;     // B x C softmax probabilities
     float* Z = nullptr;     // B x C work
+    bool bf16 = false;      // data matrix given in bf16: split-operand bf16 matrix-core path
+    const unsigned short* Xb = nullptr;   // B x d bf16 (caller's)
+    unsigned short* XTb = nullptr;        // d x B bf16 (transposed copy, owned)
+    float* Y2 = nullptr;                  // split-K partials of the second product (owned)
     // callback
     fosi_hvp_fn fn = nullptr;
     void* user = nullptr;

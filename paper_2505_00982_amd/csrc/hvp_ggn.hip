@@ -184,6 +184,167 @@ __global__ __launch_bounds__(256) void k_softmax_jacobian(float* __restrict__ pa
     }
 }
 
+// ---------------------------------------------------------------- bf16 matrix cores, split operand
+// C[z] (M x N, row-major, ldc) = A[:, kz] * B[kz, :] with A given in bf16 (M x K row-major, k
+// contiguous) and B in fp32 (K x N row-major).  Every B element is split on the fly, while its tile is
+// staged into LDS, into two bf16 values, b = hi + lo with |b - hi - lo| <= 2^-18 |b|, and both parts go
+// through v_mfma_f32_32x32x16_bf16 with fp32 accumulation: the data matrix is exact in bf16, the
+// vector operand keeps ~17 bits, at twice the bf16 cost instead of the 16x more expensive fp32 matrix
+// path.  (Splitting B once per product in a kernel of its own was measured too: the product itself is
+// no faster and the two extra launches cost 10 %.)  Workgroup tile 128 x 128, K-step 32; the four
+// waves own 64 x 64 quadrants (2 x 2 MFMA tiles).  Operand layout of the instruction (checked against
+// a host product): lane l supplies, for A, row l % 32 and the 8 consecutive k values starting at
+// 8 (l / 32); for B, column l % 32 and the same k values; so both tiles sit in LDS with k contiguous
+// and are fetched with 16-byte reads.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short ushort8 __attribute__((ext_vector_type(8)));
+
+constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int LDK = BK + 8;    // LDS row stride in bf16 (80 bytes: an odd number of 16-byte units, conflict-free reads)
+
+__device__ __forceinline__ unsigned short bf16_round(float f) {      // round to nearest even; finite inputs
+    unsigned int u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+__device__ __forceinline__ float bf16_value(unsigned short h) { return __uint_as_float((unsigned int)h << 16); }
+
+template <bool VEC>
+__global__ __launch_bounds__(256) void k_gemm_bf16x2(const unsigned short* __restrict__ A, int lda,
+                                                     const float* __restrict__ Bm, int ldb, float* __restrict__ Cout,
+                                                     int ldc, int M, int N, int K, int klen, int64_t cstride,
+                                                     float scale) {
+    __shared__ __attribute__((aligned(16))) unsigned short As[2][BM][LDK];
+    __shared__ __attribute__((aligned(16))) unsigned short Bh[2][BN][LDK];
+    __shared__ __attribute__((aligned(16))) unsigned short Bl[2][BN][LDK];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int kbeg = blockIdx.z * klen;
+    const int kend = min(K, kbeg + klen);
+
+    // staging slots: A tile: row tid / 2, 16 k values; B tile: column tid % 128, 16 k values
+    const int arow = tid >> 1, ak = (tid & 1) * 16;
+    const int bn = tid & 127, bkg = (tid >> 7) * 16;
+    ushort8 ra[2];
+    float rb[16];
+
+    auto load = [&](int k0) {
+        const int m = m0 + arow, k = k0 + ak;
+        const unsigned short* pa = A + (int64_t)m * lda + k;
+        if (VEC && m < M && k + 15 < kend) {
+            ra[0] = *reinterpret_cast<const ushort8*>(pa);
+            ra[1] = *reinterpret_cast<const ushort8*>(pa + 8);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const unsigned short v = (m < M && k + i < kend) ? pa[i] : (unsigned short)0;
+                if (i < 8) ra[0][i] = v; else ra[1][i - 8] = v;
+            }
+        }
+        const int n = n0 + bn;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int kk = k0 + bkg + i;
+            rb[i] = (n < N && kk < kend) ? Bm[(int64_t)kk * ldb + n] : 0.f;
+        }
+    };
+    auto store = [&](int buf) {
+        *reinterpret_cast<ushort8*>(&As[buf][arow][ak]) = ra[0];
+        *reinterpret_cast<ushort8*>(&As[buf][arow][ak + 8]) = ra[1];
+        ushort8 h[2], l[2];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const unsigned short hi = bf16_round(rb[i]);
+            const unsigned short lo = bf16_round(rb[i] - bf16_value(hi));
+            if (i < 8) { h[0][i] = hi; l[0][i] = lo; } else { h[1][i - 8] = hi; l[1][i - 8] = lo; }
+        }
+        *reinterpret_cast<ushort8*>(&Bh[buf][bn][bkg]) = h[0];
+        *reinterpret_cast<ushort8*>(&Bh[buf][bn][bkg + 8]) = h[1];
+        *reinterpret_cast<ushort8*>(&Bl[buf][bn][bkg]) = l[0];
+        *reinterpret_cast<ushort8*>(&Bl[buf][bn][bkg + 8]) = l[1];
+    };
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int nk = (kend - kbeg + BK - 1) / BK;
+    if (nk > 0) {
+        load(kbeg);
+        store(0);
+    }
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) load(kbeg + (kt + 1) * BK);       // next tile into registers while this one is multiplied
+#pragma unroll
+        for (int ks = 0; ks < BK; ks += 16) {
+            bf16x8 a[2], bh[2], bl[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                a[i] = *reinterpret_cast<const bf16x8*>(&As[buf][wm + 32 * i + l32][ks + 8 * half]);
+                bh[i] = *reinterpret_cast<const bf16x8*>(&Bh[buf][wn + 32 * i + l32][ks + 8 * half]);
+                bl[i] = *reinterpret_cast<const bf16x8*>(&Bl[buf][wn + 32 * i + l32][ks + 8 * half]);
+            }
+            // the small parts first; four independent accumulators between the two uses of each one
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bl[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bh[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) store(buf ^ 1);
+        __syncthreads();
+    }
+    float* Cz = Cout + (int64_t)blockIdx.z * cstride;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int col = n0 + wn + 32 * j + l32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * half + (v & 3);
+                if (row < M && col < N) Cz[(int64_t)row * ldc + col] = acc[i][j][v] * scale;
+            }
+        }
+}
+
+// XT[j, i] = X[i, j] for a bf16 matrix (rows x cols row-major -> cols x rows row-major), once per operator.
+__global__ __launch_bounds__(256) void k_transpose_u16(const unsigned short* __restrict__ X, int rows, int cols,
+                                                       unsigned short* __restrict__ XT) {
+    __shared__ unsigned short tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+    const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+    for (int i = ty; i < 32; i += 8)
+        if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = X[(int64_t)(r0 + i) * cols + c0 + tx];
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8)
+        if (c0 + i < cols && r0 + tx < rows) XT[(int64_t)(c0 + i) * rows + r0 + tx] = tile[tx][i];
+}
+
+// out[i] = scale * sum_s parts[s][i]  (fixed order)
+__global__ __launch_bounds__(256) void k_sum_splits(const float* __restrict__ parts, int nsplit, int64_t pstride,
+                                                    int64_t count, float scale, float* __restrict__ out) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += stride) {
+        float z = 0.f;
+        for (int s = 0; s < nsplit; ++s) z += parts[s * pstride + i];
+        out[i] = z * scale;
+    }
+}
+
 struct GemmPlan {
     int nsplit, klen;
 };
@@ -213,13 +374,50 @@ void launch_gemm(fosi_ctx* ctx, const float* A, int lda, const float* Bm, int ld
                            plan.klen, cstride, scale);
 }
 
+GemmPlan plan_split_bf16(int M, int N, int K, int sm_count) {
+    const int tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+    int s = (2 * sm_count) / (tiles > 0 ? tiles : 1);
+    if (s < 1) s = 1;
+    if (s > 8) s = 8;
+    int klen = ((K + s - 1) / s + BK - 1) / BK * BK;
+    if (klen < BK) klen = BK;
+    s = (K + klen - 1) / klen;
+    return {s, klen};
+}
+
+void launch_gemm_bf16(fosi_ctx* ctx, const unsigned short* A, int lda, const float* Bm, int ldb, float* Cout, int ldc,
+                      int M, int N, int K, GemmPlan plan, int64_t cstride, float scale) {
+    const dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM, plan.nsplit);
+    const bool vec = (lda % 8 == 0) && ((reinterpret_cast<uintptr_t>(A) & 15) == 0) && (plan.klen % 16 == 0);
+    if (vec)
+        hipLaunchKernelGGL((k_gemm_bf16x2<true>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N, K,
+                           plan.klen, cstride, scale);
+    else
+        hipLaunchKernelGGL((k_gemm_bf16x2<false>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N, K,
+                           plan.klen, cstride, scale);
+}
+
 }  // namespace
 
 fosi_status ggn_prepare(fosi_hvp* op) {
     fosi_ctx* ctx = op->ctx;
     const int B = op->B, d = op->dim, C = op->C;
-    const GemmPlan plan = plan_split(B, C, d, ctx->sm_count);
     const size_t bc = (size_t)B * C;
+    if (op->bf16) {
+        const GemmPlan p1 = plan_split_bf16(B, C, d, ctx->sm_count), p2 = plan_split_bf16(d, C, B, ctx->sm_count);
+        if (hipMalloc(reinterpret_cast<void**>(&op->P), bc * sizeof(float)) != hipSuccess ||
+            hipMalloc(reinterpret_cast<void**>(&op->Z), bc * sizeof(float) * p1.nsplit) != hipSuccess ||
+            hipMalloc(reinterpret_cast<void**>(&op->XTb), (size_t)B * d * sizeof(unsigned short)) != hipSuccess ||
+            hipMalloc(reinterpret_cast<void**>(&op->Y2), (size_t)d * C * sizeof(float) * p2.nsplit) != hipSuccess)
+            return fail(ctx, FOSI_ERR_NOMEM, "softmax-GGN work buffers");
+        hipLaunchKernelGGL(k_transpose_u16, dim3((d + 31) / 32, (B + 31) / 32), dim3(256), 0, ctx->stream, op->Xb, B, d,
+                           op->XTb);
+        // P = softmax(X W)
+        launch_gemm_bf16(ctx, op->Xb, d, op->W, C, op->Z, C, B, C, d, p1, (int64_t)bc, 1.f);
+        hipLaunchKernelGGL(k_row_softmax, dim3(B), dim3(256), 0, ctx->stream, op->Z, p1.nsplit, (int64_t)bc, C, op->P);
+        return check_hip(ctx, hipGetLastError(), "softmax-GGN prepare");
+    }
+    const GemmPlan plan = plan_split(B, C, d, ctx->sm_count);
     if (hipMalloc(reinterpret_cast<void**>(&op->P), bc * sizeof(float)) != hipSuccess ||
         hipMalloc(reinterpret_cast<void**>(&op->Z), bc * sizeof(float) * plan.nsplit) != hipSuccess)
         return fail(ctx, FOSI_ERR_NOMEM, "softmax-GGN work buffers");
@@ -232,8 +430,25 @@ fosi_status ggn_prepare(fosi_hvp* op) {
 fosi_status ggn_apply(fosi_hvp* op, const float* v, float* hv) {
     fosi_ctx* ctx = op->ctx;
     const int B = op->B, d = op->dim, C = op->C;
-    const GemmPlan plan = plan_split(B, C, d, ctx->sm_count);
     const int64_t bc = (int64_t)B * C;
+    if (op->bf16) {
+        const GemmPlan p1 = plan_split_bf16(B, C, d, ctx->sm_count), p2 = plan_split_bf16(d, C, B, ctx->sm_count);
+        const int64_t dc = (int64_t)d * C;
+        // Z = X V (split along d), Y = softmax-Jacobian rows of Z, hv = X^T Y / B (split along the batch)
+        launch_gemm_bf16(ctx, op->Xb, d, v, C, op->Z, C, B, C, d, p1, bc, 1.f);
+        hipLaunchKernelGGL(k_softmax_jacobian, dim3(B), dim3(256), 0, ctx->stream, op->Z, p1.nsplit, bc, C, op->P);
+        if (p2.nsplit == 1) {
+            launch_gemm_bf16(ctx, op->XTb, B, op->Z, C, hv, C, d, C, B, p2, 0, 1.f / (float)B);
+        } else {
+            launch_gemm_bf16(ctx, op->XTb, B, op->Z, C, op->Y2, C, d, C, B, p2, dc, 1.f);
+            int64_t g = (dc + 255) / 256;
+            if (g > 4096) g = 4096;
+            hipLaunchKernelGGL(k_sum_splits, dim3((unsigned)g), dim3(256), 0, ctx->stream, op->Y2, p2.nsplit, dc, dc,
+                               1.f / (float)B, hv);
+        }
+        return FOSI_OK;
+    }
+    const GemmPlan plan = plan_split(B, C, d, ctx->sm_count);
     // Z = X V (split along d), Y = softmax-Jacobian rows of Z, hv = X^T Y / B
     launch_gemm<false>(ctx, op->X, d, v, C, op->Z, C, B, C, d, plan, bc, 1.f);
     hipLaunchKernelGGL(k_softmax_jacobian, dim3(B), dim3(256), 0, ctx->stream, op->Z, plan.nsplit, bc, C, op->P);
@@ -245,8 +460,12 @@ fosi_status ggn_apply(fosi_hvp* op, const float* v, float* hv) {
 void ggn_release(fosi_hvp* op) {
     if (op->P != nullptr) (void)hipFree(op->P);
     if (op->Z != nullptr) (void)hipFree(op->Z);
+    if (op->XTb != nullptr) (void)hipFree(op->XTb);
+    if (op->Y2 != nullptr) (void)hipFree(op->Y2);
     op->P = nullptr;
     op->Z = nullptr;
+    op->XTb = nullptr;
+    op->Y2 = nullptr;
 }
 
 }  // namespace fosi

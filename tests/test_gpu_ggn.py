@@ -108,3 +108,63 @@ def test_ggn_curvature_reference_size(fo, ctx):
     # a converged block is only a well-defined subspace if it is contiguous from the top
     top = idx[: (np.diff(idx, prepend=-1) == 1).cumprod().sum()]
     assert sin_principal_angles(rz.V[:, top], gp["V"].to_numpy()[:, top]).max() < 1e-3
+
+
+# ------------------------------------------------------------------ bf16 data matrix, split-operand matrix-core path
+def dev_bf16(a):
+    """bf16 tensor holding exactly the (already bf16-representable) fp32 values of `a`."""
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(torch.bfloat16)
+    assert torch.equal(t.float().cpu(), torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)))
+    return t.contiguous()
+
+
+# shapes: single partial tile; unaligned row length (scalar staging path); several tiles with ragged edges in
+# every dimension; d, B multiples of the K step; a shape that splits both products along K
+@pytest.mark.parametrize("B,d,C", [(16, 8, 5), (1, 1, 1), (70, 200, 132), (100, 301, 130), (257, 96, 300), (640, 512, 250)])
+def test_ggn_bf16_operator_matches_oracle(fo, ctx, B, d, C):
+    g = wl.ggn_workload(B=B, d=d, C=C, bf16=True)
+    op = ctx.hvp_softmax_ggn_bf16(dev_bf16(g.X), dev(g.W))
+    for seed in (60, 61):
+        v = wl.normal_vector(3, seed, g.n)
+        out = torch.zeros(g.n, device="cuda")
+        op.apply(dev(v), out)
+        ctx.synchronize()
+        ref = oracle.hvp_softmax_ggn(g.X, g.W, v)      # the oracle sees the same bf16-exact X, in fp64
+        assert rel_l2(out.cpu().numpy(), ref) <= GGN_RTOL
+    op.close()
+
+
+def test_ggn_bf16_curvature(fo, ctx):
+    g = wl.ggn_workload(B=300, d=160, C=50, m=30, k=6, bf16=True)
+    op = ctx.hvp_softmax_ggn_bf16(dev_bf16(g.X), dev(g.W))
+    ld = wl.padded_ld(g.n)
+    Q = fo.ColMajor(g.n, g.m + 1, ld)
+    Q.col(0).copy_(dev(g.v1))
+    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, g.m)
+    V = fo.ColMajor(g.n, g.k, ld)
+    evals, _ = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, g.k, 0, V)
+    ctx.synchronize()
+    res = oracle.lanczos(lambda v: oracle.hvp_softmax_ggn(g.X, g.W, v), g.v1, g.m)
+    rz = oracle.ritz(res.Q, res.alpha, res.beta, res.m_eff, g.k, 0)
+    assert m_eff == res.m_eff == g.m
+    assert np.max(np.abs(evals - rz.evals) / np.abs(rz.evals)) <= 1e-4
+    conv = rz.resid <= 1e-3 * np.abs(rz.evals)
+    idx = np.arange(g.k)[conv]
+    top = idx[: (np.diff(idx, prepend=-1) == 1).cumprod().sum()]
+    assert len(top) >= 2
+    assert sin_principal_angles(rz.V[:, top], V.to_numpy()[:, top]).max() < 1e-3
+    op.close()
+
+
+def test_ggn_bf16_larger_batch_sampled(fo, ctx):
+    """The second softmax-GGN workload at full size (batch 8192, W 2048 x 1000): the whole result against
+    the fp64 oracle (two float64 GEMMs of 33 GFLOP on the host)."""
+    g = wl.ggn_workload(cfg_id=6)
+    op = ctx.hvp_softmax_ggn_bf16(dev_bf16(g.X), dev(g.W))
+    v = wl.normal_vector(3, 62, g.n)
+    out = torch.zeros(g.n, device="cuda")
+    op.apply(dev(v), out)
+    ctx.synchronize()
+    ref = oracle.hvp_softmax_ggn(g.X, g.W, v)
+    assert rel_l2(out.cpu().numpy(), ref) <= GGN_RTOL
+    op.close()

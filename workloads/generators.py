@@ -45,6 +45,7 @@ CONFIGS = {
     2: dict(n=1 << 20, r=64, m=60, k=10, l=5, shift=0.01, g_std=0.1,
             pos=(1e4, 1e-1), n_neg=8, grid="geometric", admm=True, steps=10),
     3: dict(B=512, d=2048, C=1000, m=60, k=20, l=0),
+    6: dict(B=8192, d=2048, C=1000, m=60, k=20, l=0, bf16=True),   # second softmax-GGN workload: larger batch, bf16 data
     4: dict(n=25_600_000, r=128, m=80, k=20, l=10, shift=0.01, g_std=float(np.sqrt(1e-3)),
             pos=(1e-2, 1e4), n_neg=16, grid="loguniform", admm=False, steps=1),
     5: dict(n=125_000_000, r=128, m=100, k=20, l=20, shift=1e-3, g_std=float(np.sqrt(1e-3)),
@@ -187,11 +188,22 @@ class GgnWorkload:
         return self.d * self.C
 
 
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """fp32 array rounded to the nearest bf16 value (ties to even), returned as fp32."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(np.shape(a))
+
+
 def ggn_workload(B: Optional[int] = None, d: Optional[int] = None, C: Optional[int] = None,
-                 m: Optional[int] = None, k: Optional[int] = None) -> GgnWorkload:
-    c = CONFIGS[3]
+                 m: Optional[int] = None, k: Optional[int] = None, cfg_id: int = 3, bf16: Optional[bool] = None) -> GgnWorkload:
+    """Softmax-GGN workload.  cfg_id 3: the small-batch fp32 one; cfg_id 6: the larger batch whose data
+    matrix is stored in bf16 (X is then rounded to bf16 values, still returned as fp32)."""
+    c = CONFIGS[cfg_id]
     B, d, C = int(B or c["B"]), int(d or c["d"]), int(C or c["C"])
     X = (philox(3, T_X).standard_normal((B, d), dtype=np.float32) * np.float32(1.0 / np.sqrt(d)))
+    if c.get("bf16", False) if bf16 is None else bf16:
+        X = round_to_bf16(X)
     W = philox(3, T_W).standard_normal((d, C), dtype=np.float32)
     labels = philox(3, T_LABELS).integers(0, C, B)
     v1 = philox(3, T_V1).standard_normal(d * C, dtype=np.float32)
