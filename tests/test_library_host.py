@@ -112,3 +112,18 @@ def test_lanczos_length_rule(fo):
     assert fo.fosi_lanczos_steps(25_600_000, 20, 10) == 120
     assert fo.fosi_lanczos_steps(10 ** 9, 1, 0) == int(np.ceil(2 * np.log(1e9)))      # the size term wins: 42
     assert fo.fosi_lanczos_steps(0, 1, 0) == 0 and fo.fosi_lanczos_steps(10, 0, 0) == 0
+
+
+def test_bf16_rounding_of_the_generator_matches_torch():
+    """The second softmax-GGN workload rounds its data matrix to bf16 on the host; the rounding (nearest,
+    ties to even) is checked against torch's conversion, including ties and values next to them."""
+    import torch
+    import workloads as wl
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.standard_normal(20000).astype(np.float32) * 3.0,
+                        np.array([1.0, 1.00390625, 1.01171875, -1.00390625, 0.0, 3.0e-39, 65280.0, 1.0 + 2.0 ** -9],
+                                 dtype=np.float32)])
+    ties = (np.arange(1, 400, dtype=np.float32) * np.float32(2.0 ** -8)) + np.float32(1.0)      # half-way points of [1, 2)
+    x = np.concatenate([x, ties, np.nextafter(ties, np.float32(0)), np.nextafter(ties, np.float32(4))])
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(wl.generators.round_to_bf16(x), ref)
