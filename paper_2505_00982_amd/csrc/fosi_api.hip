@@ -113,6 +113,7 @@ fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
     ctx->tun.comb_rows_per_thread = env_int("FOSI_COMB_ROWS", 4);
     ctx->tun.comb_cols_unroll = env_int("FOSI_COMB_COLS", 8);
     ctx->tun.comb_max_blocks = env_int("FOSI_COMB_BLOCKS", 0);
+    ctx->tun.ritz_mfma = env_int("FOSI_RITZ_MFMA", 1);
     ctx->tun.step_waves_per_cu = env_int("FOSI_STEP_WAVES", 12);
     if (ctx->tun.step_waves_per_cu < 1) ctx->tun.step_waves_per_cu = 1;
     ctx->tun.xcd_partition = env_int("FOSI_XCD_PARTITION", 0);
@@ -716,11 +717,14 @@ fosi_status fosi_ritz(fosi_ctx* ctx, int64_t n, int m_eff, const float* Q_dev, i
         evals_host[j] = u[sel[j]];
         if (resid_host != nullptr) resid_host[j] = blast * std::fabs(Z[(size_t)sel[j] * m_eff + (m_eff - 1)]);
     }
-    // Ritz vectors in chunks of at most 40 output columns (register budget of the kernel)
+    // Ritz vectors: up to 32 output columns in one sweep on the matrix cores; more in chunks of at most 40
+    // columns on the vector ALUs (register budget of that kernel)
     const double vec = kVec * (double)n;
-    for (int c0 = 0; c0 < rv; c0 += 40) {
-        const int cw = std::min(40, rv - c0);
-        const int pad = cw <= 8 ? 8 : cw <= 16 ? 16 : cw <= 24 ? 24 : cw <= 32 ? 32 : 40;
+    const bool mfma = ctx->tun.ritz_mfma != 0 && rv <= 32;
+    const int chunk = mfma ? 32 : 40;
+    for (int c0 = 0; c0 < rv; c0 += chunk) {
+        const int cw = std::min(chunk, rv - c0);
+        const int pad = mfma ? 32 : cw <= 8 ? 8 : cw <= 16 ? 16 : cw <= 24 ? 24 : cw <= 32 ? 32 : 40;
         std::vector<float> S((size_t)m_eff * pad, 0.f);
         for (int j = 0; j < m_eff; ++j)
             for (int t = 0; t < cw; ++t) S[(size_t)j * pad + t] = (float)Z[(size_t)sel[c0 + t] * m_eff + j];
@@ -729,7 +733,10 @@ fosi_status fosi_ritz(fosi_ctx* ctx, int64_t n, int m_eff, const float* Q_dev, i
                                                           hipMemcpyHostToDevice, ctx->stream), "upload S")) return s;
         if (fosi_status s = check_hip(ctx, hipStreamSynchronize(ctx->stream), "upload S sync")) return s;
         ProfScope ps(ctx, FOSI_PROF_RITZ_VECTORS, (m_eff + cw) * vec);
-        launch_ritz_vectors(ctx, Q_dev, ldq, m_eff, ctx->s.S, pad, cw, V_dev + (int64_t)c0 * ldv, ldv, n);
+        if (mfma)
+            launch_ritz_vectors_mfma(ctx, Q_dev, ldq, m_eff, ctx->s.S, cw, V_dev + (int64_t)c0 * ldv, ldv, n);
+        else
+            launch_ritz_vectors(ctx, Q_dev, ldq, m_eff, ctx->s.S, pad, cw, V_dev + (int64_t)c0 * ldv, ldv, n);
     }
     return launch_status(ctx, "ritz vectors");
 }

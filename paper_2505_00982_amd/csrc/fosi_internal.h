@@ -30,6 +30,7 @@ struct Tunables {
     int comb_cols_unroll;     // CU: columns loaded together in that kernel
     int xcd_partition;        // give each XCD a contiguous eighth of the rows (1) or interleave rows over all XCDs (0)
     int comb_max_blocks;      // cap on that kernel's grid (it grid-strides over row tiles); 0 = no cap
+    int ritz_mfma;            // 1: Ritz vectors of up to 32 columns on the matrix cores (default), 0: vector ALUs
     int step_waves_per_cu;    // resident wavefronts per CU aimed at by the fused second sweep of the update
 };
 
@@ -164,6 +165,9 @@ void launch_scale(fosi_ctx* ctx, float* x, const double* factor, int64_t n, cons
 void launch_diag_apply(fosi_ctx* ctx, const float* d, const float* v, float* out, int64_t n);
 void launch_ritz_vectors(fosi_ctx* ctx, const float* Q, int64_t ldq, int m, const float* S_dev, int rv_pad,
                          int rv, float* V, int64_t ldv, int64_t n);
+// matrix-core variant for rv <= 32; S_dev is m x 32 row-major, zero padded
+void launch_ritz_vectors_mfma(fosi_ctx* ctx, const float* Q, int64_t ldq, int m, const float* S_dev, int rv, float* V,
+                              int64_t ldv, int64_t n);
 void launch_step_coefficients(fosi_ctx* ctx, int rv, double lr);
 // Second sweep of the update fused with the transposed product of its result: x = g (+ pi) - V c, base optimiser
 // (opt 0: heavy ball on m with factor mu; opt 1: AdamW on m, v with decay against w, descent vector to o_out),

@@ -741,6 +741,94 @@ __global__ __launch_bounds__(kThreads) void k_ritz_vectors(
     }
 }
 
+// The same product on the matrix cores, for at most 32 output columns.  It is a dense contraction at
+// ~11 flop per byte, above what the vector ALUs sustain at HBM speed without packed fp32 (the kernel
+// above reaches ~60 % of the HBM rate), but within reach of v_mfma_f32_32x32x2_f32.  The product is
+// taken transposed, V^T tile (32 output columns x 32 rows) = S^T (32 x 2) . Q^T (2 x 32 rows) per
+// instruction, so that a lane ends up with all output columns of its own rows: lane l feeds the S entry
+// of output column l % 32 and Lanczos column k0 + l / 32 (from LDS) and, as the other operand, one of
+// the four rows of its float4 load of that Lanczos column (rows 4 (l % 32) + c, c = 0..3: four
+// instructions share one 16-byte load), and the four accumulators give float4 stores of 4 consecutive
+// rows per output column: 512 contiguous bytes per half wave, no transpose.
+// S: m x 32 row-major, zero padded.  A wave owns tiles of 128 rows; U column pairs are loaded together.
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+template <int U>
+__global__ __launch_bounds__(kThreads) void k_ritz_vectors_mfma(
+    const float* __restrict__ Q, int64_t ldq, int m, const float* __restrict__ S, int rv,
+    float* __restrict__ V, int64_t ldv, int64_t n) {
+    extern __shared__ float Ssh[];                 // (m rounded up to even) x 32, the extra row zero
+    const int tid = threadIdx.x;
+    const int mp = (m + 1) & ~1;
+    for (int i = tid; i < mp * 32; i += kThreads) Ssh[i] = i < m * 32 ? S[i] : 0.f;
+    __syncthreads();
+    const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(tid >> 6));
+    const int64_t n4 = n >> 2;
+    const int64_t ntiles = (n4 + 31) >> 5;
+    for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < ntiles; tile += (int64_t)gridDim.x * 4) {
+        const int64_t rg = (tile << 5) + l32;      // this lane's float4 row group
+        const bool ok = rg < n4;
+        const float* qp = Q + ((ok ? rg : n4 - 1) << 2);
+        floatx16 acc[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
+        // two register sets: the loads of the next U column pairs are in flight while the matrix
+        // instructions of the current ones run (the fences keep the compiler from serialising the two)
+        auto issue = [&](int kb, float4* q) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (kb + 2 * u < mp) {             // uniform
+                    const int k = min(kb + 2 * u + half, m - 1);   // odd m: the padding column re-reads the last one, times 0
+                    q[u] = load_stream4(qp + (int64_t)k * ldq);
+                }
+            }
+        };
+        auto multiply = [&](int kb, const float4* q) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (kb + 2 * u < mp) {
+                    const float a = Ssh[(kb + 2 * u + half) * 32 + l32];
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, q[u].x, acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, q[u].y, acc[1], 0, 0, 0);
+                    acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, q[u].z, acc[2], 0, 0, 0);
+                    acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, q[u].w, acc[3], 0, 0, 0);
+                }
+            }
+        };
+        float4 qa[U], qb[U];
+        issue(0, qa);
+        for (int k0 = 0; k0 < mp; k0 += 4 * U) {
+            issue(k0 + 2 * U, qb);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(k0, qa);
+            __builtin_amdgcn_sched_barrier(0);
+            issue(k0 + 4 * U, qa);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(k0 + 2 * U, qb);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (ok) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int col = 8 * (v >> 2) + 4 * half + (v & 3);
+                if (col < rv)
+                    store_stream4(V + (int64_t)col * ldv + (rg << 2), make_float4(acc[0][v], acc[1][v], acc[2][v], acc[3][v]));
+            }
+        }
+    }
+    const int64_t tail_row = (n4 << 2) + tid;
+    if (blockIdx.x == 0 && tid < 3 && tail_row < n) {
+        for (int t = 0; t < rv; ++t) {
+            float s = 0.f;
+            for (int j = 0; j < m; ++j) s = fmaf(Q[(int64_t)j * ldq + tail_row], Ssh[j * 32 + t], s);
+            V[(int64_t)t * ldv + tail_row] = s;
+        }
+    }
+}
+
 // Coefficients of the last sweep of the update (Eq. 4 / Eq. 12 / Eq. 14):
 //   d_j = newton_j * c_j  -  lr * e_j ,  c = V^T (g + pi),  e = V^T b,
 // so that  w += -lr b - V d  equals  w + Delta_1 + Delta_2.
@@ -921,6 +1009,18 @@ void launch_scale(fosi_ctx* ctx, float* x, const double* factor, int64_t n, cons
 
 void launch_diag_apply(fosi_ctx* ctx, const float* d, const float* v, float* out, int64_t n) {
     hipLaunchKernelGGL(k_diag_apply, dim3(elementwise_grid(n)), dim3(kThreads), 0, ctx->stream, d, v, out, n);
+}
+
+void launch_ritz_vectors_mfma(fosi_ctx* ctx, const float* Q, int64_t ldq, int m, const float* S_dev, int rv, float* V,
+                              int64_t ldv, int64_t n) {
+    const int64_t ntiles = ((n >> 2) + 31) >> 5;
+    int64_t grid = (ntiles + 3) / 4;
+    const int64_t cap = (int64_t)ctx->sm_count * 8;     // resident workgroups; the kernel grid-strides over row tiles
+    if (grid > cap) grid = cap;
+    if (grid < 1) grid = 1;
+    const size_t lds = sizeof(float) * 32 * ((m + 1) & ~1);
+    hipLaunchKernelGGL((k_ritz_vectors_mfma<8>), dim3((unsigned)grid), dim3(kThreads), lds, ctx->stream, Q, ldq, m, S_dev, rv,
+                       V, ldv, n);
 }
 
 void launch_ritz_vectors(fosi_ctx* ctx, const float* Q, int64_t ldq, int m, const float* S_dev, int rv_pad, int rv,
