@@ -36,7 +36,7 @@ def algorithmic_vectors(m_eff: int, r: int, r_v: int, reorth: str, with_pi: bool
     "twice": two times; "local_full": the local pass rides on the operator's
     expand sweep (+1 vector, q_{i-1}, when i > 0), the full pass reads h, q_i and
     q_{i-1} to form its vector (c + 2 + [i > 0]) and one subtraction follows
-    (c+2); normalisation 2.  Start vector 3.  Ritz vectors m_eff + r_v.  Update:
+    (c+2) that also normalises (the other schemes: a normalisation sweep, 2).  Start vector 3.  Ritz vectors m_eff + r_v.  Update:
     3 sweeps of V-hat plus 7 vector accesses (+2 with a dual variable)."""
     hvp = m_eff * (2 * r + 3)
     if reorth == "local_full":
@@ -47,8 +47,9 @@ def algorithmic_vectors(m_eff: int, r: int, r_v: int, reorth: str, with_pi: bool
         if reorth == "local_full":
             return full + 1 + (1 if c > 1 else 0)
         return {"single": full, "twice": 2 * full}[reorth]
+    reorth_name = reorth
     reorth = sum(gs(i + 1) for i in range(m_eff))
-    norm = 2 * m_eff + 3
+    norm = (0 if reorth_name == "local_full" else 2 * m_eff) + 3   # 'local_full' normalises inside the subtraction
     ritz = m_eff + r_v
     step = 3 * r_v + 7 + (2 if with_pi else 0)
     return dict(hvp=hvp, reorth=reorth, normalise=norm, ritz=ritz, step=step,

@@ -113,6 +113,7 @@ fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
     ctx->tun.comb_rows_per_thread = env_int("FOSI_COMB_ROWS", 4);
     ctx->tun.comb_cols_unroll = env_int("FOSI_COMB_COLS", 8);
     ctx->tun.comb_max_blocks = env_int("FOSI_COMB_BLOCKS", 0);
+    ctx->tun.early_beta = env_int("FOSI_EARLY_BETA", 1);
     ctx->tun.ritz_mfma = env_int("FOSI_RITZ_MFMA", 1);
     ctx->tun.step_waves_per_cu = env_int("FOSI_STEP_WAVES", 12);
     if (ctx->tun.step_waves_per_cu < 1) ctx->tun.step_waves_per_cu = 1;
@@ -397,6 +398,15 @@ static fosi_status enqueue_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m
             launch_dot_columns(ctx, Q_dev, ldq, ncols, h, q, qprev, ctx->s.scal + 4, n, ctx->s.coef_b, nullptr, 0, 1.0,
                                ctx->s.loc, flags, FOSI_PROF_REORTH_DOT, (ncols + 1 + (qprev != nullptr ? 2 : 1)) * vec);
             // coef_b now holds the total coefficient per column (local + full); one subtraction removes both
+            if (ctx->tun.early_beta) {
+                // beta from the coefficients, then the subtraction writes the normalised vector itself
+                launch_lanczos_finalize_early(ctx, i, ctx->s.coef_b, ncols, tol);
+                launch_combine_columns(ctx, Q_dev, ldq, ncols, ctx->s.coef_b, h, 1.0, nullptr, 0.0, nullptr, 0.0, nullptr,
+                                       false, -1.0, h, n, false, flags, FOSI_PROF_REORTH_SUB, (ncols + 2) * vec,
+                                       ctx->s.scal);
+                if (fosi_status s = launch_status(ctx, "lanczos step")) return s;
+                continue;
+            }
             norm_slots = launch_combine_columns(ctx, Q_dev, ldq, ncols, ctx->s.coef_b, h, 1.0, nullptr, 0.0, nullptr,
                                                 0.0, nullptr, false, -1.0, h, n, true, flags, FOSI_PROF_REORTH_SUB,
                                                 (ncols + 2) * vec);
@@ -653,6 +663,17 @@ fosi_status fosi_lanczos_row_sharded(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int
             if (fosi_status s = sharded_operator(op, sh, q, h, qprev, true)) return s;
             sharded_dot(ctx, sh, Q_dev, ldq, ncols, h, q, qprev, ctx->s.scal + 4, ctx->s.coef_b, nullptr, 0, ctx->s.loc,
                         flags, FOSI_PROF_REORTH_DOT);
+            if (ctx->tun.early_beta) {
+                launch_lanczos_finalize_early(ctx, i, ctx->s.coef_b, ncols, tol);
+                for (int c = 0; c < sh.count; ++c) {
+                    const int64_t o = sh.begin[c], nr = sh.rows(c);
+                    launch_combine_columns(ctx, Q_dev + o, ldq, ncols, ctx->s.coef_b, h + o, 1.0, nullptr, 0.0, nullptr, 0.0,
+                                           nullptr, false, -1.0, h + o, nr, false, flags, FOSI_PROF_REORTH_SUB,
+                                           (ncols + 2) * kVec * (double)nr, ctx->s.scal);
+                }
+                if (fosi_status s = launch_status(ctx, "sharded lanczos step")) return s;
+                continue;
+            }
             sharded_subtract(ctx, sh, Q_dev, ldq, ncols, ctx->s.coef_b, h, flags);
             launch_lanczos_finalize(ctx, i, sh.count, ctx->s.coef_b, ncols, nullptr, 0, ctx->s.loc + 2, tol, ctx->s.xchg3);
         } else {

@@ -30,6 +30,7 @@ struct Tunables {
     int comb_cols_unroll;     // CU: columns loaded together in that kernel
     int xcd_partition;        // give each XCD a contiguous eighth of the rows (1) or interleave rows over all XCDs (0)
     int comb_max_blocks;      // cap on that kernel's grid (it grid-strides over row tiles); 0 = no cap
+    int early_beta;           // 1 (default): 'local_full' runs take beta from the coefficients and normalise inside the subtraction
     int ritz_mfma;            // 1: Ritz vectors of up to 32 columns on the matrix cores (default), 0: vector ALUs
     int step_waves_per_cu;    // resident wavefronts per CU aimed at by the fused second sweep of the update
 };
@@ -142,10 +143,14 @@ void launch_dot_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, c
 int launch_combine_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const double* d,
                            const float* y, double a0, const float* x1, double a1, const float* x2,
                            double a2, const float* x3, bool local_dots, double sa, float* out, int64_t n,
-                           bool want_norm, const int* stop, int prof_cls, double prof_bytes);
+                           bool want_norm, const int* stop, int prof_cls, double prof_bytes,
+                           const double* oscale = nullptr);   // oscale (device): factor on the whole result
 
 // cols_a / cols_b: number of columns of the first / second Gram-Schmidt pass (cols_b == 0: single pass);
 // in both the current Lanczos vector is the last column of the range.
+// 'local_full' scheme: alpha, beta, flags and 1/beta from the full pass's coefficients (coef[cols] = squared norm of
+// the vector it worked on) and ctx->s.loc, before the subtraction sweep.
+void launch_lanczos_finalize_early(fosi_ctx* ctx, int step, const double* coef, int cols, double tol);
 // norm_parts == null: the partial sums the last column-combination kernel left in ctx->s.norm_partials.
 void launch_lanczos_finalize(fosi_ctx* ctx, int step, int norm_slots, const double* coef_a, int cols_a,
                              const double* coef_b, int cols_b, const double* hh, double tol,

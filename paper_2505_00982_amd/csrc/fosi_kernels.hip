@@ -289,6 +289,7 @@ __device__ __forceinline__ void accumulate_columns(const float* __restrict__ A, 
 // touched in one burst (a workgroup that hops across all columns for every 4 KiB thrashes the
 // address-translation caches).  d is read through uniform (scalar) loads.  With NORM the block's
 // sum of out^2 (of the stored, rounded values) goes to norm_partials[blockIdx.x].
+// oscale (device, may be null): factor applied to every element before the rounding, e.g. 1/beta.
 // With LDOT (used by the planted operator inside a Lanczos run) the block also emits the partial sums
 // of out.x1 and out.x3 (x3 may be null): norm_partials[3*block + {0,1,2}] = {out^2, out.x1, out.x3}.
 template <bool HAS_Y, bool HAS_X1, bool HAS_X2, bool NORM, bool LDOT, int RPT, int CU>
@@ -296,9 +297,10 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
     const float* __restrict__ A, int64_t lda, int ncols, const double* __restrict__ d, const float* y,
     double a0, const float* __restrict__ x1, double a1, const float* __restrict__ x2, double a2,
     const float* __restrict__ x3, double sa, float* out, int64_t n, double* __restrict__ norm_partials,
-    int xcd_part, const int* __restrict__ stop) {
+    int xcd_part, const double* __restrict__ oscale, const int* __restrict__ stop) {
     if (stop != nullptr && *stop != 0) return;
     __shared__ double red[4];
+    const double osc = oscale != nullptr ? oscale[0] : 1.0;   // device-side factor applied to the whole result
     const int tid = threadIdx.x;
     const int64_t n4 = n >> 2;
     const int64_t tile = (int64_t)kThreads * RPT;
@@ -351,6 +353,7 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
                 o0 = fma(a2, (double)v.x, o0); o1 = fma(a2, (double)v.y, o1);
                 o2 = fma(a2, (double)v.z, o2); o3 = fma(a2, (double)v.w, o3);
             }
+            if (oscale != nullptr) { o0 *= osc; o1 *= osc; o2 *= osc; o3 *= osc; }
             const float4 o = make_float4((float)o0, (float)o1, (float)o2, (float)o3);
             store_stream4(out + (r4[q] << 2), o);
             if (NORM || LDOT) nrm = fma((double)o.x, (double)o.x, fma((double)o.y, (double)o.y,
@@ -374,6 +377,7 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
         if (HAS_Y) o = fma(a0, (double)y[tail_row], o);
         if (HAS_X1) o = fma(a1, (double)x1[tail_row], o);
         if (HAS_X2) o = fma(a2, (double)x2[tail_row], o);
+        if (oscale != nullptr) o *= osc;
         const float of = (float)o;
         out[tail_row] = of;
         if (NORM || LDOT) nrm = fma((double)of, (double)of, nrm);
@@ -604,6 +608,42 @@ __global__ __launch_bounds__(kThreads) void k_lanczos_finalize(
         const double b = sqrt(s);
         // ||H q_step||^2 before orthogonalisation: by-product of the first pass, or handed in
         const double hn = sqrt(hh_ptr != nullptr ? hh_ptr[0] : coef_a[cols_a]);
+        alpha[step] = a;
+        beta[step] = b;
+        hnorm[step] = hn;
+        flags[1] = step + 1;
+        const bool finite = (a - a == 0.0) && (b - b == 0.0) && (hn - hn == 0.0);
+        if (!finite) flags[0] = 2;
+        else if (!(b > tol * hn)) flags[0] = 1;
+        scal[0] = 1.0 / b;
+    }
+}
+
+// End of a Lanczos step when the full pass only removes rounding-level components (the local pass has
+// taken the rest): c holds the total coefficients (local + full) for `cols` columns and, in c[cols], the
+// squared norm of the vector x the full pass worked on; loc = {alpha~, beta~, ||H q||^2} are the local
+// parts added to the last two coefficients.  Then x - Q c_full has squared norm ||x||^2 - ||c_full||^2
+// up to (Q^T Q - I) c_full . c_full, far below fp64 rounding here, so beta is known BEFORE the
+// subtraction sweep, which can then write the normalised vector directly (no separate scaling sweep).
+__global__ __launch_bounds__(kThreads) void k_lanczos_finalize_early(
+    const double* __restrict__ c, int cols, const double* __restrict__ loc, int step, double tol,
+    double* __restrict__ alpha, double* __restrict__ beta, double* __restrict__ hnorm, double* __restrict__ scal,
+    int* flags) {
+    if (flags[0] != 0) return;
+    __shared__ double red[4];
+    double s = 0.0;
+    for (int j = threadIdx.x; j < cols; j += kThreads) {
+        double cf = c[j];
+        if (j == cols - 1) cf -= loc[0];
+        if (j == cols - 2) cf -= loc[1];
+        s = fma(cf, cf, s);
+    }
+    s = block_sum(s, red);
+    if (threadIdx.x == 0) {
+        const double a = c[cols - 1];
+        const double b2 = c[cols] - s;
+        const double b = b2 > 0.0 ? sqrt(b2) : (b2 == b2 ? 0.0 : b2);     // NaN stays NaN
+        const double hn = sqrt(loc[2]);
         alpha[step] = a;
         beta[step] = b;
         hnorm[step] = hn;
@@ -918,7 +958,7 @@ template <int RPT, int CU>
 int combine_columns_cfg(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const double* d, const float* y,
                         double a0, const float* x1, double a1, const float* x2, double a2, const float* x3,
                         bool local_dots, double sa, float* out, int64_t n, bool want_norm, const int* stop,
-                        int prof_cls, double prof_bytes) {
+                        int prof_cls, double prof_bytes, const double* oscale) {
     const int64_t n4 = n >> 2;
     const int64_t tile = (int64_t)kThreads * RPT;
     int64_t g = (n4 + tile - 1) / tile;
@@ -934,7 +974,7 @@ int combine_columns_cfg(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, c
     if (prof_cls >= 0) prof_begin(ctx, prof_cls, prof_bytes);
 #define FOSI_COMBINE(Y, X1, X2, NRM, LD)                                                                         \
     hipLaunchKernelGGL((k_combine_columns<Y, X1, X2, NRM, LD, RPT, CU>), dim3(grid), dim3(kThreads), 0, ctx->stream, \
-                       A, lda, ncols, d, y, a0, x1, a1, x2, a2, x3, sa, out, n, ctx->s.norm_partials, xcd_part, stop)
+                       A, lda, ncols, d, y, a0, x1, a1, x2, a2, x3, sa, out, n, ctx->s.norm_partials, xcd_part, oscale, stop)
     const bool hy = y != nullptr, h1 = x1 != nullptr, h2 = x2 != nullptr;
     if (!hy && h1 && !h2 && !want_norm && local_dots) FOSI_COMBINE(false, true, false, false, true);   // expand + local dots
     else if (!hy && h1 && !h2 && !want_norm) FOSI_COMBINE(false, true, false, false, false);     // operator expand
@@ -953,10 +993,10 @@ int combine_columns_cfg(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, c
 int launch_combine_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const double* d, const float* y,
                            double a0, const float* x1, double a1, const float* x2, double a2, const float* x3,
                            bool local_dots, double sa, float* out, int64_t n, bool want_norm, const int* stop,
-                           int prof_cls, double prof_bytes) {
+                           int prof_cls, double prof_bytes, const double* oscale) {
 #define FOSI_CFG(R, C)                                                                                            \
     return combine_columns_cfg<R, C>(ctx, A, lda, ncols, d, y, a0, x1, a1, x2, a2, x3, local_dots, sa, out, n,     \
-                                     want_norm, stop, prof_cls, prof_bytes)
+                                     want_norm, stop, prof_cls, prof_bytes, oscale)
     switch (ctx->tun.comb_rows_per_thread * 100 + ctx->tun.comb_cols_unroll) {
         case 108: FOSI_CFG(1, 8);
         case 116: FOSI_CFG(1, 16);
@@ -977,6 +1017,11 @@ void launch_lanczos_finalize(fosi_ctx* ctx, int step, int norm_slots, const doub
                        norm_parts != nullptr ? norm_parts : ctx->s.norm_partials, norm_slots,
                        coef_a, coef_b, cols_a, cols_b, hh, step, tol, ctx->s.alpha, ctx->s.beta, ctx->s.hnorm,
                        ctx->s.scal, ctx->s.flags);
+}
+
+void launch_lanczos_finalize_early(fosi_ctx* ctx, int step, const double* coef, int cols, double tol) {
+    hipLaunchKernelGGL(k_lanczos_finalize_early, dim3(1), dim3(kThreads), 0, ctx->stream, coef, cols, ctx->s.loc, step, tol,
+                       ctx->s.alpha, ctx->s.beta, ctx->s.hnorm, ctx->s.scal, ctx->s.flags);
 }
 
 void launch_reduce_local(fosi_ctx* ctx, int nslots, const int* stop, const double* parts) {
