@@ -117,7 +117,6 @@ fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
     ctx->tun.ritz_mfma = env_int("FOSI_RITZ_MFMA", 1);
     ctx->tun.step_waves_per_cu = env_int("FOSI_STEP_WAVES", 12);
     if (ctx->tun.step_waves_per_cu < 1) ctx->tun.step_waves_per_cu = 1;
-    ctx->tun.xcd_partition = env_int("FOSI_XCD_PARTITION", 0);
 
     const size_t cols1 = kMaxCols + 1;
     size_t off = 0;

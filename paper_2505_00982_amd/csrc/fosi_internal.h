@@ -28,7 +28,6 @@ struct Tunables {
     int dot_target_blocks;    // workgroups launched by the transposed product (it grid-strides over rows)
     int comb_rows_per_thread; // RPT: float4 row groups per thread in the column-combination kernel
     int comb_cols_unroll;     // CU: columns loaded together in that kernel
-    int xcd_partition;        // give each XCD a contiguous eighth of the rows (1) or interleave rows over all XCDs (0)
     int comb_max_blocks;      // cap on that kernel's grid (it grid-strides over row tiles); 0 = no cap
     int early_beta;           // 1 (default): 'local_full' runs take beta from the coefficients and normalise inside the subtraction
     int ritz_mfma;            // 1: Ritz vectors of up to 32 columns on the matrix cores (default), 0: vector ALUs

@@ -122,7 +122,7 @@ template <int JB, int NX>
 __global__ __launch_bounds__(kThreads) void k_dot_columns(
     const float* __restrict__ A, int64_t lda, int ncols, const float* __restrict__ x,
     const float* __restrict__ x2, const float* __restrict__ x3, const double* __restrict__ xs, int64_t n,
-    double* __restrict__ partials, int pstride, int S, int xcd_part, const int* __restrict__ stop) {
+    double* __restrict__ partials, int pstride, int S, const int* __restrict__ stop) {
     static_assert(JB == 32, "the sweep variants below cover slots of up to 32 columns");
     if (stop != nullptr && *stop != 0) return;
     const int lane = threadIdx.x & 63;
@@ -143,21 +143,10 @@ __global__ __launch_bounds__(kThreads) void k_dot_columns(
     double xx = 0.0;
 
     const int64_t n4 = n >> 2;
-    // Row ranges.  Workgroups are handed to the 8 XCDs round-robin, so with xcd_part every XCD is given
-    // one contiguous eighth of the rows.  (Correctness does not depend on how the hardware places workgroups.)
-    int64_t t_begin, r_end, stride;          // all uniform across the wave (float4 units)
-    if (xcd_part) {
-        const int nx = gridDim.x >> 3;                                     // gridDim.x is a multiple of 8
-        const int64_t chunk = ((n4 + 7) / 8 + 63) / 64 * 64;
-        const int part = blockIdx.x & 7;
-        t_begin = part * chunk + ((int64_t)(blockIdx.x >> 3) * rows_per_block + rowlane) * 64;
-        r_end = min(n4, (part + 1) * chunk);
-        stride = (int64_t)nx * rows_per_block * 64;
-    } else {
-        t_begin = ((int64_t)blockIdx.x * rows_per_block + rowlane) * 64;
-        r_end = n4;
-        stride = (int64_t)gridDim.x * rows_per_block * 64;
-    }
+    // row groups are handed out round-robin over (block, row lane); all uniform across the wave (float4 units)
+    const int64_t t_begin = ((int64_t)blockIdx.x * rows_per_block + rowlane) * 64;
+    const int64_t r_end = n4;
+    const int64_t stride = (int64_t)gridDim.x * rows_per_block * 64;
     const double s2 = NX >= 2 ? xs[0] : 0.0, s3 = NX >= 3 ? xs[1] : 0.0;
     const float* Aj0 = A + (int64_t)j0 * lda;
 #define FOSI_SWEEP(NC_) dot_sweep<NC_, NX>(Aj0, lda, nc, x, x2, x3, s2, s3, t_begin, r_end, stride, lane, do_xx, acc, xx)
@@ -297,7 +286,7 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
     const float* __restrict__ A, int64_t lda, int ncols, const double* __restrict__ d, const float* y,
     double a0, const float* __restrict__ x1, double a1, const float* __restrict__ x2, double a2,
     const float* __restrict__ x3, double sa, float* out, int64_t n, double* __restrict__ norm_partials,
-    int xcd_part, const double* __restrict__ oscale, const int* __restrict__ stop) {
+    const double* __restrict__ oscale, const int* __restrict__ stop) {
     if (stop != nullptr && *stop != 0) return;
     __shared__ double red[4];
     const double osc = oscale != nullptr ? oscale[0] : 1.0;   // device-side factor applied to the whole result
@@ -306,15 +295,7 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
     const int64_t tile = (int64_t)kThreads * RPT;
     const int64_t ntiles = (n4 + tile - 1) / tile;
     double nrm = 0.0, dot1 = 0.0, dot3 = 0.0;
-    // tile ranges: with xcd_part each XCD (workgroup index mod 8) owns one contiguous eighth of the tiles
-    int64_t t_begin = blockIdx.x, t_end = ntiles, t_step = gridDim.x;
-    if (xcd_part) {
-        const int64_t per = (ntiles + 7) / 8;
-        const int part = blockIdx.x & 7;
-        t_begin = part * per + (blockIdx.x >> 3);
-        t_end = min(ntiles, (part + 1) * per);
-        t_step = gridDim.x >> 3;
-    }
+    const int64_t t_begin = blockIdx.x, t_end = ntiles, t_step = gridDim.x;
     for (int64_t t = t_begin; t < t_end; t += t_step) {
         int64_t r4[RPT], rc[RPT];
 #pragma unroll
@@ -473,8 +454,10 @@ __global__ __launch_bounds__(512) void k_complement_reproject(
             return *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(x + base) + lane_bytes);
         };
         const float4 pg = vec4(g);
-        float4 pp = make_float4(0.f, 0.f, 0.f, 0.f), pw = pp, pv = pp;
-        if (has_pi) pp = vec4(pi);
+        // no branch around a load: without pi the gradient is read again (a cache hit) and dropped, so that all
+        // loads of the tile are issued back to back
+        float4 pp = vec4(has_pi ? pi : g), pw = make_float4(0.f, 0.f, 0.f, 0.f), pv = pw;
+        if (!has_pi) pp = pw;
         float4 pm = vec4(m);
         if (OPT == 1) {
             pw = vec4(w);
@@ -922,8 +905,6 @@ void dot_columns_launch(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, c
     if (cap < 1) cap = 1;
     if (gx > cap) gx = cap;
     if (gx < 1) gx = 1;
-    const int xcd_part = (ctx->tun.xcd_partition && gx >= 16) ? 1 : 0;
-    if (xcd_part) gx = gx / 8 * 8;
     const int rowslots = (int)gx * rows_per_block;
     const int pstride = ncols + 1;
     dim3 grid((unsigned)gx, (unsigned)gy);
@@ -931,13 +912,13 @@ void dot_columns_launch(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, c
     if (x2 != nullptr && xs == nullptr) xs = ctx->s.scal + 2;   // plain sum of the vectors: scales 1, 1
     if (x3 != nullptr)
         hipLaunchKernelGGL((k_dot_columns<JB, 3>), grid, dim3(kThreads), 0, ctx->stream, A, lda, ncols, x, x2, x3, xs, n,
-                           ctx->s.partials, pstride, S, xcd_part, stop);
+                           ctx->s.partials, pstride, S, stop);
     else if (x2 != nullptr)
         hipLaunchKernelGGL((k_dot_columns<JB, 2>), grid, dim3(kThreads), 0, ctx->stream, A, lda, ncols, x, x2, x3, xs, n,
-                           ctx->s.partials, pstride, S, xcd_part, stop);
+                           ctx->s.partials, pstride, S, stop);
     else
         hipLaunchKernelGGL((k_dot_columns<JB, 1>), grid, dim3(kThreads), 0, ctx->stream, A, lda, ncols, x, x2, x3, xs, n,
-                           ctx->s.partials, pstride, S, xcd_part, stop);
+                           ctx->s.partials, pstride, S, stop);
     if (prof_cls >= 0) prof_end(ctx);
     hipLaunchKernelGGL(k_reduce_columns, dim3(ncols + 1), dim3(64), 0, ctx->stream, ctx->s.partials, rowslots, pstride,
                        coef, scale, nscale, gscale, ncols, add_last2, stop);
@@ -965,16 +946,11 @@ int combine_columns_cfg(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, c
     if (g < 1) g = 1;
     if (g > kMaxNormSlots) g = kMaxNormSlots;
     if (ctx->tun.comb_max_blocks > 0 && g > ctx->tun.comb_max_blocks) g = ctx->tun.comb_max_blocks;
-    const int xcd_part = (ctx->tun.xcd_partition && g >= 16) ? 1 : 0;
-    if (xcd_part) {
-        g = (g + 7) / 8 * 8;
-        if (g > kMaxNormSlots) g = kMaxNormSlots;
-    }
     const int grid = (int)g;
     if (prof_cls >= 0) prof_begin(ctx, prof_cls, prof_bytes);
 #define FOSI_COMBINE(Y, X1, X2, NRM, LD)                                                                         \
     hipLaunchKernelGGL((k_combine_columns<Y, X1, X2, NRM, LD, RPT, CU>), dim3(grid), dim3(kThreads), 0, ctx->stream, \
-                       A, lda, ncols, d, y, a0, x1, a1, x2, a2, x3, sa, out, n, ctx->s.norm_partials, xcd_part, oscale, stop)
+                       A, lda, ncols, d, y, a0, x1, a1, x2, a2, x3, sa, out, n, ctx->s.norm_partials, oscale, stop)
     const bool hy = y != nullptr, h1 = x1 != nullptr, h2 = x2 != nullptr;
     if (!hy && h1 && !h2 && !want_norm && local_dots) FOSI_COMBINE(false, true, false, false, true);   // expand + local dots
     else if (!hy && h1 && !h2 && !want_norm) FOSI_COMBINE(false, true, false, false, false);     // operator expand
