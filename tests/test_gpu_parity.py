@@ -381,3 +381,42 @@ def test_callback_operator_matches_builtin(fo, ctx):
     assert m1 == m2 == 8 and np.array_equal(a1, a2) and np.array_equal(b1, b2)
     op1.close()
     op2.close()
+
+
+# ------------------------------------------------------------------ built-in maxima: 255 steps, rank 256
+def test_maximum_lanczos_length_and_planted_rank(fo, ctx):
+    """m + 1 = FOSI_MAX_COLS columns in the basis and a planted operator of rank FOSI_MAX_COLS: all eight column
+    slots of the transposed product, the widest Ritz coefficient block."""
+    n, r, m = 3001, 256, 255
+    rng = np.random.default_rng(11)
+    U = np.linalg.qr(rng.standard_normal((n, r)))[0].astype(np.float32)
+    lam = np.concatenate([np.geomspace(50.0, 0.5, r - 20), -np.geomspace(3.0, 0.3, 20)]).astype(np.float32)
+    shift = np.float32(0.05)
+    v1 = wl.normal_vector(1, 123, n)
+    ld = wl.padded_ld(n)
+    Ud = fo.ColMajor.from_numpy(U, ld)
+    op = ctx.hvp_planted(Ud, dev(lam), float(shift))
+    Q = fo.ColMajor(n, m + 1, ld)
+    Q.col(0).copy_(dev(v1))
+    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, m)
+    # at this length one classical Gram-Schmidt pass loses orthogonality completely even in fp64 (max |Q^T Q - I|
+    # = 1.0, Ritz values far outside the spectrum), so the oracle runs with its second pass here
+    res = oracle.lanczos(lambda v: oracle.hvp_planted(U, lam, float(shift), v), v1, m, passes=2)
+    assert m_eff == res.m_eff == m
+    Qh = Q.to_numpy(m).astype(np.float64)
+    assert np.abs(Qh.T @ Qh - np.eye(m)).max() < 1e-5
+    assert np.max(np.abs(alpha[:12] - res.alpha[:12])) < 1e-4 * 50 and np.max(np.abs(beta[:12] - res.beta[:12])) < 1e-4 * 50
+    for k, l in ((20, 12), (24, 16)):          # 32 columns: matrix-core Ritz kernel; 40: vector-ALU kernel
+        V = fo.ColMajor(n, k + l, ld)
+        evals, _ = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, k, l, V)
+        ctx.synchronize()
+        rz = oracle.ritz(res.Q, res.alpha, res.beta, res.m_eff, k, l)
+        conv = rz.resid <= 1e-6 * np.abs(rz.evals)
+        assert conv[:k].sum() >= 10
+        assert np.max(np.abs(evals - rz.evals)[conv] / np.abs(rz.evals)[conv]) <= EVAL_RTOL
+        Vg = V.to_numpy().astype(np.float64)
+        top = np.arange(k)[conv[:k]]
+        assert sin_principal_angles(rz.V[:, top], Vg[:, top]).max() < ANGLE_TOL
+        # every Ritz vector is Q S with orthonormal S: unit norm and mutually orthogonal to fp32 accuracy
+        assert np.abs(Vg.T @ Vg - np.eye(k + l)).max() < 1e-5
+    op.close()
