@@ -414,3 +414,31 @@ def test_oracle_reproduces_stored_values(cfg1):
                               float(p.alpha), float(p.lr), float(p.momentum))
     assert np.isclose(np.linalg.norm(w1 - w.w0), gold["step_update_norm"], rtol=1e-9)
     assert np.isclose(np.linalg.norm(b1), gold["momentum_norm"], rtol=1e-9)
+
+
+def test_second_pass_option_on_a_long_run():
+    """The oracle's optional second Gram-Schmidt pass, pinned where it matters: a run that nearly exhausts the
+    Krylov space (rank 128 + shift, 127 steps).  With it the basis is orthonormal to rounding, every Ritz value
+    lies inside the spectrum and the converged ones equal planted eigenvalues; the single pass of the printed
+    algorithm has lost orthogonality by then even in float64."""
+    n, r, m = 900, 128, 127
+    rng = np.random.default_rng(3)
+    U = np.linalg.qr(rng.standard_normal((n, r)))[0]
+    lam = np.concatenate([np.geomspace(40.0, 0.5, r - 10), -np.geomspace(2.0, 0.2, 10)])
+    shift = 0.05
+    v1 = rng.standard_normal(n)
+    hv = lambda v: U @ (lam * (U.T @ v)) + shift * v
+    two = oracle.lanczos(hv, v1, m, passes=2)
+    assert two.m_eff == m
+    Q = two.Q[:, :m]
+    assert np.abs(Q.T @ Q - np.eye(m)).max() < 1e-12
+    rz = oracle.ritz(two.Q, two.alpha, two.beta, two.m_eff, 12, 6)
+    truth = np.sort(np.concatenate([lam + shift, [shift]]))
+    assert rz.all_evals.min() >= truth[0] - 1e-9 and rz.all_evals.max() <= truth[-1] + 1e-9
+    conv = rz.resid <= 1e-9 * np.abs(rz.evals)
+    assert conv.sum() >= 12
+    for ev in rz.evals[conv]:
+        assert np.min(np.abs(truth - ev)) <= 1e-8 * max(1.0, abs(ev))
+    one = oracle.lanczos(hv, v1, m, passes=1)
+    Q1 = one.Q[:, : one.m_eff]
+    assert np.abs(Q1.T @ Q1 - np.eye(one.m_eff)).max() > 1e-6
