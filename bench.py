@@ -365,7 +365,8 @@ def main() -> int:
                                f"{' with ADMM begin/end' if w.admm else ''}",
                    "accumulation": "f64 products and sums, one rounding per stored fp32 vector",
                    "m_eff": state["m_eff"], "algorithmic_GB_per_step": round(step_bytes / 1e9, 1),
-                   "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4)},
+                   "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+                   "device": torch.cuda.get_device_name(0), "hip": getattr(torch.version, "hip", None)},
         "roofline": roofline,
         "phases": phases,
     }
