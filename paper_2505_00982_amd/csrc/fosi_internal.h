@@ -106,6 +106,8 @@ struct fosi_hvp {
     const unsigned short* Xb = nullptr;   // B x d bf16 (caller's)
     unsigned short* XTb = nullptr;        // d x B bf16 (transposed copy, owned)
     float* Y2 = nullptr;                  // split-K partials of the second product (owned)
+    unsigned short* S1 = nullptr;         // bf16 (hi, lo) pair of the first product's fp32 operand, C x d each (owned)
+    unsigned short* S2 = nullptr;         // ... of the second product's, C x B each (owned)
     // callback
     fosi_hvp_fn fn = nullptr;
     void* user = nullptr;

@@ -13,6 +13,32 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
+// Tile of a workgroup.  The hardware hands workgroups to the 8 XCDs round-robin (linear id mod 8) and each XCD
+// has an L2 of its own, so with the natural (x, y, z) mapping every XCD ends up touching all of A and all of B
+// and neither stays in its L2: at 8192 x 2048 x 1000 the product then pulls ~770 MB through the fabric for 40 MB
+// of operands and is bound by that traffic, not by the matrix cores.  Here XCD x takes a contiguous range of the
+// tile sequence (n fastest, then m, then the K split): the tiles that share a row block of A run on the same
+// XCD at the same time and the XCD's share of A is fetched once.  Launch ceil(T / 8) * 8 workgroups in one
+// dimension; returns false for the padding workgroups.
+__device__ __forceinline__ bool xcd_tile(int gn, int gm, int gz, int& tn, int& tm, int& tz) {
+    const int T = gn * gm * gz, per = (T + 7) / 8;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int t = xcd * per + slot;
+    if (slot >= per || t >= T) return false;
+    tn = t % gn;
+    tm = (t / gn) % gm;
+    tz = t / (gn * gm);
+    return true;
+}
+
+// Workgroup barrier for LDS hand-over inside the K loops.  __syncthreads() also waits for every outstanding
+// global load (vmcnt(0)), which would make the register lookahead of the loops below pointless: each K-step
+// would again pay a full memory round trip.  Here only LDS traffic is drained; the global loads in flight
+// target registers that no other wave touches.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 constexpr int TM = 64, TN = 64, TK = 16;   // workgroup tile; each of the 4 waves owns a 32 x 32 quadrant
 constexpr int LDT = TM + 4;
 
@@ -22,13 +48,15 @@ constexpr int LDT = TM + 4;
 template <bool A_KM, bool VEC>
 __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, int lda, const float* __restrict__ Bm,
                                                   int ldb, float* __restrict__ Cout, int ldc, int M, int N, int K,
-                                                  int klen, int64_t cstride, float scale) {
+                                                  int klen, int nsplit, int64_t cstride, float scale) {
     __shared__ float As[2][TK][LDT];   // [k][m]
     __shared__ float Bs[2][TK][LDT];   // [k][n]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32;
-    const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
-    const int kbeg = blockIdx.z * klen;
+    int tn, tm, tz;
+    if (!xcd_tile((N + TN - 1) / TN, (M + TM - 1) / TM, nsplit, tn, tm, tz)) return;
+    const int m0 = tm * TM, n0 = tn * TN;
+    const int kbeg = tz * klen;
     const int kend = min(K, kbeg + klen);
 
     // this thread's slots in the two tiles
@@ -103,9 +131,9 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, i
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
         }
         if (kt + 1 < nk) store(buf ^ 1);
-        __syncthreads();
+        lds_barrier();
     }
-    float* Cz = Cout + (int64_t)blockIdx.z * cstride;
+    float* Cz = Cout + (int64_t)tz * cstride;
     const int col = n0 + wn + l32;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -186,21 +214,27 @@ __global__ __launch_bounds__(256) void k_softmax_jacobian(float* __restrict__ pa
 
 // ---------------------------------------------------------------- bf16 matrix cores, split operand
 // C[z] (M x N, row-major, ldc) = A[:, kz] * B[kz, :] with A given in bf16 (M x K row-major, k
-// contiguous) and B in fp32 (K x N row-major).  Every B element is split on the fly, while its tile is
-// staged into LDS, into two bf16 values, b = hi + lo with |b - hi - lo| <= 2^-18 |b|, and both parts go
-// through v_mfma_f32_32x32x16_bf16 with fp32 accumulation: the data matrix is exact in bf16, the
-// vector operand keeps ~17 bits, at twice the bf16 cost instead of the 16x more expensive fp32 matrix
-// path.  (Splitting B once per product in a kernel of its own was measured too: the product itself is
-// no faster and the two extra launches cost 10 %.)  Workgroup tile 128 x 128, K-step 32; the four
-// waves own 64 x 64 quadrants (2 x 2 MFMA tiles).  Operand layout of the instruction (checked against
-// a host product): lane l supplies, for A, row l % 32 and the 8 consecutive k values starting at
-// 8 (l / 32); for B, column l % 32 and the same k values; so both tiles sit in LDS with k contiguous
-// and are fetched with 16-byte reads.
+// contiguous) and the fp32 matrix B (K x N) given as two bf16 matrices, b = hi + lo with
+// |b - hi - lo| <= 2^-18 |b| (k_split_transpose), both stored transposed (N x K, k contiguous).  Both
+// parts go through v_mfma_f32_32x32x16_bf16 with fp32 accumulation: the data matrix is exact in bf16,
+// the vector operand keeps ~17 bits, at twice the bf16 cost instead of the 16x more expensive fp32
+// matrix path.  Workgroup tile 128 x 128, K-step 32; the four waves own 64 x 64 quadrants (2 x 2 MFMA
+// tiles).  Operand layout of the instruction (checked against a host product): lane l supplies, for
+// A, row l % 32 and the 8 consecutive k values starting at 8 (l / 32); for B, column l % 32 and the
+// same k values; so all three tiles sit in LDS with k contiguous, are staged with 16-byte copies and
+// fetched with 16-byte reads.
+// What was measured on the way (batch 8192 x 2048 x 1000, per product of 33.5 GFLOP): splitting B
+// inside this kernel while staging it costs ~300 vector instructions per wave and K-step, more than
+// the 16 matrix instructions take (114 us); selects on loaded values let the compiler put every load
+// under a branch that ends in a full wait, eight memory round trips per K-step (114 us as well, with
+// either variant of the split) -- hence the split in a kernel of its own, unconditional loads with
+// clamped addresses, masks applied when the registers are consumed, and PF K-steps of lookahead.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned short ushort8 __attribute__((ext_vector_type(8)));
 
 constexpr int BM = 128, BN = 128, BK = 32;
 constexpr int LDK = BK + 8;    // LDS row stride in bf16 (80 bytes: an odd number of 16-byte units, conflict-free reads)
+constexpr int PF = 3;          // K-steps of register lookahead for the global loads
 
 __device__ __forceinline__ unsigned short bf16_round(float f) {      // round to nearest even; finite inputs
     unsigned int u = __float_as_uint(f);
@@ -209,61 +243,111 @@ __device__ __forceinline__ unsigned short bf16_round(float f) {      // round to
 }
 __device__ __forceinline__ float bf16_value(unsigned short h) { return __uint_as_float((unsigned int)h << 16); }
 
+// hi_t[n, k], lo_t[n, k] (N x K, leading dimension ldt) from src[k, n] (K x N row-major, leading dimension lds_).
+__global__ __launch_bounds__(256) void k_split_transpose(const float* __restrict__ src, int K, int N, int lds_,
+                                                         unsigned short* __restrict__ hi_t,
+                                                         unsigned short* __restrict__ lo_t, int ldt) {
+    __shared__ unsigned short th[32][33], tl[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+    const int n0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+    for (int i = ty; i < 32; i += 8) {
+        const int k = k0 + i, n = n0 + tx;
+        float v = 0.f;
+        if (k < K && n < N) v = src[(int64_t)k * lds_ + n];
+        const unsigned short hi = bf16_round(v);
+        th[i][tx] = hi;
+        tl[i][tx] = bf16_round(v - bf16_value(hi));
+    }
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) {
+        const int n = n0 + i, k = k0 + tx;
+        if (n < N && k < K) {
+            hi_t[(int64_t)n * ldt + k] = th[tx][i];
+            lo_t[(int64_t)n * ldt + k] = tl[tx][i];
+        }
+    }
+}
+
+// VEC: all three matrices have 16-byte aligned rows and K is a multiple of 16 (a 16-value chunk then lies
+// inside the K range of the split or outside it).
 template <bool VEC>
 __global__ __launch_bounds__(256) void k_gemm_bf16x2(const unsigned short* __restrict__ A, int lda,
-                                                     const float* __restrict__ Bm, int ldb, float* __restrict__ Cout,
-                                                     int ldc, int M, int N, int K, int klen, int64_t cstride,
-                                                     float scale) {
+                                                     const unsigned short* __restrict__ Bht,
+                                                     const unsigned short* __restrict__ Blt, int ldbt,
+                                                     float* __restrict__ Cout, int ldc, int M, int N, int K, int klen,
+                                                     int nsplit, int64_t cstride, float scale) {
     __shared__ __attribute__((aligned(16))) unsigned short As[2][BM][LDK];
     __shared__ __attribute__((aligned(16))) unsigned short Bh[2][BN][LDK];
     __shared__ __attribute__((aligned(16))) unsigned short Bl[2][BN][LDK];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-    const int kbeg = blockIdx.z * klen;
+    int tn, tm, tz;
+    if (!xcd_tile((N + BN - 1) / BN, (M + BM - 1) / BM, nsplit, tn, tm, tz)) return;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int kbeg = tz * klen;
     const int kend = min(K, kbeg + klen);
 
-    // staging slots: A tile: row tid / 2, 16 k values; B tile: column tid % 128, 16 k values
-    const int arow = tid >> 1, ak = (tid & 1) * 16;
-    const int bn = tid & 127, bkg = (tid >> 7) * 16;
-    ushort8 ra[2];
-    float rb[16];
+    // staging slot of this thread in each of the three tiles: row tid / 2, 16 consecutive k values
+    const int srow = tid >> 1, sk = (tid & 1) * 16;
+    const int am = m0 + srow, bn = n0 + srow;
+    const unsigned short* pa = A + (int64_t)min(am, M - 1) * lda;
+    const unsigned short* ph = Bht + (int64_t)min(bn, N - 1) * ldbt;
+    const unsigned short* pl = Blt + (int64_t)min(bn, N - 1) * ldbt;
+    ushort8 r[PF][6];
 
-    auto load = [&](int k0) {
-        const int m = m0 + arow, k = k0 + ak;
-        const unsigned short* pa = A + (int64_t)m * lda + k;
-        if (VEC && m < M && k + 15 < kend) {
-            ra[0] = *reinterpret_cast<const ushort8*>(pa);
-            ra[1] = *reinterpret_cast<const ushort8*>(pa + 8);
+    // raw loads from clamped (always valid) addresses; the masks are applied in store(), when the registers
+    // are consumed, so that nothing here waits for memory
+    auto load = [&](int k0, ushort8* q) {
+        const int k = k0 + sk;
+        if (VEC) {
+            const int kc = k < kend ? k : 0;
+            q[0] = *reinterpret_cast<const ushort8*>(pa + kc);
+            q[1] = *reinterpret_cast<const ushort8*>(pa + kc + 8);
+            q[2] = *reinterpret_cast<const ushort8*>(ph + kc);
+            q[3] = *reinterpret_cast<const ushort8*>(ph + kc + 8);
+            q[4] = *reinterpret_cast<const ushort8*>(pl + kc);
+            q[5] = *reinterpret_cast<const ushort8*>(pl + kc + 8);
         } else {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const unsigned short v = (m < M && k + i < kend) ? pa[i] : (unsigned short)0;
-                if (i < 8) ra[0][i] = v; else ra[1][i - 8] = v;
+                const int kc = min(k + i, K - 1);
+                q[i >> 3][i & 7] = pa[kc];
+                q[2 + (i >> 3)][i & 7] = ph[kc];
+                q[4 + (i >> 3)][i & 7] = pl[kc];
             }
         }
-        const int n = n0 + bn;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int kk = k0 + bkg + i;
-            rb[i] = (n < N && kk < kend) ? Bm[(int64_t)kk * ldb + n] : 0.f;
-        }
     };
-    auto store = [&](int buf) {
-        *reinterpret_cast<ushort8*>(&As[buf][arow][ak]) = ra[0];
-        *reinterpret_cast<ushort8*>(&As[buf][arow][ak + 8]) = ra[1];
-        ushort8 h[2], l[2];
+    auto store = [&](int buf, int k0, const ushort8* q) {
+        const int k = k0 + sk;
+        ushort8 t[6];
+        if (VEC) {     // a 16-value chunk is inside the K range or outside: one mask per tile row, four dword ANDs per vector
+            typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+            const unsigned int keep_a = (am < M && k < kend) ? 0xffffffffu : 0u;
+            const unsigned int keep_b = (bn < N && k < kend) ? 0xffffffffu : 0u;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const unsigned short hi = bf16_round(rb[i]);
-            const unsigned short lo = bf16_round(rb[i] - bf16_value(hi));
-            if (i < 8) { h[0][i] = hi; l[0][i] = lo; } else { h[1][i - 8] = hi; l[1][i - 8] = lo; }
+            for (int j = 0; j < 6; ++j) {
+                uint4v w = __builtin_bit_cast(uint4v, q[j]);
+                w &= (j < 2 ? keep_a : keep_b);
+                t[j] = __builtin_bit_cast(ushort8, w);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 6; ++j) {
+                const bool row_ok = j < 2 ? am < M : bn < N;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const unsigned short keep = (row_ok && k + 8 * (j & 1) + i < kend) ? (unsigned short)0xffff : (unsigned short)0;
+                    t[j][i] = q[j][i] & keep;
+                }
+            }
         }
-        *reinterpret_cast<ushort8*>(&Bh[buf][bn][bkg]) = h[0];
-        *reinterpret_cast<ushort8*>(&Bh[buf][bn][bkg + 8]) = h[1];
-        *reinterpret_cast<ushort8*>(&Bl[buf][bn][bkg]) = l[0];
-        *reinterpret_cast<ushort8*>(&Bl[buf][bn][bkg + 8]) = l[1];
+        *reinterpret_cast<ushort8*>(&As[buf][srow][sk]) = t[0];
+        *reinterpret_cast<ushort8*>(&As[buf][srow][sk + 8]) = t[1];
+        *reinterpret_cast<ushort8*>(&Bh[buf][srow][sk]) = t[2];
+        *reinterpret_cast<ushort8*>(&Bh[buf][srow][sk + 8]) = t[3];
+        *reinterpret_cast<ushort8*>(&Bl[buf][srow][sk]) = t[4];
+        *reinterpret_cast<ushort8*>(&Bl[buf][srow][sk + 8]) = t[5];
     };
 
     floatx16 acc[2][2];
@@ -275,39 +359,46 @@ __global__ __launch_bounds__(256) void k_gemm_bf16x2(const unsigned short* __res
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     const int nk = (kend - kbeg + BK - 1) / BK;
-    if (nk > 0) {
-        load(kbeg);
-        store(0);
-    }
+    // (steps past the end of the K range load clamped addresses and are never stored)
+#pragma unroll
+    for (int u = 0; u < PF; ++u) load(kbeg + u * BK, r[u]);
+    if (nk > 0) store(0, kbeg, r[0]);
     __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) load(kbeg + (kt + 1) * BK);       // next tile into registers while this one is multiplied
+    for (int kt0 = 0; kt0 < nk; kt0 += PF) {
 #pragma unroll
-        for (int ks = 0; ks < BK; ks += 16) {
-            bf16x8 a[2], bh[2], bl[2];
+        for (int u = 0; u < PF; ++u) {
+            const int kt = kt0 + u;
+            if (kt < nk) {                                     // uniform
+                const int buf = kt & 1;
+                // the registers of step kt went to LDS one step ago: refill them with step kt + PF
+                load(kbeg + (kt + PF) * BK, r[u]);
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                a[i] = *reinterpret_cast<const bf16x8*>(&As[buf][wm + 32 * i + l32][ks + 8 * half]);
-                bh[i] = *reinterpret_cast<const bf16x8*>(&Bh[buf][wn + 32 * i + l32][ks + 8 * half]);
-                bl[i] = *reinterpret_cast<const bf16x8*>(&Bl[buf][wn + 32 * i + l32][ks + 8 * half]);
+                for (int ks = 0; ks < BK; ks += 16) {
+                    bf16x8 a[2], bh[2], bl[2];
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        a[i] = *reinterpret_cast<const bf16x8*>(&As[buf][wm + 32 * i + l32][ks + 8 * half]);
+                        bh[i] = *reinterpret_cast<const bf16x8*>(&Bh[buf][wn + 32 * i + l32][ks + 8 * half]);
+                        bl[i] = *reinterpret_cast<const bf16x8*>(&Bl[buf][wn + 32 * i + l32][ks + 8 * half]);
+                    }
+                    // the small parts first; four independent accumulators between the two uses of each one
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bl[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bh[j], acc[i][j], 0, 0, 0);
+                }
+                if (kt + 1 < nk) store(buf ^ 1, kbeg + (kt + 1) * BK, r[(u + 1) % PF]);
+                lds_barrier();
             }
-            // the small parts first; four independent accumulators between the two uses of each one
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bl[j], acc[i][j], 0, 0, 0);
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bh[j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < nk) store(buf ^ 1);
-        __syncthreads();
     }
-    float* Cz = Cout + (int64_t)blockIdx.z * cstride;
+    float* Cz = Cout + (int64_t)tz * cstride;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -363,15 +454,16 @@ GemmPlan plan_split(int M, int N, int K, int sm_count) {
 template <bool A_KM>
 void launch_gemm(fosi_ctx* ctx, const float* A, int lda, const float* Bm, int ldb, float* Cout, int ldc, int M, int N,
                  int K, GemmPlan plan, int64_t cstride, float scale) {
-    const dim3 grid((N + TN - 1) / TN, (M + TM - 1) / TM, plan.nsplit);
+    const int tiles = ((N + TN - 1) / TN) * ((M + TM - 1) / TM) * plan.nsplit;
+    const dim3 grid((tiles + 7) / 8 * 8);
     const bool vec = (lda % 4 == 0) && (ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(A) & 15) == 0) &&
                      ((reinterpret_cast<uintptr_t>(Bm) & 15) == 0);
     if (vec)
         hipLaunchKernelGGL((k_gemm_f32<A_KM, true>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N, K,
-                           plan.klen, cstride, scale);
+                           plan.klen, plan.nsplit, cstride, scale);
     else
         hipLaunchKernelGGL((k_gemm_f32<A_KM, false>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N, K,
-                           plan.klen, cstride, scale);
+                           plan.klen, plan.nsplit, cstride, scale);
 }
 
 GemmPlan plan_split_bf16(int M, int N, int K, int sm_count) {
@@ -385,16 +477,25 @@ GemmPlan plan_split_bf16(int M, int N, int K, int sm_count) {
     return {s, klen};
 }
 
-void launch_gemm_bf16(fosi_ctx* ctx, const unsigned short* A, int lda, const float* Bm, int ldb, float* Cout, int ldc,
-                      int M, int N, int K, GemmPlan plan, int64_t cstride, float scale) {
-    const dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM, plan.nsplit);
-    const bool vec = (lda % 8 == 0) && ((reinterpret_cast<uintptr_t>(A) & 15) == 0) && (plan.klen % 16 == 0);
+// Splits the fp32 matrix Bm (K x N row-major) into the operator's transposed bf16 pair (sh, sl: N x ldt), then
+// C = A * Bm on the bf16 matrix cores.
+void launch_gemm_bf16(fosi_ctx* ctx, const unsigned short* A, int lda, const float* Bm, int ldb, unsigned short* sh,
+                      unsigned short* sl, float* Cout, int ldc, int M, int N, int K, GemmPlan plan, int64_t cstride,
+                      float scale) {
+    const int ldt = (K + 7) / 8 * 8;
+    hipLaunchKernelGGL(k_split_transpose, dim3((N + 31) / 32, (K + 31) / 32), dim3(256), 0, ctx->stream, Bm, K, N, ldb, sh,
+                       sl, ldt);
+    const int tiles = ((N + BN - 1) / BN) * ((M + BM - 1) / BM) * plan.nsplit;
+    const dim3 grid((tiles + 7) / 8 * 8);
+    const bool vec = (lda % 8 == 0) && (K % 16 == 0) && (plan.klen % 16 == 0) &&
+                     ((reinterpret_cast<uintptr_t>(A) & 15) == 0) && ((reinterpret_cast<uintptr_t>(sh) & 15) == 0) &&
+                     ((reinterpret_cast<uintptr_t>(sl) & 15) == 0);
     if (vec)
-        hipLaunchKernelGGL((k_gemm_bf16x2<true>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N, K,
-                           plan.klen, cstride, scale);
+        hipLaunchKernelGGL((k_gemm_bf16x2<true>), grid, dim3(256), 0, ctx->stream, A, lda, sh, sl, ldt, Cout, ldc, M, N, K,
+                           plan.klen, plan.nsplit, cstride, scale);
     else
-        hipLaunchKernelGGL((k_gemm_bf16x2<false>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N, K,
-                           plan.klen, cstride, scale);
+        hipLaunchKernelGGL((k_gemm_bf16x2<false>), grid, dim3(256), 0, ctx->stream, A, lda, sh, sl, ldt, Cout, ldc, M, N, K,
+                           plan.klen, plan.nsplit, cstride, scale);
 }
 
 }  // namespace
@@ -408,12 +509,20 @@ fosi_status ggn_prepare(fosi_hvp* op) {
         if (hipMalloc(reinterpret_cast<void**>(&op->P), bc * sizeof(float)) != hipSuccess ||
             hipMalloc(reinterpret_cast<void**>(&op->Z), bc * sizeof(float) * p1.nsplit) != hipSuccess ||
             hipMalloc(reinterpret_cast<void**>(&op->XTb), (size_t)B * d * sizeof(unsigned short)) != hipSuccess ||
-            hipMalloc(reinterpret_cast<void**>(&op->Y2), (size_t)d * C * sizeof(float) * p2.nsplit) != hipSuccess)
+            hipMalloc(reinterpret_cast<void**>(&op->Y2), (size_t)d * C * sizeof(float) * p2.nsplit) != hipSuccess ||
+            hipMalloc(reinterpret_cast<void**>(&op->S1), 2 * (size_t)C * ((d + 7) / 8 * 8) * sizeof(unsigned short)) != hipSuccess ||
+            hipMalloc(reinterpret_cast<void**>(&op->S2), 2 * (size_t)C * ((B + 7) / 8 * 8) * sizeof(unsigned short)) != hipSuccess)
             return fail(ctx, FOSI_ERR_NOMEM, "softmax-GGN work buffers");
+        // the split kernel leaves the padding columns of a row (k in [K, ldt)) untouched: clear them once, the
+        // product reads whole 16-byte chunks
+        (void)hipMemsetAsync(op->S1, 0, 2 * (size_t)C * ((d + 7) / 8 * 8) * sizeof(unsigned short), ctx->stream);
+        (void)hipMemsetAsync(op->S2, 0, 2 * (size_t)C * ((B + 7) / 8 * 8) * sizeof(unsigned short), ctx->stream);
+        unsigned short* s1h = op->S1;
+        unsigned short* s1l = op->S1 + (size_t)C * ((d + 7) / 8 * 8);
         hipLaunchKernelGGL(k_transpose_u16, dim3((d + 31) / 32, (B + 31) / 32), dim3(256), 0, ctx->stream, op->Xb, B, d,
                            op->XTb);
         // P = softmax(X W)
-        launch_gemm_bf16(ctx, op->Xb, d, op->W, C, op->Z, C, B, C, d, p1, (int64_t)bc, 1.f);
+        launch_gemm_bf16(ctx, op->Xb, d, op->W, C, s1h, s1l, op->Z, C, B, C, d, p1, (int64_t)bc, 1.f);
         hipLaunchKernelGGL(k_row_softmax, dim3(B), dim3(256), 0, ctx->stream, op->Z, p1.nsplit, (int64_t)bc, C, op->P);
         return check_hip(ctx, hipGetLastError(), "softmax-GGN prepare");
     }
@@ -434,13 +543,17 @@ fosi_status ggn_apply(fosi_hvp* op, const float* v, float* hv) {
     if (op->bf16) {
         const GemmPlan p1 = plan_split_bf16(B, C, d, ctx->sm_count), p2 = plan_split_bf16(d, C, B, ctx->sm_count);
         const int64_t dc = (int64_t)d * C;
+        unsigned short* s1h = op->S1;
+        unsigned short* s1l = op->S1 + (size_t)C * ((d + 7) / 8 * 8);
+        unsigned short* s2h = op->S2;
+        unsigned short* s2l = op->S2 + (size_t)C * ((B + 7) / 8 * 8);
         // Z = X V (split along d), Y = softmax-Jacobian rows of Z, hv = X^T Y / B (split along the batch)
-        launch_gemm_bf16(ctx, op->Xb, d, v, C, op->Z, C, B, C, d, p1, bc, 1.f);
+        launch_gemm_bf16(ctx, op->Xb, d, v, C, s1h, s1l, op->Z, C, B, C, d, p1, bc, 1.f);
         hipLaunchKernelGGL(k_softmax_jacobian, dim3(B), dim3(256), 0, ctx->stream, op->Z, p1.nsplit, bc, C, op->P);
         if (p2.nsplit == 1) {
-            launch_gemm_bf16(ctx, op->XTb, B, op->Z, C, hv, C, d, C, B, p2, 0, 1.f / (float)B);
+            launch_gemm_bf16(ctx, op->XTb, B, op->Z, C, s2h, s2l, hv, C, d, C, B, p2, 0, 1.f / (float)B);
         } else {
-            launch_gemm_bf16(ctx, op->XTb, B, op->Z, C, op->Y2, C, d, C, B, p2, dc, 1.f);
+            launch_gemm_bf16(ctx, op->XTb, B, op->Z, C, s2h, s2l, op->Y2, C, d, C, B, p2, dc, 1.f);
             int64_t g = (dc + 255) / 256;
             if (g > 4096) g = 4096;
             hipLaunchKernelGGL(k_sum_splits, dim3((unsigned)g), dim3(256), 0, ctx->stream, op->Y2, p2.nsplit, dc, dc,
@@ -462,6 +575,10 @@ void ggn_release(fosi_hvp* op) {
     if (op->Z != nullptr) (void)hipFree(op->Z);
     if (op->XTb != nullptr) (void)hipFree(op->XTb);
     if (op->Y2 != nullptr) (void)hipFree(op->Y2);
+    if (op->S1 != nullptr) (void)hipFree(op->S1);
+    if (op->S2 != nullptr) (void)hipFree(op->S2);
+    op->S1 = nullptr;
+    op->S2 = nullptr;
     op->P = nullptr;
     op->Z = nullptr;
     op->XTb = nullptr;
