@@ -218,8 +218,8 @@ __global__ __launch_bounds__(256) void k_softmax_jacobian(float* __restrict__ pa
 // |b - hi - lo| <= 2^-18 |b| (k_split_transpose), both stored transposed (N x K, k contiguous).  Both
 // parts go through v_mfma_f32_32x32x16_bf16 with fp32 accumulation: the data matrix is exact in bf16,
 // the vector operand keeps ~17 bits, at twice the bf16 cost instead of the 16x more expensive fp32
-// matrix path.  Workgroup tile 128 x 128, K-step 32; the four waves own 64 x 64 quadrants (2 x 2 MFMA
-// tiles).  Operand layout of the instruction (checked against a host product): lane l supplies, for
+// matrix path.  Workgroup tile 128 x 128, K-step 64, one set of LDS tiles (two barriers per K-step); the
+// four waves own 64 x 64 quadrants (2 x 2 MFMA tiles).  Operand layout of the instruction (checked against a host product): lane l supplies, for
 // A, row l % 32 and the 8 consecutive k values starting at 8 (l / 32); for B, column l % 32 and the
 // same k values; so all three tiles sit in LDS with k contiguous, are staged with 16-byte copies and
 // fetched with 16-byte reads.
@@ -232,9 +232,9 @@ __global__ __launch_bounds__(256) void k_softmax_jacobian(float* __restrict__ pa
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned short ushort8 __attribute__((ext_vector_type(8)));
 
-constexpr int BM = 128, BN = 128, BK = 32;
-constexpr int LDK = BK + 8;    // LDS row stride in bf16 (80 bytes: an odd number of 16-byte units, conflict-free reads)
-constexpr int PF = 3;          // K-steps of register lookahead for the global loads
+constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int LDK = BK + 8;    // LDS row stride in bf16 (144 bytes: an odd number of 16-byte units, conflict-free reads)
+constexpr int PF = 2;          // K-steps of register lookahead for the global loads
 
 __device__ __forceinline__ unsigned short bf16_round(float f) {      // round to nearest even; finite inputs
     unsigned int u = __float_as_uint(f);
@@ -268,17 +268,17 @@ __global__ __launch_bounds__(256) void k_split_transpose(const float* __restrict
     }
 }
 
-// VEC: all three matrices have 16-byte aligned rows and K is a multiple of 16 (a 16-value chunk then lies
+// VEC: all three matrices have 16-byte aligned rows and K is a multiple of 8 (an 8-value chunk then lies
 // inside the K range of the split or outside it).
 template <bool VEC>
-__global__ __launch_bounds__(256) void k_gemm_bf16x2(const unsigned short* __restrict__ A, int lda,
+__global__ __launch_bounds__(256, 2) void k_gemm_bf16x2(const unsigned short* __restrict__ A, int lda,
                                                      const unsigned short* __restrict__ Bht,
                                                      const unsigned short* __restrict__ Blt, int ldbt,
                                                      float* __restrict__ Cout, int ldc, int M, int N, int K, int klen,
                                                      int nsplit, int64_t cstride, float scale) {
-    __shared__ __attribute__((aligned(16))) unsigned short As[2][BM][LDK];
-    __shared__ __attribute__((aligned(16))) unsigned short Bh[2][BN][LDK];
-    __shared__ __attribute__((aligned(16))) unsigned short Bl[2][BN][LDK];
+    __shared__ __attribute__((aligned(16))) unsigned short As[BM][LDK];
+    __shared__ __attribute__((aligned(16))) unsigned short Bh[BN][LDK];
+    __shared__ __attribute__((aligned(16))) unsigned short Bl[BN][LDK];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, half = lane >> 5;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
@@ -288,66 +288,67 @@ __global__ __launch_bounds__(256) void k_gemm_bf16x2(const unsigned short* __res
     const int kbeg = tz * klen;
     const int kend = min(K, kbeg + klen);
 
-    // staging slot of this thread in each of the three tiles: row tid / 2, 16 consecutive k values
-    const int srow = tid >> 1, sk = (tid & 1) * 16;
-    const int am = m0 + srow, bn = n0 + srow;
-    const unsigned short* pa = A + (int64_t)min(am, M - 1) * lda;
-    const unsigned short* ph = Bht + (int64_t)min(bn, N - 1) * ldbt;
-    const unsigned short* pl = Blt + (int64_t)min(bn, N - 1) * ldbt;
-    ushort8 r[PF][6];
+    // staging: 8 consecutive lanes cover the 128 bytes (64 k values) of one tile row, so a wave instruction
+    // touches 8 cache lines (not 32) and writes LDS without bank conflicts; a thread owns the 16-byte chunk
+    // sc of rows sr, sr + 32, sr + 64, sr + 96 in each of the three tiles.
+    const int sc = (tid & 7) * 8, sr = tid >> 3;
+    ushort8 r[PF][12];
 
     // raw loads from clamped (always valid) addresses; the masks are applied in store(), when the registers
     // are consumed, so that nothing here waits for memory
     auto load = [&](int k0, ushort8* q) {
-        const int k = k0 + sk;
-        if (VEC) {
-            const int kc = k < kend ? k : 0;
-            q[0] = *reinterpret_cast<const ushort8*>(pa + kc);
-            q[1] = *reinterpret_cast<const ushort8*>(pa + kc + 8);
-            q[2] = *reinterpret_cast<const ushort8*>(ph + kc);
-            q[3] = *reinterpret_cast<const ushort8*>(ph + kc + 8);
-            q[4] = *reinterpret_cast<const ushort8*>(pl + kc);
-            q[5] = *reinterpret_cast<const ushort8*>(pl + kc + 8);
-        } else {
+        const int k = k0 + sc;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int kc = min(k + i, K - 1);
-                q[i >> 3][i & 7] = pa[kc];
-                q[2 + (i >> 3)][i & 7] = ph[kc];
-                q[4 + (i >> 3)][i & 7] = pl[kc];
-            }
-        }
-    };
-    auto store = [&](int buf, int k0, const ushort8* q) {
-        const int k = k0 + sk;
-        ushort8 t[6];
-        if (VEC) {     // a 16-value chunk is inside the K range or outside: one mask per tile row, four dword ANDs per vector
-            typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
-            const unsigned int keep_a = (am < M && k < kend) ? 0xffffffffu : 0u;
-            const unsigned int keep_b = (bn < N && k < kend) ? 0xffffffffu : 0u;
-#pragma unroll
-            for (int j = 0; j < 6; ++j) {
-                uint4v w = __builtin_bit_cast(uint4v, q[j]);
-                w &= (j < 2 ? keep_a : keep_b);
-                t[j] = __builtin_bit_cast(ushort8, w);
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < 6; ++j) {
-                const bool row_ok = j < 2 ? am < M : bn < N;
+        for (int j = 0; j < 4; ++j) {
+            const int row = sr + 32 * j;
+            const unsigned short* pa = A + (int64_t)min(m0 + row, M - 1) * lda;
+            const unsigned short* ph = Bht + (int64_t)min(n0 + row, N - 1) * ldbt;
+            const unsigned short* pl = Blt + (int64_t)min(n0 + row, N - 1) * ldbt;
+            if (VEC) {
+                const int kc = k < kend ? k : 0;
+                q[j] = *reinterpret_cast<const ushort8*>(pa + kc);
+                q[4 + j] = *reinterpret_cast<const ushort8*>(ph + kc);
+                q[8 + j] = *reinterpret_cast<const ushort8*>(pl + kc);
+            } else {
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const unsigned short keep = (row_ok && k + 8 * (j & 1) + i < kend) ? (unsigned short)0xffff : (unsigned short)0;
-                    t[j][i] = q[j][i] & keep;
+                    const int kc = min(k + i, K - 1);
+                    q[j][i] = pa[kc];
+                    q[4 + j][i] = ph[kc];
+                    q[8 + j][i] = pl[kc];
                 }
             }
         }
-        *reinterpret_cast<ushort8*>(&As[buf][srow][sk]) = t[0];
-        *reinterpret_cast<ushort8*>(&As[buf][srow][sk + 8]) = t[1];
-        *reinterpret_cast<ushort8*>(&Bh[buf][srow][sk]) = t[2];
-        *reinterpret_cast<ushort8*>(&Bh[buf][srow][sk + 8]) = t[3];
-        *reinterpret_cast<ushort8*>(&Bl[buf][srow][sk]) = t[4];
-        *reinterpret_cast<ushort8*>(&Bl[buf][srow][sk + 8]) = t[5];
+    };
+    auto store = [&](int k0, const ushort8* q) {
+        const int k = k0 + sc;
+        typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int row = sr + 32 * j;
+            ushort8 t[3];
+            if (VEC) {     // one mask per chunk: four dword ANDs per vector
+                const unsigned int keep_a = (m0 + row < M && k < kend) ? 0xffffffffu : 0u;
+                const unsigned int keep_b = (n0 + row < N && k < kend) ? 0xffffffffu : 0u;
+#pragma unroll
+                for (int w = 0; w < 3; ++w) {
+                    uint4v x = __builtin_bit_cast(uint4v, q[4 * w + j]);
+                    x &= (w == 0 ? keep_a : keep_b);
+                    t[w] = __builtin_bit_cast(ushort8, x);
+                }
+            } else {
+#pragma unroll
+                for (int w = 0; w < 3; ++w)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const bool ok = (w == 0 ? m0 + row < M : n0 + row < N) && k + i < kend;
+                        t[w][i] = q[4 * w + j][i] & (ok ? (unsigned short)0xffff : (unsigned short)0);
+                    }
+            }
+            *reinterpret_cast<ushort8*>(&As[row][sc]) = t[0];
+            *reinterpret_cast<ushort8*>(&Bh[row][sc]) = t[1];
+            *reinterpret_cast<ushort8*>(&Bl[row][sc]) = t[2];
+        }
     };
 
     floatx16 acc[2][2];
@@ -362,24 +363,23 @@ __global__ __launch_bounds__(256) void k_gemm_bf16x2(const unsigned short* __res
     // (steps past the end of the K range load clamped addresses and are never stored)
 #pragma unroll
     for (int u = 0; u < PF; ++u) load(kbeg + u * BK, r[u]);
-    if (nk > 0) store(0, kbeg, r[0]);
-    __syncthreads();
     for (int kt0 = 0; kt0 < nk; kt0 += PF) {
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             const int kt = kt0 + u;
             if (kt < nk) {                                     // uniform
-                const int buf = kt & 1;
-                // the registers of step kt went to LDS one step ago: refill them with step kt + PF
-                load(kbeg + (kt + PF) * BK, r[u]);
+                if (kt > 0) lds_barrier();                     // every wave has finished reading the previous tiles
+                store(kbeg + kt * BK, r[u]);
+                lds_barrier();
+                load(kbeg + (kt + PF) * BK, r[u]);             // refill the registers just consumed
 #pragma unroll
                 for (int ks = 0; ks < BK; ks += 16) {
                     bf16x8 a[2], bh[2], bl[2];
 #pragma unroll
                     for (int i = 0; i < 2; ++i) {
-                        a[i] = *reinterpret_cast<const bf16x8*>(&As[buf][wm + 32 * i + l32][ks + 8 * half]);
-                        bh[i] = *reinterpret_cast<const bf16x8*>(&Bh[buf][wn + 32 * i + l32][ks + 8 * half]);
-                        bl[i] = *reinterpret_cast<const bf16x8*>(&Bl[buf][wn + 32 * i + l32][ks + 8 * half]);
+                        a[i] = *reinterpret_cast<const bf16x8*>(&As[wm + 32 * i + l32][ks + 8 * half]);
+                        bh[i] = *reinterpret_cast<const bf16x8*>(&Bh[wn + 32 * i + l32][ks + 8 * half]);
+                        bl[i] = *reinterpret_cast<const bf16x8*>(&Bl[wn + 32 * i + l32][ks + 8 * half]);
                     }
                     // the small parts first; four independent accumulators between the two uses of each one
 #pragma unroll
@@ -393,8 +393,6 @@ __global__ __launch_bounds__(256) void k_gemm_bf16x2(const unsigned short* __res
                         for (int j = 0; j < 2; ++j)
                             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bh[j], acc[i][j], 0, 0, 0);
                 }
-                if (kt + 1 < nk) store(buf ^ 1, kbeg + (kt + 1) * BK, r[(u + 1) % PF]);
-                lds_barrier();
             }
         }
     }
@@ -487,7 +485,7 @@ void launch_gemm_bf16(fosi_ctx* ctx, const unsigned short* A, int lda, const flo
                        sl, ldt);
     const int tiles = ((N + BN - 1) / BN) * ((M + BM - 1) / BM) * plan.nsplit;
     const dim3 grid((tiles + 7) / 8 * 8);
-    const bool vec = (lda % 8 == 0) && (K % 16 == 0) && (plan.klen % 16 == 0) &&
+    const bool vec = (lda % 8 == 0) && (K % 8 == 0) && (plan.klen % 8 == 0) &&
                      ((reinterpret_cast<uintptr_t>(A) & 15) == 0) && ((reinterpret_cast<uintptr_t>(sh) & 15) == 0) &&
                      ((reinterpret_cast<uintptr_t>(sl) & 15) == 0);
     if (vec)
