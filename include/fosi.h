@@ -55,6 +55,10 @@ typedef struct fosi_hvp fosi_hvp;   /* a curvature operator v -> H v bound to a 
 /* Creates a context on GPU `device`.  `hip_stream` is a hipStream_t passed as
  * a pointer (NULL = the default stream); the caller keeps the stream alive. */
 fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream);
+/* Bytes of device memory the context holds for itself (partial sums, coefficient vectors, the tridiagonal,
+ * flags): a fixed amount, independent of the problem sizes; every other buffer is the caller's.  Operators
+ * created by hvp_softmax_ggn*_create own their work matrices in addition. */
+size_t fosi_workspace_bytes(const fosi_ctx* ctx);
 fosi_status fosi_ctx_destroy(fosi_ctx* ctx);
 /* Blocks until all work enqueued through this context has finished. */
 fosi_status fosi_ctx_synchronize(fosi_ctx* ctx);

@@ -26,7 +26,7 @@ PROF = {"hvp_project": 0, "hvp_expand": 1, "reorth_dot": 2, "reorth_sub": 3, "no
 EXPORTS = [
     "fosi_ctx_create", "fosi_ctx_destroy", "fosi_ctx_synchronize", "fosi_last_error", "fosi_status_string",
     "hvp_planted_create", "hvp_diag_create", "hvp_softmax_ggn_create", "hvp_softmax_ggn_bf16_create", "hvp_callback_create", "hvp_apply",
-    "hvp_destroy", "fosi_lanczos", "fosi_graph_stats", "fosi_lanczos_row_sharded", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_step_adamw", "fosi_admm_begin",
+    "hvp_destroy", "fosi_workspace_bytes", "fosi_lanczos", "fosi_graph_stats", "fosi_lanczos_row_sharded", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_step_adamw", "fosi_admm_begin",
     "fosi_admm_end", "fosi_profile_enable", "fosi_profile_reset", "fosi_profile_read",
 ]
 
@@ -85,6 +85,8 @@ def load_library() -> C.CDLL:
     lib.fosi_lanczos.argtypes = [vp, vp, i64, C.c_int, vp, i64, dp, dp, C.POINTER(i32), C.POINTER(_LanczosOpts)]
     lib.fosi_lanczos_row_sharded.argtypes = [vp, vp, i64, C.c_int, C.c_int, vp, i64, dp, dp, C.POINTER(i32),
                                              C.POINTER(_LanczosOpts)]
+    lib.fosi_workspace_bytes.argtypes = [vp]
+    lib.fosi_workspace_bytes.restype = C.c_size_t
     lib.fosi_graph_stats.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.fosi_lanczos_steps.argtypes = [i64, C.c_int, C.c_int]
     lib.fosi_tridiag_eigh.argtypes = [C.c_int, dp, dp, dp, dp]
@@ -97,7 +99,7 @@ def load_library() -> C.CDLL:
     lib.fosi_profile_reset.argtypes = [vp]
     lib.fosi_profile_read.argtypes = [vp, C.c_int, C.POINTER(i64), dp, dp]
     for name in EXPORTS:
-        if name not in ("fosi_last_error", "fosi_status_string"):
+        if name not in ("fosi_last_error", "fosi_status_string", "fosi_workspace_bytes"):
             getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -241,6 +243,9 @@ class Context:
         n, ms, by = C.c_int64(), C.c_double(), C.c_double()
         self.check(self.lib.fosi_profile_read(self.handle, cls, C.byref(n), C.byref(ms), C.byref(by)))
         return n.value, ms.value, by.value
+
+    def workspace_bytes(self) -> int:
+        return int(self.lib.fosi_workspace_bytes(self.handle))
 
     def graph_stats(self) -> Tuple[int, int]:
         """(captures, replays) of HIP graphs by fosi_lanczos on this context."""

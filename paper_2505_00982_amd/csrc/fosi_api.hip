@@ -132,6 +132,7 @@ fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
     const size_t o_S = take(sizeof(float) * kMaxCols * kMaxCols);
     const size_t o_fl = take(sizeof(int) * 8);
     const size_t o_x = take(sizeof(double) * kMaxShards * cols1), o_x3 = take(sizeof(double) * kMaxShards * 3);
+    ctx->scratch_bytes = off;
     if (hipMalloc(&ctx->scratch_base, off) != hipSuccess) {
         delete ctx;
         return FOSI_ERR_NOMEM;
@@ -178,6 +179,8 @@ fosi_status fosi_ctx_destroy(fosi_ctx* ctx) {
     delete ctx;
     return FOSI_OK;
 }
+
+size_t fosi_workspace_bytes(const fosi_ctx* ctx) { return ctx == nullptr ? 0 : ctx->scratch_bytes; }
 
 fosi_status fosi_ctx_synchronize(fosi_ctx* ctx) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;

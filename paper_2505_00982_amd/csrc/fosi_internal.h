@@ -60,6 +60,7 @@ struct fosi_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
     void* scratch_base = nullptr;
+    size_t scratch_bytes = 0;
     fosi::Scratch s{};
     fosi::Tunables tun{};
     std::string last_error;

@@ -23,7 +23,7 @@ def fo():
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "fosi.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"\b(?:fosi_status|const char\*|int32_t)\s+((?:fosi|hvp)_[a-z0-9_]+)\s*\(", text)
+    names = re.findall(r"\b(?:fosi_status|const char\*|int32_t|size_t)\s+((?:fosi|hvp)_[a-z0-9_]+)\s*\(", text)
     return sorted(set(names))
 
 
