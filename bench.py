@@ -56,6 +56,16 @@ def algorithmic_vectors(m_eff: int, r: int, r_v: int, reorth: str, with_pi: bool
                 total=hvp + reorth + norm + ritz + step)
 
 
+def device_name(torch) -> str:
+    """Marketing name if the driver's id table has one, else the architecture string (e.g. gfx950)."""
+    name = torch.cuda.get_device_name(0)
+    if not name:
+        props = torch.cuda.get_device_properties(0)
+        name = f"{getattr(props, 'gcnArchName', 'unknown arch')}, {props.multi_processor_count} CUs, " \
+               f"{props.total_memory / 2**30:.0f} GiB"
+    return name
+
+
 def cpu_baseline(cfg_id: int, n_sample: int) -> dict:
     """The CPU oracle, as it stands, on a reduced-n copy of the same workload."""
     import numpy as np
@@ -366,7 +376,7 @@ def main() -> int:
                    "accumulation": "f64 products and sums, one rounding per stored fp32 vector",
                    "m_eff": state["m_eff"], "algorithmic_GB_per_step": round(step_bytes / 1e9, 1),
                    "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
-                   "device": torch.cuda.get_device_name(0), "hip": getattr(torch.version, "hip", None)},
+                   "device": device_name(torch), "hip": getattr(torch.version, "hip", None)},
         "roofline": roofline,
         "phases": phases,
     }

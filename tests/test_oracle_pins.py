@@ -14,18 +14,32 @@ def planted_op(w):
     return lambda v: oracle.hvp_planted(w.U, w.lam, float(w.shift), v)
 
 
-@pytest.fixture(scope="module")
-def cfg1():
+def make_cfg1():
     w = wl.planted_workload(1)
     res = oracle.lanczos(planted_op(w), w.v1, w.m)
     return w, res
 
 
-@pytest.fixture(scope="module")
-def cfg2_small():
+def make_cfg2_small():
     w = wl.planted_workload(2, n=1 << 15)
     res = oracle.lanczos(planted_op(w), w.v1, w.m)
     return w, res
+
+
+def make_ggn_small():
+    return wl.ggn_workload(B=16, d=8, C=5)
+
+
+# (plain builders above so that tests/test_pins_catch_planted_mistakes.py can rebuild the inputs
+# with a deliberately broken oracle)
+@pytest.fixture(scope="module")
+def cfg1():
+    return make_cfg1()
+
+
+@pytest.fixture(scope="module")
+def cfg2_small():
+    return make_cfg2_small()
 
 
 # ---------------------------------------------------------------- operators
@@ -276,6 +290,51 @@ def test_step_with_dual_closed_form_and_g1_readings():
     assert not np.allclose(b1, b2, atol=1e-6)         # ... but not the same momentum buffer
 
 
+def test_step_abs_mode_with_dual_and_negative_curvature():
+    # negative and tiny Ritz values with a penalty: signed divides by a + sigma, abs by |a| + sigma (not |a + sigma|)
+    n, r = 70, 4
+    V = _orthonormal(n, r, 21)
+    rng = np.random.default_rng(22)
+    a = np.array([3.0, -2.0, 0.5, -0.01])
+    w, g, b0, pi = (rng.standard_normal(n) for _ in range(4))
+    sig, al, lr, mu = 0.05, 0.3, 0.02, 0.7
+    gt = g + pi
+    Pc = np.eye(n) - V @ V.T
+    tail = -lr * Pc @ (mu * b0 + Pc @ gt)
+    w_signed, _ = oracle.fosi_step(w, g, V, a, b0, al, lr, mu, sigma=sig, pi=pi)
+    assert np.allclose(w_signed, w - al * V @ ((V.T @ gt) / np.array([3.05, -1.95, 0.55, 0.04])) + tail, atol=1e-12)
+    w_abs, _ = oracle.fosi_step(w, g, V, a, b0, al, lr, mu, sigma=sig, pi=pi, curv_mode="abs")
+    assert np.allclose(w_abs, w - al * V @ ((V.T @ gt) / np.array([3.05, 2.05, 0.55, 0.06])) + tail, atol=1e-12)
+
+
+def test_adamw_step_dense_closed_form():
+    """Three consecutive updates with a non-empty subspace, a dual variable and both curvature modes: the base
+    optimiser's vector is taken from torch.optim.AdamW fed with the complement part of g + pi, the projections are
+    dense matrices."""
+    import torch
+    n, r = 80, 5
+    V = _orthonormal(n, r, 23)
+    rng = np.random.default_rng(24)
+    a = np.array([4.0, 1.5, -0.8, 0.3, -0.02])
+    lr, b1, b2, eps, wd, al, sig = 2e-3, 0.9, 0.99, 1e-8, 0.1, 0.25, 0.05
+    Pc = np.eye(n) - V @ V.T
+    for mode, denom in (("signed", a + sig), ("abs", np.abs(a) + sig)):
+        w = rng.standard_normal(n)
+        m, v = np.zeros(n), np.zeros(n)
+        p = torch.nn.Parameter(torch.tensor(w, dtype=torch.float64))
+        opt = torch.optim.AdamW([p], lr=lr, betas=(b1, b2), eps=eps, weight_decay=wd)
+        for t in range(1, 4):
+            g, pi = rng.standard_normal(n), 0.3 * rng.standard_normal(n)
+            with torch.no_grad():
+                p.copy_(torch.tensor(w))                      # the library optimiser starts from the current point
+            p.grad = torch.tensor(Pc @ (g + pi))
+            opt.step()
+            o = p.detach().numpy() - w                        # its whole descent vector, decay included
+            expect = w - al * V @ ((V.T @ (g + pi)) / denom) + Pc @ o
+            w, m, v = oracle.fosi_step_adamw(w, g, V, a, m, v, t, al, lr, b1, b2, eps, wd, sigma=sig, pi=pi, curv_mode=mode)
+            assert np.allclose(w, expect, rtol=0, atol=1e-12)
+
+
 def test_adamw_step_without_subspace_is_library_adamw():
     import torch
     n = 64
@@ -337,7 +396,7 @@ def test_admm_outer_rules():
 # ---------------------------------------------------------------- softmax GGN
 @pytest.fixture(scope="module")
 def ggn_small():
-    return wl.ggn_workload(B=16, d=8, C=5)
+    return make_ggn_small()
 
 
 def test_ggn_equals_autograd_hessian_product(ggn_small):
