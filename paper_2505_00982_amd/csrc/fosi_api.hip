@@ -335,8 +335,7 @@ static fosi_status apply_operator(fosi_hvp* op, const float* v_dev, float* hv_de
         const float* base = vprev != nullptr ? vprev : v_dev;
         const int64_t ld = vprev != nullptr ? (int64_t)(v_dev - vprev) : 0;
         launch_dot_columns(ctx, base, ld, nc, hv_dev, nullptr, nullptr, nullptr, n, ctx->s.coef_a, nullptr, 0, 1.0,
-                           nullptr, stop, FOSI_PROF_REORTH_DOT, (nc + 1) * vec);
-        launch_local_from_coef(ctx, ctx->s.coef_a, nc, stop);
+                           nullptr, stop, FOSI_PROF_REORTH_DOT, (nc + 1) * vec, kTailLocal);
     }
     return launch_status(ctx, "hvp_apply");
 }
@@ -397,18 +396,21 @@ static fosi_status enqueue_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m
             // untouched and the full pass works on h - alpha~ q_i - beta~ q_{i-1}, formed on the fly in fp64
             const float* qprev = i > 0 ? q - ldq : nullptr;
             if (fosi_status s = apply_operator(op, q, h, qprev, true)) return s;
-            launch_dot_columns(ctx, Q_dev, ldq, ncols, h, q, qprev, ctx->s.scal + 4, n, ctx->s.coef_b, nullptr, 0, 1.0,
-                               ctx->s.loc, flags, FOSI_PROF_REORTH_DOT, (ncols + 1 + (qprev != nullptr ? 2 : 1)) * vec);
-            // coef_b now holds the total coefficient per column (local + full); one subtraction removes both
+            // coef_b receives the total coefficient per column (local + full); one subtraction removes both
             if (ctx->tun.early_beta) {
-                // beta from the coefficients, then the subtraction writes the normalised vector itself
-                launch_lanczos_finalize_early(ctx, i, ctx->s.coef_b, ncols, tol);
+                // beta from the coefficients (by the last workgroup of the product's second stage), then the
+                // subtraction writes the normalised vector itself
+                launch_dot_columns(ctx, Q_dev, ldq, ncols, h, q, qprev, ctx->s.scal + 4, n, ctx->s.coef_b, nullptr, 0, 1.0,
+                                   ctx->s.loc, flags, FOSI_PROF_REORTH_DOT, (ncols + 1 + (qprev != nullptr ? 2 : 1)) * vec,
+                                   kTailLanczosStep, i, tol);
                 launch_combine_columns(ctx, Q_dev, ldq, ncols, ctx->s.coef_b, h, 1.0, nullptr, 0.0, nullptr, 0.0, nullptr,
                                        false, -1.0, h, n, false, flags, FOSI_PROF_REORTH_SUB, (ncols + 2) * vec,
                                        ctx->s.scal);
                 if (fosi_status s = launch_status(ctx, "lanczos step")) return s;
                 continue;
             }
+            launch_dot_columns(ctx, Q_dev, ldq, ncols, h, q, qprev, ctx->s.scal + 4, n, ctx->s.coef_b, nullptr, 0, 1.0,
+                               ctx->s.loc, flags, FOSI_PROF_REORTH_DOT, (ncols + 1 + (qprev != nullptr ? 2 : 1)) * vec);
             norm_slots = launch_combine_columns(ctx, Q_dev, ldq, ncols, ctx->s.coef_b, h, 1.0, nullptr, 0.0, nullptr,
                                                 0.0, nullptr, false, -1.0, h, n, true, flags, FOSI_PROF_REORTH_SUB,
                                                 (ncols + 2) * vec);

@@ -49,7 +49,8 @@ struct Scratch {
     double* hnorm;         // kMaxCols
     double* newton;        // kMaxCols: alpha / (a_j + sigma)
     float* S;              // kMaxCols x kMaxCols Ritz coefficient block
-    int* flags;            // [0] stop flag (1 = breakdown, 2 = non-finite), [1] completed steps
+    int* flags;            // [0] stop flag (1 = breakdown, 2 = non-finite), [1] completed steps, [2] arrival counter
+                           // of the second reduction stage (zero between launches)
     double* xchg;          // kMaxShards x (kMaxCols + 1): per-shard coefficient partials (row-sharded emulation)
     double* xchg3;         // kMaxShards x 3: per-shard {||.||^2, local dots}
 };
@@ -134,10 +135,17 @@ struct ProfScope {
 // coef[ncols] = sum_rows (x + x2)^2.   x2 and scale may be null.  stop may be null.
 // The vector is x, or x + xs[0] x2 (+ xs[1] x3) with xs in device memory (xs == null: scales 1).
 // add_last2 (device, may be null): values added to the last and the last-but-one coefficient.
+// tail_kind: what the second stage's last workgroup does once all coefficients are in memory, in the same launch:
+//   kTailNone;  kTailLocal: ctx->s.loc = {coef[ncols-1], ncols > 1 ? coef[0] : 0, coef[ncols]} and their negatives
+//   in ctx->s.scal[4..5] (transposed product against [q_{i-1}, q_i] or [q_i]);  kTailLanczosStep: end of step
+//   tail_step of a 'local_full' run (alpha, beta, flags and 1/beta from the coefficients and ctx->s.loc, before
+//   the subtraction sweep; same arithmetic as launch_lanczos_finalize_early).
+constexpr int kTailNone = 0, kTailLocal = 1, kTailLanczosStep = 2;
 void launch_dot_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const float* x,
                         const float* x2, const float* x3, const double* xs, int64_t n, double* coef,
                         const float* scale, int nscale, double gscale, const double* add_last2,
-                        const int* stop, int prof_cls, double prof_bytes);
+                        const int* stop, int prof_cls, double prof_bytes, int tail_kind = kTailNone,
+                        int tail_step = 0, double tail_tol = 0.0);
 
 // out = a0*y + a1*x1 + a2*x2 + sa * A[:, :ncols] d   (null pointers drop their term; out may alias y).
 // With want_norm the per-block partial sums of out^2 are left in ctx->s.norm_partials; their count is

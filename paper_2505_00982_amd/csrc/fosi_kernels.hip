@@ -60,8 +60,9 @@ __device__ __forceinline__ double block_sum(double v, double* lds4) {
 // the vector x is fetched from HBM once and re-read from the CU's L1; the remaining 4/S waves of
 // the block take other rows.  The sweep is compiled for 4, 8, ..., 32 columns; a slot whose width
 // is not a multiple of 4 re-reads its last column for the (at most 3) padding positions, which hit
-// in cache and are discarded.  partials[rowslot * pstride + column] receives the wave's sums,
-// column index `ncols` the partial of sum(x^2) (from the waves of slot 0).
+// in cache and are discarded.  partials[column * pslots + rowslot] receives the wave's sums (the row
+// slots of a column are contiguous, so that the second stage reads them with coalesced loads), column
+// index `ncols` the partial of sum(x^2) (from the waves of slot 0).
 
 // One sweep of a slot compiled for NCOL columns (nc <= NCOL of them real).  `Aj0` points at row 0 of
 // the slot's first column.  Everything but `lane` is uniform across the wave, so the column bases
@@ -122,7 +123,7 @@ template <int JB, int NX>
 __global__ __launch_bounds__(kThreads) void k_dot_columns(
     const float* __restrict__ A, int64_t lda, int ncols, const float* __restrict__ x,
     const float* __restrict__ x2, const float* __restrict__ x3, const double* __restrict__ xs, int64_t n,
-    double* __restrict__ partials, int pstride, int S, const int* __restrict__ stop) {
+    double* __restrict__ partials, int pslots, int S, const int* __restrict__ stop) {
     static_assert(JB == 32, "the sweep variants below cover slots of up to 32 columns");
     if (stop != nullptr && *stop != 0) return;
     const int lane = threadIdx.x & 63;
@@ -193,32 +194,65 @@ __global__ __launch_bounds__(kThreads) void k_dot_columns(
             if (j < nc) acc[j] = fma((double)Aj0[(int64_t)j * lda + tail_row], dx, acc[j]);
     }
 
-    double* prow = partials + ((int64_t)blockIdx.x * rows_per_block + rowlane) * pstride;
+    double* pslot = partials + ((int64_t)blockIdx.x * rows_per_block + rowlane);
 #pragma unroll
     for (int j = 0; j < JB; ++j) {
         if (j < nc) {                                   // uniform test: whole waves skip the padding columns
             const double v = wave_sum(acc[j]);
-            if (lane == 0) prow[j0 + j] = v;
+            if (lane == 0) pslot[(int64_t)(j0 + j) * pslots] = v;
         }
     }
     if (do_xx) {
         const double v = wave_sum(xx);
-        if (lane == 0) prow[ncols] = v;
+        if (lane == 0) pslot[(int64_t)ncols * pslots] = v;
     }
 }
 
-// Second stage: one wavefront per output column sums the row-slot partials in
-// a fixed order and applies the per-column scale.
+// What the last workgroup of the second stage does once every column sum is in memory (saves a launch
+// and the ~6 us between two dependent launches).
+struct ReduceTail {
+    int kind;          // 0 none; 1 scalars of the local Gram-Schmidt pass; 2 end of a Lanczos step
+    int step;          // kind 2: Lanczos step index
+    double tol;        // kind 2: breakdown tolerance
+    double* loc;       // kind 1: written {alpha~, beta~, ||h||^2}; kind 2: read
+    double* neg;       // kind 1: written {-alpha~, -beta~}
+    double* alpha;     // kind 2 outputs
+    double* beta;
+    double* hnorm;
+    double* scal;      // kind 2: scal[0] = 1 / beta
+    int* flags;        // [0] stop flag, [1] completed steps, [2] arrival counter of this kernel
+};
+
+// Second stage: one wavefront per output column sums the row-slot partials in a fixed order and applies
+// the per-column scale.  Partial (slot, j) lives at partials[slot * slot_stride + j * col_stride].
+// tail.kind != 0: every workgroup announces its result (release fence + counter); the one that arrives
+// last reads all of `out` and finishes the step:
+//   kind 1 (transposed product against [q_{i-1}, q_i] or [q_i], ncols = 2 or 1):
+//          loc = {out[ncols-1], ncols > 1 ? out[0] : 0, out[ncols]}, neg = -loc[0..1];
+//   kind 2 (end of a Lanczos step of the 'local_full' scheme): out holds the total coefficients (local +
+//          full) of `ncols` columns and, in out[ncols], the squared norm of the vector x the full pass
+//          worked on; loc = {alpha~, beta~, ||H q||^2} are the local parts of the last two coefficients.
+//          x - Q c_full has squared norm ||x||^2 - ||c_full||^2 up to (Q^T Q - I) c_full . c_full, far below
+//          fp64 rounding here, so beta is known BEFORE the subtraction sweep, which can then write the
+//          normalised vector directly (no separate scaling sweep).
 __global__ __launch_bounds__(64) void k_reduce_columns(
-    const double* __restrict__ partials, int nslots, int pstride, double* __restrict__ out,
+    const double* __restrict__ partials, int nslots, int64_t slot_stride, int64_t col_stride, double* out,
     const float* __restrict__ scale, int nscale, double gscale, int ncols, const double* __restrict__ add_last2,
-    const int* __restrict__ stop) {
+    const int* __restrict__ stop, ReduceTail tail) {
     if (stop != nullptr && *stop != 0) return;
-    const int j = blockIdx.x;
-    double s = 0.0;
-    for (int slot = threadIdx.x; slot < nslots; slot += 64) s += partials[(int64_t)slot * pstride + j];
-    s = wave_sum(s);
-    if (threadIdx.x == 0) {
+    const int j = blockIdx.x, lane = threadIdx.x;
+    const double* pj = partials + (int64_t)j * col_stride;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int slot = lane;
+    for (; slot + 192 < nslots; slot += 256) {           // four independent loads in flight per lane
+        const double v0 = pj[(int64_t)slot * slot_stride], v1 = pj[(int64_t)(slot + 64) * slot_stride];
+        const double v2 = pj[(int64_t)(slot + 128) * slot_stride], v3 = pj[(int64_t)(slot + 192) * slot_stride];
+        s0 += v0; s1 += v1; s2 += v2; s3 += v3;
+    }
+    for (; slot < nslots; slot += 64) s0 += pj[(int64_t)slot * slot_stride];
+    double s = wave_sum((s0 + s1) + (s2 + s3));
+    int last = 0;
+    if (lane == 0) {
         if (j < ncols) {
             s *= gscale;
             if (scale != nullptr && j < nscale) s *= (double)scale[j];
@@ -228,6 +262,46 @@ __global__ __launch_bounds__(64) void k_reduce_columns(
             }
         }
         out[j] = s;   // j == ncols: the plain sum of squares
+        if (tail.kind != 0) {
+            __threadfence();                                     // out[j] is visible before the arrival is
+            last = atomicAdd(&tail.flags[2], 1) == (int)gridDim.x - 1;
+        }
+    }
+    if (tail.kind == 0) return;
+    last = __shfl(last, 0, 64);
+    if (!last) return;
+    __threadfence();                                             // the other workgroups' results are visible now
+    if (lane == 0) tail.flags[2] = 0;                            // ready for the next launch
+    if (tail.kind == 1) {
+        if (lane == 0) {
+            const double a = out[ncols - 1], b = ncols > 1 ? out[0] : 0.0;
+            tail.loc[0] = a; tail.loc[1] = b; tail.loc[2] = out[ncols];
+            tail.neg[0] = -a; tail.neg[1] = -b;
+        }
+        return;
+    }
+    if (tail.flags[0] != 0) return;
+    double q = 0.0;
+    for (int c = lane; c < ncols; c += 64) {
+        double cf = out[c];
+        if (c == ncols - 1) cf -= tail.loc[0];
+        if (c == ncols - 2) cf -= tail.loc[1];
+        q = fma(cf, cf, q);
+    }
+    q = wave_sum(q);
+    if (lane == 0) {
+        const double a = out[ncols - 1];
+        const double b2 = out[ncols] - q;
+        const double b = b2 > 0.0 ? sqrt(b2) : (b2 == b2 ? 0.0 : b2);     // NaN stays NaN
+        const double hn = sqrt(tail.loc[2]);
+        tail.alpha[tail.step] = a;
+        tail.beta[tail.step] = b;
+        tail.hnorm[tail.step] = hn;
+        tail.flags[1] = tail.step + 1;
+        const bool finite = (a - a == 0.0) && (b - b == 0.0) && (hn - hn == 0.0);
+        if (!finite) tail.flags[0] = 2;
+        else if (!(b > tail.tol * hn)) tail.flags[0] = 1;
+        tail.scal[0] = 1.0 / b;
     }
 }
 
@@ -280,7 +354,7 @@ __device__ __forceinline__ void accumulate_columns(const float* __restrict__ A, 
 // sum of out^2 (of the stored, rounded values) goes to norm_partials[blockIdx.x].
 // oscale (device, may be null): factor applied to every element before the rounding, e.g. 1/beta.
 // With LDOT (used by the planted operator inside a Lanczos run) the block also emits the partial sums
-// of out.x1 and out.x3 (x3 may be null): norm_partials[3*block + {0,1,2}] = {out^2, out.x1, out.x3}.
+// of out.x1 and out.x3 (x3 may be null): norm_partials[{0,1,2} * gridDim.x + block] = {out^2, out.x1, out.x3}.
 template <bool HAS_Y, bool HAS_X1, bool HAS_X2, bool NORM, bool LDOT, int RPT, int CU>
 __global__ __launch_bounds__(kThreads) void k_combine_columns(
     const float* __restrict__ A, int64_t lda, int ncols, const double* __restrict__ d, const float* y,
@@ -370,9 +444,9 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
     if (LDOT) {
         const double b0 = block_sum(nrm, red), b1 = block_sum(dot1, red), b3 = block_sum(dot3, red);
         if (tid == 0) {
-            norm_partials[3 * (int64_t)blockIdx.x] = b0;
-            norm_partials[3 * (int64_t)blockIdx.x + 1] = b1;
-            norm_partials[3 * (int64_t)blockIdx.x + 2] = b3;
+            norm_partials[blockIdx.x] = b0;
+            norm_partials[(int64_t)gridDim.x + blockIdx.x] = b1;
+            norm_partials[2 * (int64_t)gridDim.x + blockIdx.x] = b3;
         }
     } else if (NORM) {
         const double b = block_sum(nrm, red);
@@ -393,7 +467,7 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
 // MAXC) columns of the tile in registers, the partial sums of V c are exchanged through LDS (added in a
 // fixed order, so all waves hold identical values), every wave evaluates the optimiser for the tile and
 // wave 0 stores its state, then each wave accumulates the e_j of its own columns from the registers.
-// partials[block * pstride + j] receives the block's part of e_j.
+// partials[j * gridDim.x + block] receives the block's part of e_j.
 struct OptScalars {
     double mu;                                   // heavy ball
     double b1, b2, inv_bc1, inv_bc2, eps, lr, wd;   // AdamW (bc1, bc2: bias corrections of this step)
@@ -423,7 +497,7 @@ template <int OPT, int NCOL>
 __global__ __launch_bounds__(512) void k_complement_reproject(
     const float* __restrict__ V, int64_t ldv, int ncols, int cw, const double* __restrict__ c,
     const float* __restrict__ g, const float* __restrict__ pi, const float* __restrict__ w, float* m, float* v,
-    float* __restrict__ o_out, int64_t n, OptScalars p, double* __restrict__ partials, int pstride) {
+    float* __restrict__ o_out, int64_t n, OptScalars p, double* __restrict__ partials) {
     extern __shared__ double exch[];             // [2][S][4][64]: partial sums of V c, double buffered
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -554,15 +628,15 @@ __global__ __launch_bounds__(512) void k_complement_reproject(
         }
     }
 
-    double* prow = partials + (int64_t)blockIdx.x * pstride;
+    double* pblock = partials + blockIdx.x;
 #pragma unroll
     for (int j = 0; j < NCOL; ++j) {
         if (j < nc) {                            // uniform test
             const double e = wave_sum(acc[j]);
-            if (lane == 0) prow[j0 + j] = e;
+            if (lane == 0) pblock[(int64_t)(j0 + j) * gridDim.x] = e;
         }
     }
-    if (wave == 0 && lane == 0) prow[ncols] = 0.0;   // the reduction kernel also sums this (unused) slot
+    if (wave == 0 && lane == 0) pblock[(int64_t)ncols * gridDim.x] = 0.0;   // the reduction kernel also sums this (unused) slot
 }
 
 // d_j = newton_j c_j + e_j  (AdamW variant of the last sweep's coefficients: w += o - V d)
@@ -638,37 +712,44 @@ __global__ __launch_bounds__(kThreads) void k_lanczos_finalize_early(
     }
 }
 
+// Fixed-order sum over `nslots` partial sums of one quantity (element i at p[i * stride]) by the 256 threads of
+// a block: four independent loads per thread and trip, then the block sum.  Result valid in thread 0.
+__device__ __forceinline__ double block_sum_strided(const double* __restrict__ p, int nslots, int64_t stride, double* red) {
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int i = threadIdx.x;
+    for (; i + 3 * kThreads < nslots; i += 4 * kThreads) {
+        const double v0 = p[(int64_t)i * stride], v1 = p[(int64_t)(i + kThreads) * stride];
+        const double v2 = p[(int64_t)(i + 2 * kThreads) * stride], v3 = p[(int64_t)(i + 3 * kThreads) * stride];
+        s0 += v0; s1 += v1; s2 += v2; s3 += v3;
+    }
+    for (; i < nslots; i += kThreads) s0 += p[(int64_t)i * stride];
+    return block_sum((s0 + s1) + (s2 + s3), red);
+}
+
 // Sums the {out^2, out.x1, out.x3} partials of the operator's expand sweep: loc = {alpha~, beta~, ||h||^2},
 // neg = {-alpha~, -beta~} (the scales with which q_i and q_{i-1} enter the vector of the full pass).
-__global__ __launch_bounds__(kThreads) void k_reduce_local(const double* __restrict__ parts, int nslots,
-                                                           double* __restrict__ loc, double* __restrict__ neg,
-                                                           const int* __restrict__ stop) {
+// Partial w of slot i lives at parts[w * wstride + i * sstride].
+__global__ __launch_bounds__(kThreads) void k_reduce_local(const double* __restrict__ parts, int nslots, int64_t wstride,
+                                                           int64_t sstride, double* __restrict__ loc,
+                                                           double* __restrict__ neg, const int* __restrict__ stop) {
     if (stop != nullptr && *stop != 0) return;
     __shared__ double red[4];
-    double s0 = 0.0, s1 = 0.0, s3 = 0.0;
-    for (int i = threadIdx.x; i < nslots; i += kThreads) {
-        s0 += parts[3 * (int64_t)i];
-        s1 += parts[3 * (int64_t)i + 1];
-        s3 += parts[3 * (int64_t)i + 2];
-    }
-    s0 = block_sum(s0, red);
-    s1 = block_sum(s1, red);
-    s3 = block_sum(s3, red);
+    const double s0 = block_sum_strided(parts, nslots, sstride, red);
+    const double s1 = block_sum_strided(parts + wstride, nslots, sstride, red);
+    const double s3 = block_sum_strided(parts + 2 * wstride, nslots, sstride, red);
     if (threadIdx.x == 0) {
         loc[0] = s1; loc[1] = s3; loc[2] = s0;
         neg[0] = -s1; neg[1] = -s3;
     }
 }
 
-// dst[w] = sum over slots of parts[slot * width + w], w < width <= 3 (fixed order).
+// dst[w] = sum over slots of parts[w * nslots + slot], w < width <= 3 (fixed order).
 __global__ __launch_bounds__(kThreads) void k_fold_partials(const double* __restrict__ parts, int nslots, int width,
                                                             double* __restrict__ dst, const int* __restrict__ stop) {
     if (stop != nullptr && *stop != 0) return;
     __shared__ double red[4];
     for (int w = 0; w < width; ++w) {
-        double s = 0.0;
-        for (int i = threadIdx.x; i < nslots; i += kThreads) s += parts[(int64_t)i * width + w];
-        s = block_sum(s, red);
+        const double s = block_sum_strided(parts + (int64_t)w * nslots, nslots, 1, red);
         if (threadIdx.x == 0) dst[w] = s;
     }
 }
@@ -889,9 +970,25 @@ int elementwise_grid(int64_t work_items) {
     return (int)g;
 }
 
+ReduceTail make_tail(fosi_ctx* ctx, int kind, int step, double tol) {
+    ReduceTail t{};
+    t.kind = kind;
+    t.step = step;
+    t.tol = tol;
+    t.loc = ctx->s.loc;
+    t.neg = ctx->s.scal + 4;
+    t.alpha = ctx->s.alpha;
+    t.beta = ctx->s.beta;
+    t.hnorm = ctx->s.hnorm;
+    t.scal = ctx->s.scal;
+    t.flags = ctx->s.flags;
+    return t;
+}
+
 void dot_columns_launch(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const float* x, const float* x2,
                         const float* x3, const double* xs, int64_t n, double* coef, const float* scale, int nscale,
-                        double gscale, const double* add_last2, const int* stop, int prof_cls, double prof_bytes) {
+                        double gscale, const double* add_last2, const int* stop, int prof_cls, double prof_bytes,
+                        int tail_kind, int tail_step, double tail_tol) {
     constexpr int JB = 32;
     const int nslots = ncols > 0 ? (ncols + JB - 1) / JB : 1;
     const int S = nslots >= 3 ? 4 : nslots;             // waves of a block that share the same rows
@@ -906,31 +1003,32 @@ void dot_columns_launch(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, c
     if (gx > cap) gx = cap;
     if (gx < 1) gx = 1;
     const int rowslots = (int)gx * rows_per_block;
-    const int pstride = ncols + 1;
     dim3 grid((unsigned)gx, (unsigned)gy);
     if (prof_cls >= 0) prof_begin(ctx, prof_cls, prof_bytes);
     if (x2 != nullptr && xs == nullptr) xs = ctx->s.scal + 2;   // plain sum of the vectors: scales 1, 1
     if (x3 != nullptr)
         hipLaunchKernelGGL((k_dot_columns<JB, 3>), grid, dim3(kThreads), 0, ctx->stream, A, lda, ncols, x, x2, x3, xs, n,
-                           ctx->s.partials, pstride, S, stop);
+                           ctx->s.partials, rowslots, S, stop);
     else if (x2 != nullptr)
         hipLaunchKernelGGL((k_dot_columns<JB, 2>), grid, dim3(kThreads), 0, ctx->stream, A, lda, ncols, x, x2, x3, xs, n,
-                           ctx->s.partials, pstride, S, stop);
+                           ctx->s.partials, rowslots, S, stop);
     else
         hipLaunchKernelGGL((k_dot_columns<JB, 1>), grid, dim3(kThreads), 0, ctx->stream, A, lda, ncols, x, x2, x3, xs, n,
-                           ctx->s.partials, pstride, S, stop);
+                           ctx->s.partials, rowslots, S, stop);
     if (prof_cls >= 0) prof_end(ctx);
-    hipLaunchKernelGGL(k_reduce_columns, dim3(ncols + 1), dim3(64), 0, ctx->stream, ctx->s.partials, rowslots, pstride,
-                       coef, scale, nscale, gscale, ncols, add_last2, stop);
+    hipLaunchKernelGGL(k_reduce_columns, dim3(ncols + 1), dim3(64), 0, ctx->stream, ctx->s.partials, rowslots, (int64_t)1,
+                       (int64_t)rowslots, coef, scale, nscale, gscale, ncols, add_last2, stop,
+                       make_tail(ctx, tail_kind, tail_step, tail_tol));
 }
 
 }  // namespace
 
 void launch_dot_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const float* x, const float* x2,
                         const float* x3, const double* xs, int64_t n, double* coef, const float* scale, int nscale,
-                        double gscale, const double* add_last2, const int* stop, int prof_cls, double prof_bytes) {
+                        double gscale, const double* add_last2, const int* stop, int prof_cls, double prof_bytes,
+                        int tail_kind, int tail_step, double tail_tol) {
     dot_columns_launch(ctx, A, lda, ncols, x, x2, x3, xs, n, coef, scale, nscale, gscale, add_last2, stop, prof_cls,
-                       prof_bytes);
+                       prof_bytes, tail_kind, tail_step, tail_tol);
 }
 
 namespace {
@@ -1001,8 +1099,13 @@ void launch_lanczos_finalize_early(fosi_ctx* ctx, int step, const double* coef, 
 }
 
 void launch_reduce_local(fosi_ctx* ctx, int nslots, const int* stop, const double* parts) {
-    hipLaunchKernelGGL(k_reduce_local, dim3(1), dim3(kThreads), 0, ctx->stream,
-                       parts != nullptr ? parts : ctx->s.norm_partials, nslots, ctx->s.loc, ctx->s.scal + 4, stop);
+    // the expand sweep leaves [3][nslots]; a caller's buffer holds one {out^2, out.x1, out.x3} triple per slot
+    if (parts == nullptr)
+        hipLaunchKernelGGL(k_reduce_local, dim3(1), dim3(kThreads), 0, ctx->stream, ctx->s.norm_partials, nslots,
+                           (int64_t)nslots, (int64_t)1, ctx->s.loc, ctx->s.scal + 4, stop);
+    else
+        hipLaunchKernelGGL(k_reduce_local, dim3(1), dim3(kThreads), 0, ctx->stream, parts, nslots, (int64_t)1, (int64_t)3,
+                           ctx->s.loc, ctx->s.scal + 4, stop);
 }
 
 void launch_fold_partials(fosi_ctx* ctx, int nslots, int width, double* dst, const int* stop) {
@@ -1012,8 +1115,9 @@ void launch_fold_partials(fosi_ctx* ctx, int nslots, int width, double* dst, con
 
 void launch_reduce_shards(fosi_ctx* ctx, int shards, int ncols, double* coef, const float* scale, int nscale,
                           double gscale, const double* add_last2, const int* stop) {
-    hipLaunchKernelGGL(k_reduce_columns, dim3(ncols + 1), dim3(64), 0, ctx->stream, ctx->s.xchg, shards, kMaxCols + 1,
-                       coef, scale, nscale, gscale, ncols, add_last2, stop);
+    hipLaunchKernelGGL(k_reduce_columns, dim3(ncols + 1), dim3(64), 0, ctx->stream, ctx->s.xchg, shards,
+                       (int64_t)(kMaxCols + 1), (int64_t)1, coef, scale, nscale, gscale, ncols, add_last2, stop,
+                       make_tail(ctx, 0, 0, 0.0));
 }
 
 void launch_local_from_coef(fosi_ctx* ctx, const double* coef, int nc, const int* stop) {
@@ -1092,16 +1196,15 @@ void launch_complement_reproject(fosi_ctx* ctx, int opt, const float* V, int64_t
     if (blocks > ntiles) blocks = ntiles;
     if (blocks < 1) blocks = 1;
     const size_t lds = S > 1 ? sizeof(double) * 2 * S * 4 * 64 : 0;
-    const int pstride = rv + 1;
     OptScalars p{mu, b1, b2, inv_bc1, inv_bc2, eps, lr, wd};
 #define FOSI_CR(NCOL)                                                                                              \
     do {                                                                                                           \
         if (opt == 0)                                                                                              \
             hipLaunchKernelGGL((k_complement_reproject<0, NCOL>), dim3((unsigned)blocks), dim3(64 * S), lds,        \
-                               ctx->stream, V, ldv, rv, cw, c, g, pi, w, m, v, o_out, n, p, ctx->s.partials, pstride); \
+                               ctx->stream, V, ldv, rv, cw, c, g, pi, w, m, v, o_out, n, p, ctx->s.partials);      \
         else                                                                                                       \
             hipLaunchKernelGGL((k_complement_reproject<1, NCOL>), dim3((unsigned)blocks), dim3(64 * S), lds,        \
-                               ctx->stream, V, ldv, rv, cw, c, g, pi, w, m, v, o_out, n, p, ctx->s.partials, pstride); \
+                               ctx->stream, V, ldv, rv, cw, c, g, pi, w, m, v, o_out, n, p, ctx->s.partials);      \
     } while (0)
     if (cw <= 4) FOSI_CR(4);
     else if (cw <= 8) FOSI_CR(8);
@@ -1111,8 +1214,9 @@ void launch_complement_reproject(fosi_ctx* ctx, int opt, const float* V, int64_t
     else FOSI_CR(32);
 #undef FOSI_CR
     if (rv > 0)
-        hipLaunchKernelGGL(k_reduce_columns, dim3(rv + 1), dim3(64), 0, ctx->stream, ctx->s.partials, (int)blocks, pstride,
-                           e_out, (const float*)nullptr, 0, 1.0, rv, (const double*)nullptr, (const int*)nullptr);
+        hipLaunchKernelGGL(k_reduce_columns, dim3(rv + 1), dim3(64), 0, ctx->stream, ctx->s.partials, (int)blocks, (int64_t)1,
+                           (int64_t)blocks, e_out, (const float*)nullptr, 0, 1.0, rv, (const double*)nullptr,
+                           (const int*)nullptr, make_tail(ctx, 0, 0, 0.0));
 }
 
 void launch_step_coefficients_plus(fosi_ctx* ctx, int rv) {

@@ -39,7 +39,9 @@ __device__ __forceinline__ void lds_barrier() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-constexpr int TM = 64, TN = 64, TK = 16;   // workgroup tile; each of the 4 waves owns a 32 x 32 quadrant
+constexpr int TM = 64, TN = 64;            // workgroup tile; each of the 4 waves owns a 32 x 32 quadrant
+constexpr int TK = 16;                     // K-step of the generic kernel
+constexpr int FK = 32;                     // K-step of the aligned-shape kernel (plans use multiples of FK)
 constexpr int LDT = TM + 4;
 
 // C[z] (M x N, row-major, ldc) = scale * A[:, kz] * B[kz, :]   over the K range of split z.
@@ -132,6 +134,123 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, i
         }
         if (kt + 1 < nk) store(buf ^ 1);
         lds_barrier();
+    }
+    float* Cz = Cout + (int64_t)tz * cstride;
+    const int col = n0 + wn + l32;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm + 8 * (v >> 2) + 4 * half + (v & 3);
+        if (row < M && col < N) Cz[(int64_t)row * ldc + col] = acc[v] * scale;
+    }
+}
+
+// The same product for aligned shapes (all row starts 16-byte aligned, N and the contiguous extent of A
+// multiples of 4): the generic kernel above keeps its loads behind bounds tests and looks one K-step of
+// 16 ahead, which leaves the matrix cores waiting for memory (measured on 512 x 1000 x 2048: 43 % busy).
+// Here every global load is unconditional from a clamped, always valid address, the bounds masks are
+// applied when the registers are written to LDS, the K-step is 32 (16 matrix instructions per wave
+// between two barriers) and the registers run FPF K-steps ahead of the LDS tiles, which are double
+// buffered so that one LDS-only barrier per K-step suffices.
+constexpr int FPF = 2;
+typedef unsigned int uint4v_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float4 mask4(const float4 v, const unsigned int keep) {
+    uint4v_t x = __builtin_bit_cast(uint4v_t, v);
+    x &= keep;
+    return __builtin_bit_cast(float4, x);
+}
+
+template <bool A_KM>
+__global__ __launch_bounds__(256) void k_gemm_f32_aligned(const float* __restrict__ A, int lda,
+                                                          const float* __restrict__ Bm, int ldb,
+                                                          float* __restrict__ Cout, int ldc, int M, int N, int K,
+                                                          int klen, int nsplit, int64_t cstride, float scale) {
+    __shared__ __attribute__((aligned(16))) float As[2][FK][LDT];   // [k][m]
+    __shared__ __attribute__((aligned(16))) float Bs[2][FK][LDT];   // [k][n]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32;
+    int tn, tm, tz;
+    if (!xcd_tile((N + TN - 1) / TN, (M + TM - 1) / TM, nsplit, tn, tm, tz)) return;
+    const int m0 = tm * TM, n0 = tn * TN;
+    const int kbeg = tz * klen;
+    const int kend = min(K, kbeg + klen);
+
+    // k-major tiles (B always, A when it is stored K x M): rows kr and kr + 16, four columns from c4
+    const int kr = tid >> 4, c4 = (tid & 15) * 4;
+    // A stored M x K: rows am and am + 32 of the tile, four k values from ak4
+    const int am = tid >> 3, ak4 = (tid & 7) * 4;
+    float4 ra[FPF][2], rb[FPF][2];
+
+    auto load = [&](int k0, float4* qa, float4* qb) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int k = k0 + kr + 16 * j;
+            const int kc = k < kend ? k : 0;
+            const int nb = n0 + c4;
+            qb[j] = *reinterpret_cast<const float4*>(Bm + (int64_t)kc * ldb + (nb < N ? nb : 0));
+            if (A_KM) {
+                const int ma = m0 + c4;
+                qa[j] = *reinterpret_cast<const float4*>(A + (int64_t)kc * lda + (ma < M ? ma : 0));
+            } else {
+                const int m = m0 + am + 32 * j, ka = k0 + ak4;
+                qa[j] = *reinterpret_cast<const float4*>(A + (int64_t)(m < M ? m : 0) * lda + (ka < kend ? ka : 0));
+            }
+        }
+    };
+    auto store = [&](int k0, int buf, const float4* qa, const float4* qb) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int k = k0 + kr + 16 * j;
+            const unsigned int keep_b = (k < kend && n0 + c4 < N) ? 0xffffffffu : 0u;
+            *reinterpret_cast<float4*>(&Bs[buf][kr + 16 * j][c4]) = mask4(qb[j], keep_b);
+            if (A_KM) {
+                const unsigned int keep_a = (k < kend && m0 + c4 < M) ? 0xffffffffu : 0u;
+                *reinterpret_cast<float4*>(&As[buf][kr + 16 * j][c4]) = mask4(qa[j], keep_a);
+            } else {
+                const unsigned int keep_a = (m0 + am + 32 * j < M && k0 + ak4 < kend) ? 0xffffffffu : 0u;
+                const float4 v = mask4(qa[j], keep_a);
+                As[buf][ak4 + 0][am + 32 * j] = v.x;
+                As[buf][ak4 + 1][am + 32 * j] = v.y;
+                As[buf][ak4 + 2][am + 32 * j] = v.z;
+                As[buf][ak4 + 3][am + 32 * j] = v.w;
+            }
+        }
+    };
+
+    floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+
+    const int half = lane >> 5, l32 = lane & 31;
+    const int nk = (kend - kbeg + FK - 1) / FK;
+    // (K-steps past the end of the range load clamped addresses and are never stored)
+    // the fences keep the issue order of the register sets (oldest first), so that waiting for one set
+    // leaves the younger one in flight, and keep the refill in front of the matrix instructions
+#pragma unroll
+    for (int u = 0; u < FPF; ++u) {
+        load(kbeg + u * FK, ra[u], rb[u]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    for (int kt0 = 0; kt0 < nk; kt0 += FPF) {
+#pragma unroll
+        for (int u = 0; u < FPF; ++u) {
+            const int kt = kt0 + u;
+            if (kt < nk) {                                          // uniform
+                const int buf = u & 1;                              // FPF is even: kt and u have the same parity
+                // this buffer was last read two K-steps ago, and every wave has passed the barrier of the
+                // K-step in between since
+                store(kbeg + kt * FK, buf, ra[u], rb[u]);
+                lds_barrier();
+                load(kbeg + (kt + FPF) * FK, ra[u], rb[u]);         // refill the registers just consumed
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int kk = 0; kk < FK; kk += 2) {
+                    const float a = As[buf][kk + half][wm + l32];
+                    const float b = Bs[buf][kk + half][wn + l32];
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+                }
+            }
+        }
     }
     float* Cz = Cout + (int64_t)tz * cstride;
     const int col = n0 + wn + l32;
@@ -443,8 +562,8 @@ GemmPlan plan_split(int M, int N, int K, int sm_count) {
     int s = (2 * sm_count) / (tiles > 0 ? tiles : 1);
     if (s < 1) s = 1;
     if (s > 8) s = 8;
-    int klen = ((K + s - 1) / s + TK - 1) / TK * TK;
-    if (klen < TK) klen = TK;
+    int klen = ((K + s - 1) / s + FK - 1) / FK * FK;
+    if (klen < FK) klen = FK;
     s = (K + klen - 1) / klen;
     return {s, klen};
 }
@@ -456,7 +575,12 @@ void launch_gemm(fosi_ctx* ctx, const float* A, int lda, const float* Bm, int ld
     const dim3 grid((tiles + 7) / 8 * 8);
     const bool vec = (lda % 4 == 0) && (ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(A) & 15) == 0) &&
                      ((reinterpret_cast<uintptr_t>(Bm) & 15) == 0);
-    if (vec)
+    // whole 16-byte groups only: N (columns of B) and the contiguous extent of A (M if stored K x M, else K)
+    const bool aligned = vec && N % 4 == 0 && (A_KM ? M : K) % 4 == 0 && plan.klen % FK == 0;
+    if (aligned)
+        hipLaunchKernelGGL((k_gemm_f32_aligned<A_KM>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N,
+                           K, plan.klen, plan.nsplit, cstride, scale);
+    else if (vec)
         hipLaunchKernelGGL((k_gemm_f32<A_KM, true>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N, K,
                            plan.klen, plan.nsplit, cstride, scale);
     else
@@ -563,7 +687,7 @@ fosi_status ggn_apply(fosi_hvp* op, const float* v, float* hv) {
     // Z = X V (split along d), Y = softmax-Jacobian rows of Z, hv = X^T Y / B
     launch_gemm<false>(ctx, op->X, d, v, C, op->Z, C, B, C, d, plan, bc, 1.f);
     hipLaunchKernelGGL(k_softmax_jacobian, dim3(B), dim3(256), 0, ctx->stream, op->Z, plan.nsplit, bc, C, op->P);
-    launch_gemm<true>(ctx, op->X, d, op->Z, C, hv, C, d, C, B, GemmPlan{1, (B + TK - 1) / TK * TK}, 0,
+    launch_gemm<true>(ctx, op->X, d, op->Z, C, hv, C, d, C, B, GemmPlan{1, (B + FK - 1) / FK * FK}, 0,
                       1.f / (float)B);
     return FOSI_OK;
 }
