@@ -124,7 +124,9 @@ def bench_ggn(args, fo, torch, np) -> int:
 
     for _ in range(args.warmup):
         one_step()
-    ctx.profile_enable(True)
+    # timed region: HIP events around the operator only (events around every kernel would add ~5 us of
+    # stream time per event to a step of a few hundred short kernels)
+    ctx.profile_enable("hvp_ggn")
     ctx.profile_reset()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -132,11 +134,15 @@ def bench_ggn(args, fo, torch, np) -> int:
         one_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ctx.profile_enable(False)
     cnt, ms, flops = ctx.profile_read("hvp_ggn")
     tf = flops / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
     peak = 2500.0 if bf16 else 157.3
-    phases = {}
+    # per-class breakdown from one more, untimed step with events around every kernel class
+    ctx.profile_enable(True)
+    ctx.profile_reset()
+    one_step()
+    ctx.profile_enable(False)
+    phases = {"note": "one extra untimed step with events around every kernel class"}
     for name in ("hvp_ggn", "reorth_dot", "reorth_sub", "normalise", "ritz_vectors"):
         c, m_, by = ctx.profile_read(name)
         if c:
@@ -325,7 +331,11 @@ def main() -> int:
 
     for _ in range(args.warmup):
         one_step()
-    ctx.profile_enable(True)
+    # Timed region: HIP events (on the library's stream) around the dominant kernel only -- the operator's expand
+    # sweep (k_combine_columns<false,true,false,false,LDOT,...>: U, the current and, from the second Lanczos step
+    # on in 'local_full' mode, the previous Lanczos vector, one store).  Events around every kernel would add
+    # ~5 us of stream time per event, which matters for the small workloads.
+    ctx.profile_enable("hvp_expand")
     ctx.profile_reset()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -333,7 +343,8 @@ def main() -> int:
         one_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ctx.profile_enable(False)
+    cnt, ms, by = ctx.profile_read("hvp_expand")
+    achieved = by / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
 
     ms_per_step = dt / args.steps * 1e3
     vec_bytes = 4.0 * w.n
@@ -343,16 +354,17 @@ def main() -> int:
     step_bytes = vecs["total"] * vec_bytes
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    phases = {}
+    # per-class breakdown from one more, untimed step with events around every kernel class
+    ctx.profile_enable(True)
+    ctx.profile_reset()
+    one_step()
+    ctx.profile_enable(False)
+    phases = {"note": "one extra untimed step with events around every kernel class"}
     for name in ("hvp_project", "hvp_expand", "reorth_dot", "reorth_sub", "normalise", "ritz_vectors", "step", "admm"):
-        cnt, ms, by = ctx.profile_read(name)
-        if cnt:
-            phases[name] = {"launches": cnt, "ms_total": round(ms, 3), "avg_ms": round(ms / cnt, 4),
-                            "GBps": round(by / (ms * 1e-3) / 1e9, 1) if ms > 0 else None}
-    # dominant kernel: the operator's expand sweep (k_combine_columns<false,true,false,false,LDOT,...>): U, the
-    # current and (from the second Lanczos step on, in 'local_full' mode) the previous Lanczos vector, one store
-    cnt, ms, by = ctx.profile_read("hvp_expand")
-    achieved = by / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        c_, m_, b_ = ctx.profile_read(name)
+        if c_:
+            phases[name] = {"launches": c_, "ms_total": round(m_, 3), "avg_ms": round(m_ / c_, 4),
+                            "GBps": round(b_ / (m_ * 1e-3) / 1e9, 1) if m_ > 0 else None}
     traffic = None
     tfile = os.path.join(ROOT, "profiles", f"hvp_expand_cfg{args.config}_pmc.txt")
     if os.path.exists(tfile) and args.n is None:

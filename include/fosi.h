@@ -248,6 +248,10 @@ fosi_status fosi_admm_end(fosi_ctx* ctx, int64_t n, float sigma, const float* w_
                                     /* field returns its GEMM flops (4 B d C) instead  */
 #define FOSI_PROF_HVP_OTHER     9   /* diagonal / callback operators                   */
 #define FOSI_PROF_NUM          10
+/* on = 0: off; 1: every class; FOSI_PROF_ONLY(c) [| FOSI_PROF_ONLY(c2) ...]: only those classes.  Two events
+ * around a kernel cost about 5 us of stream time each on MI355X (the stream drains at every event), so a
+ * timed run that must not be disturbed selects the one class it needs. */
+#define FOSI_PROF_ONLY(kernel_class) (1 << ((kernel_class) + 1))
 fosi_status fosi_profile_enable(fosi_ctx* ctx, int on);
 fosi_status fosi_profile_reset(fosi_ctx* ctx);
 fosi_status fosi_profile_read(fosi_ctx* ctx, int kernel_class, int64_t* launches, double* total_ms,

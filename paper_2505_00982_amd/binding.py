@@ -231,7 +231,15 @@ class Context:
         return Hvp(self, h, n, keep=(cb, fn))
 
     # -- timers
-    def profile_enable(self, on: bool = True):
+    def profile_enable(self, on=True):
+        """True / False: every kernel class / none; a class name or a list of names: only those classes."""
+        if isinstance(on, str):
+            on = [on]
+        if isinstance(on, (list, tuple)):
+            mask = 0
+            for name in on:
+                mask |= 1 << (PROF[name] + 1)
+            on = mask
         self.check(self.lib.fosi_profile_enable(self.handle, int(on)))
 
     def profile_reset(self):

@@ -22,7 +22,9 @@ fosi_status check_hip(fosi_ctx* ctx, hipError_t e, const char* what) {
 }
 
 void prof_begin(fosi_ctx* ctx, int cls, double bytes) {
+    ctx->prof_open = false;
     if (!ctx->prof_on) return;
+    if (ctx->prof_mask != 1 && ((ctx->prof_mask >> (cls + 1)) & 1) == 0) return;   // class not selected
     ProfRecord r{};
     r.cls = cls;
     r.bytes = bytes;
@@ -36,11 +38,13 @@ void prof_begin(fosi_ctx* ctx, int cls, double bytes) {
     }
     (void)hipEventRecord(r.start, ctx->stream);
     ctx->prof.push_back(r);
+    ctx->prof_open = true;
 }
 
 void prof_end(fosi_ctx* ctx) {
-    if (!ctx->prof_on || ctx->prof.empty()) return;
+    if (!ctx->prof_on || !ctx->prof_open || ctx->prof.empty()) return;
     (void)hipEventRecord(ctx->prof.back().stop, ctx->stream);
+    ctx->prof_open = false;
 }
 
 namespace {
@@ -904,7 +908,9 @@ fosi_status fosi_admm_end(fosi_ctx* ctx, int64_t n, float sigma, const float* w_
 
 fosi_status fosi_profile_enable(fosi_ctx* ctx, int on) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (on < 0) return fail(ctx, FOSI_ERR_INVALID_ARG, "bad profile selection");
     ctx->prof_on = on != 0;
+    ctx->prof_mask = on;
     return FOSI_OK;
 }
 

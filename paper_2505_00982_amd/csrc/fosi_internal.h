@@ -66,6 +66,8 @@ struct fosi_ctx {
     fosi::Tunables tun{};
     std::string last_error;
     bool prof_on = false;
+    int prof_mask = 1;                  // 1: every kernel class; else bit (class + 1) selects a class
+    bool prof_open = false;             // the last prof_begin recorded a start event
     std::vector<fosi::ProfRecord> prof;
     std::vector<hipEvent_t> event_pool;
     std::vector<double> newton_cache;   // host copy of what `s.newton` holds

@@ -102,6 +102,30 @@ def test_planted_operator_matches_oracle(fo, ctx, n):
     op.close()
 
 
+def test_profile_class_selection(fo, ctx):
+    """The opt-in timers can be limited to chosen kernel classes; the others record nothing."""
+    w = wl.planted_workload(1)
+    Ud = fo.ColMajor.from_numpy(w.U, wl.padded_ld(w.n))
+    op = ctx.hvp_planted(Ud, dev(w.lam), float(w.shift))
+    vd, out = dev(w.v1), torch.zeros(w.n, device="cuda")
+    try:
+        for selection, expect in (("hvp_expand", (0, 2)), (["hvp_project", "hvp_expand"], (2, 2)), (True, (2, 2)),
+                                  (False, (0, 0))):
+            ctx.profile_enable(selection)
+            ctx.profile_reset()
+            op.apply(vd, out)
+            op.apply(vd, out)
+            got = (ctx.profile_read("hvp_project")[0], ctx.profile_read("hvp_expand")[0])
+            assert got == expect, (selection, got)
+            if expect[1]:
+                cnt, ms, by = ctx.profile_read("hvp_expand")
+                assert ms > 0 and by == cnt * (w.r + 2) * 4 * w.n
+    finally:
+        ctx.profile_enable(False)
+        ctx.profile_reset()
+        op.close()
+
+
 def test_diag_operator_and_full_spectrum(fo, ctx):
     n = 48
     d = (np.linspace(-3.0, 7.0, n) + 0.01 * np.arange(n) ** 1.5).astype(np.float32)
