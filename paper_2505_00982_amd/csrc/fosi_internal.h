@@ -26,6 +26,7 @@ struct ProfRecord {
 
 struct Tunables {
     int dot_target_blocks;    // workgroups launched by the transposed product (it grid-strides over rows)
+    int dot_slot_cols;        // columns per wave in that kernel: 8, 16 or 32; 0 = chosen from the row count
     int comb_rows_per_thread; // RPT: float4 row groups per thread in the column-combination kernel
     int comb_cols_unroll;     // CU: columns loaded together in that kernel
     int comb_max_blocks;      // cap on that kernel's grid (it grid-strides over row tiles); 0 = no cap

@@ -54,14 +54,14 @@ __device__ __forceinline__ double block_sum(double v, double* lds4) {
 }
 
 // ---------------------------------------------------------------- dot_columns
-// Work is split per wavefront: a wave owns a "slot" of up to 32 consecutive columns and sweeps
+// Work is split per wavefront: a wave owns a "slot" of up to JB (16 or 32) consecutive columns and sweeps
 // float4 row groups (64 lanes x 4 rows) with a grid stride, keeping one fp64 accumulator per
-// column.  The S (= 1, 2 or 4) waves of a block that own different slots walk the SAME rows, so
-// the vector x is fetched from HBM once and re-read from the CU's L1; the remaining 4/S waves of
-// the block take other rows.  The sweep is compiled for 4, 8, ..., 32 columns; a slot whose width
+// column.  Consecutive waves (across the grid) own consecutive slots and walk the SAME rows, so the
+// waves of a block mostly share their rows of the vector x (one fetch, then cache hits) and no wave is
+// idle whatever the number of slots.  The sweep is compiled for 4, 8, ..., JB columns; a slot whose width
 // is not a multiple of 4 re-reads its last column for the (at most 3) padding positions, which hit
-// in cache and are discarded.  partials[column * pslots + rowslot] receives the wave's sums (the row
-// slots of a column are contiguous, so that the second stage reads them with coalesced loads), column
+// in cache and are discarded.  partials[column * nrowlanes + rowlane] receives the wave's sums (the row
+// lanes of a column are contiguous, so that the second stage reads them with coalesced loads), column
 // index `ncols` the partial of sum(x^2) (from the waves of slot 0).
 
 // One sweep of a slot compiled for NCOL columns (nc <= NCOL of them real).  `Aj0` points at row 0 of
@@ -123,20 +123,22 @@ template <int JB, int NX>
 __global__ __launch_bounds__(kThreads) void k_dot_columns(
     const float* __restrict__ A, int64_t lda, int ncols, const float* __restrict__ x,
     const float* __restrict__ x2, const float* __restrict__ x3, const double* __restrict__ xs, int64_t n,
-    double* __restrict__ partials, int pslots, int S, const int* __restrict__ stop) {
-    static_assert(JB == 32, "the sweep variants below cover slots of up to 32 columns");
+    double* __restrict__ partials, int nslots, int nrowlanes, const int* __restrict__ stop) {
+    static_assert(JB == 8 || JB == 16 || JB == 32, "the sweep variants below cover slots of up to 8, 16 or 32 columns");
     if (stop != nullptr && *stop != 0) return;
     const int lane = threadIdx.x & 63;
     // the wave index is the same for all 64 lanes: tell the compiler, so that the slot and its column
     // bases live in scalar registers
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int slot = blockIdx.y * S + (wave % S);       // column slot of this wave
-    const int rowlane = wave / S;                       // which of the block's 4/S row groups
-    const int rows_per_block = 4 / S;
+    // waves are numbered across the grid: consecutive waves take consecutive column slots of the same row
+    // lane, so every wave has work whatever the number of slots, and the waves of a block mostly share rows
+    const int gw = blockIdx.x * 4 + wave;
+    const int slot = gw % nslots;
+    const int rowlane = gw / nslots;
+    if (rowlane >= nrowlanes) return;                   // spare waves of the last block
     const int j0 = slot * JB;
     const int nc = max(0, min(JB, ncols - j0));
     const bool do_xx = (slot == 0);
-    if (nc == 0 && !do_xx) return;
 
     double acc[JB];
 #pragma unroll
@@ -144,47 +146,52 @@ __global__ __launch_bounds__(kThreads) void k_dot_columns(
     double xx = 0.0;
 
     const int64_t n4 = n >> 2;
-    // row groups are handed out round-robin over (block, row lane); all uniform across the wave (float4 units)
-    const int64_t t_begin = ((int64_t)blockIdx.x * rows_per_block + rowlane) * 64;
+    // row groups are handed out round-robin over the row lanes; all uniform across the wave (float4 units)
+    const int64_t t_begin = (int64_t)rowlane * 64;
     const int64_t r_end = n4;
-    const int64_t stride = (int64_t)gridDim.x * rows_per_block * 64;
+    const int64_t stride = (int64_t)nrowlanes * 64;
     const double s2 = NX >= 2 ? xs[0] : 0.0, s3 = NX >= 3 ? xs[1] : 0.0;
     const float* Aj0 = A + (int64_t)j0 * lda;
 #define FOSI_SWEEP(NC_) dot_sweep<NC_, NX>(Aj0, lda, nc, x, x2, x3, s2, s3, t_begin, r_end, stride, lane, do_xx, acc, xx)
-    switch ((nc + 3) >> 2) {
-        case 0: {   // no columns (only reached by slot 0 when ncols == 0): just the sum of squares
-            for (int64_t t = t_begin; t < r_end; t += stride) {
-                if (t + lane < r_end) {
-                    const float4 xv = reinterpret_cast<const float4*>(x)[t + lane];
-                    double d0 = xv.x, d1 = xv.y, d2 = xv.z, d3 = xv.w;
-                    if (NX >= 2) {
-                        const float4 u = reinterpret_cast<const float4*>(x2)[t + lane];
-                        d0 = fma(s2, (double)u.x, d0); d1 = fma(s2, (double)u.y, d1);
-                        d2 = fma(s2, (double)u.z, d2); d3 = fma(s2, (double)u.w, d3);
-                    }
-                    if (NX >= 3) {
-                        const float4 u = reinterpret_cast<const float4*>(x3)[t + lane];
-                        d0 = fma(s3, (double)u.x, d0); d1 = fma(s3, (double)u.y, d1);
-                        d2 = fma(s3, (double)u.z, d2); d3 = fma(s3, (double)u.w, d3);
-                    }
-                    xx = fma(d0, d0, fma(d1, d1, fma(d2, d2, fma(d3, d3, xx))));
+    const int quads = (nc + 3) >> 2;
+    if (quads == 0) {   // no columns (only reached by slot 0 when ncols == 0): just the sum of squares
+        for (int64_t t = t_begin; t < r_end; t += stride) {
+            if (t + lane < r_end) {
+                const float4 xv = reinterpret_cast<const float4*>(x)[t + lane];
+                double d0 = xv.x, d1 = xv.y, d2 = xv.z, d3 = xv.w;
+                if (NX >= 2) {
+                    const float4 u = reinterpret_cast<const float4*>(x2)[t + lane];
+                    d0 = fma(s2, (double)u.x, d0); d1 = fma(s2, (double)u.y, d1);
+                    d2 = fma(s2, (double)u.z, d2); d3 = fma(s2, (double)u.w, d3);
                 }
+                if (NX >= 3) {
+                    const float4 u = reinterpret_cast<const float4*>(x3)[t + lane];
+                    d0 = fma(s3, (double)u.x, d0); d1 = fma(s3, (double)u.y, d1);
+                    d2 = fma(s3, (double)u.z, d2); d3 = fma(s3, (double)u.w, d3);
+                }
+                xx = fma(d0, d0, fma(d1, d1, fma(d2, d2, fma(d3, d3, xx))));
             }
-            break;
         }
-        case 1: FOSI_SWEEP(4); break;
-        case 2: FOSI_SWEEP(8); break;
-        case 3: FOSI_SWEEP(12); break;
-        case 4: FOSI_SWEEP(16); break;
-        case 5: FOSI_SWEEP(20); break;
-        case 6: FOSI_SWEEP(24); break;
-        case 7: FOSI_SWEEP(28); break;
-        default: FOSI_SWEEP(32); break;
+    } else if (quads == 1) {
+        FOSI_SWEEP(4);
+    } else if (quads == 2) {
+        FOSI_SWEEP(8);
+    } else if constexpr (JB >= 16) {       // a narrower kernel never gets here and keeps its smaller register count
+        if (quads == 3) {
+            FOSI_SWEEP(12);
+        } else if (quads == 4) {
+            FOSI_SWEEP(16);
+        } else if constexpr (JB == 32) {
+            if (quads == 5) FOSI_SWEEP(20);
+            else if (quads == 6) FOSI_SWEEP(24);
+            else if (quads == 7) FOSI_SWEEP(28);
+            else FOSI_SWEEP(32);
+        }
     }
 #undef FOSI_SWEEP
     // the last (n mod 4) rows: one scalar row per lane of the first row group
     const int64_t tail_row = (n4 << 2) + lane;
-    if (blockIdx.x == 0 && rowlane == 0 && lane < 3 && tail_row < n) {
+    if (rowlane == 0 && lane < 3 && tail_row < n) {
         double dx = x[tail_row];
         if (NX >= 2) dx = fma(s2, (double)x2[tail_row], dx);
         if (NX >= 3) dx = fma(s3, (double)x3[tail_row], dx);
@@ -194,17 +201,17 @@ __global__ __launch_bounds__(kThreads) void k_dot_columns(
             if (j < nc) acc[j] = fma((double)Aj0[(int64_t)j * lda + tail_row], dx, acc[j]);
     }
 
-    double* pslot = partials + ((int64_t)blockIdx.x * rows_per_block + rowlane);
+    double* pslot = partials + rowlane;
 #pragma unroll
     for (int j = 0; j < JB; ++j) {
         if (j < nc) {                                   // uniform test: whole waves skip the padding columns
             const double v = wave_sum(acc[j]);
-            if (lane == 0) pslot[(int64_t)(j0 + j) * pslots] = v;
+            if (lane == 0) pslot[(int64_t)(j0 + j) * nrowlanes] = v;
         }
     }
     if (do_xx) {
         const double v = wave_sum(xx);
-        if (lane == 0) pslot[(int64_t)ncols * pslots] = v;
+        if (lane == 0) pslot[(int64_t)ncols * nrowlanes] = v;
     }
 }
 
@@ -989,32 +996,42 @@ void dot_columns_launch(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, c
                         const float* x3, const double* xs, int64_t n, double* coef, const float* scale, int nscale,
                         double gscale, const double* add_last2, const int* stop, int prof_cls, double prof_bytes,
                         int tail_kind, int tail_step, double tail_tol) {
-    constexpr int JB = 32;
-    const int nslots = ncols > 0 ? (ncols + JB - 1) / JB : 1;
-    const int S = nslots >= 3 ? 4 : nslots;             // waves of a block that share the same rows
-    const int gy = (nslots + S - 1) / S;
-    const int rows_per_block = 4 / S;
     const int64_t n4 = n >> 2;
-    // row slots: enough blocks to fill the chip a few times over, within the partials buffer
-    int64_t gx = (n4 + 64 * rows_per_block - 1) / (64 * rows_per_block);
-    int64_t cap = ctx->tun.dot_target_blocks / gy;
-    if (cap * rows_per_block > kMaxDotSlots) cap = kMaxDotSlots / rows_per_block;
-    if (cap < 1) cap = 1;
-    if (gx > cap) gx = cap;
-    if (gx < 1) gx = 1;
-    const int rowslots = (int)gx * rows_per_block;
-    dim3 grid((unsigned)gx, (unsigned)gy);
+    // Columns per wave: 32 (216-230 registers, two waves per SIMD), 16 (120-134, three to four) or 8.  Measured on
+    // MI355X: 16 is never slower than 32 (n = 25.6 M: 430.3 against 431.9 ms per step of workload 4; n = 2^20:
+    // 10.1 against 11.2 ms of workload 2); 8 wins below a few million rows, where a wave makes only a handful of
+    // trips (9.8 ms at n = 2^20) and loses a little on the large workloads' Gram-Schmidt products.
+    int JB = ctx->tun.dot_slot_cols;
+    if (JB != 8 && JB != 16 && JB != 32) JB = n <= ((int64_t)1 << 22) ? 8 : 16;
+    const int nslots = ncols > 0 ? (ncols + JB - 1) / JB : 1;
+    // row lanes: as many as the targeted number of resident waves allows, at most one per row group of 256 rows
+    int64_t lanes = ((int64_t)ctx->tun.dot_target_blocks * 4) / nslots;
+    const int64_t groups = (n4 + 63) / 64;
+    if (lanes > groups) lanes = groups;
+    if (lanes > kMaxDotSlots) lanes = kMaxDotSlots;
+    if (lanes < 1) lanes = 1;
+    const int rowslots = (int)lanes;
+    const int64_t waves = lanes * nslots;
+    dim3 grid((unsigned)((waves + 3) / 4));
     if (prof_cls >= 0) prof_begin(ctx, prof_cls, prof_bytes);
     if (x2 != nullptr && xs == nullptr) xs = ctx->s.scal + 2;   // plain sum of the vectors: scales 1, 1
-    if (x3 != nullptr)
-        hipLaunchKernelGGL((k_dot_columns<JB, 3>), grid, dim3(kThreads), 0, ctx->stream, A, lda, ncols, x, x2, x3, xs, n,
-                           ctx->s.partials, rowslots, S, stop);
-    else if (x2 != nullptr)
-        hipLaunchKernelGGL((k_dot_columns<JB, 2>), grid, dim3(kThreads), 0, ctx->stream, A, lda, ncols, x, x2, x3, xs, n,
-                           ctx->s.partials, rowslots, S, stop);
-    else
-        hipLaunchKernelGGL((k_dot_columns<JB, 1>), grid, dim3(kThreads), 0, ctx->stream, A, lda, ncols, x, x2, x3, xs, n,
-                           ctx->s.partials, rowslots, S, stop);
+#define FOSI_DOT(JB_, NX_)                                                                                          \
+    hipLaunchKernelGGL((k_dot_columns<JB_, NX_>), grid, dim3(kThreads), 0, ctx->stream, A, lda, ncols, x, x2, x3, xs, n, \
+                       ctx->s.partials, nslots, rowslots, stop)
+    if (JB == 8) {
+        if (x3 != nullptr) FOSI_DOT(8, 3);
+        else if (x2 != nullptr) FOSI_DOT(8, 2);
+        else FOSI_DOT(8, 1);
+    } else if (JB == 16) {
+        if (x3 != nullptr) FOSI_DOT(16, 3);
+        else if (x2 != nullptr) FOSI_DOT(16, 2);
+        else FOSI_DOT(16, 1);
+    } else {
+        if (x3 != nullptr) FOSI_DOT(32, 3);
+        else if (x2 != nullptr) FOSI_DOT(32, 2);
+        else FOSI_DOT(32, 1);
+    }
+#undef FOSI_DOT
     if (prof_cls >= 0) prof_end(ctx);
     hipLaunchKernelGGL(k_reduce_columns, dim3(ncols + 1), dim3(64), 0, ctx->stream, ctx->s.partials, rowslots, (int64_t)1,
                        (int64_t)rowslots, coef, scale, nscale, gscale, ncols, add_last2, stop,
