@@ -56,9 +56,9 @@ __device__ __forceinline__ double block_sum(double v, double* lds4) {
 // ---------------------------------------------------------------- dot_columns
 // Work is split per wavefront: a wave owns a "slot" of up to JB (16 or 32) consecutive columns and sweeps
 // float4 row groups (64 lanes x 4 rows) with a grid stride, keeping one fp64 accumulator per
-// column.  Consecutive waves (across the grid) own consecutive slots and walk the SAME rows, so the
-// waves of a block mostly share their rows of the vector x (one fetch, then cache hits) and no wave is
-// idle whatever the number of slots.  The sweep is compiled for 4, 8, ..., JB columns; a slot whose width
+// column.  Consecutive waves (of one XCD) own consecutive slots and walk the SAME rows, so the waves that
+// share rows of the vector x sit in one workgroup or at least behind one L2, and no wave is idle
+// whatever the number of slots.  The sweep is compiled for 4, 8, ..., JB columns; a slot whose width
 // is not a multiple of 4 re-reads its last column for the (at most 3) padding positions, which hit
 // in cache and are discarded.  partials[column * nrowlanes + rowlane] receives the wave's sums (the row
 // lanes of a column are contiguous, so that the second stage reads them with coalesced loads), column
@@ -130,12 +130,16 @@ __global__ __launch_bounds__(kThreads) void k_dot_columns(
     // the wave index is the same for all 64 lanes: tell the compiler, so that the slot and its column
     // bases live in scalar registers
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    // waves are numbered across the grid: consecutive waves take consecutive column slots of the same row
-    // lane, so every wave has work whatever the number of slots, and the waves of a block mostly share rows
-    const int gw = blockIdx.x * 4 + wave;
-    const int slot = gw % nslots;
-    const int rowlane = gw / nslots;
-    if (rowlane >= nrowlanes) return;                   // spare waves of the last block
+    // Waves are numbered within each XCD (the hardware deals workgroups to the 8 XCDs round-robin, and each
+    // XCD has an L2 of its own): consecutive waves take consecutive column slots of the same row lane, so every
+    // wave has work whatever the number of slots, and the waves that share rows of the vector x sit behind the
+    // same L2 (x then comes from HBM once even when a row lane's slots span several workgroups).
+    const int xcd = blockIdx.x & 7;
+    const int lw = (int)(blockIdx.x >> 3) * 4 + wave;
+    const int slot = lw % nslots;
+    const int lane_in_xcd = lw / nslots;
+    if (lane_in_xcd >= (nrowlanes >> 3)) return;        // spare waves of an XCD's last workgroup
+    const int rowlane = lane_in_xcd * 8 + xcd;
     const int j0 = slot * JB;
     const int nc = max(0, min(JB, ncols - j0));
     const bool do_xx = (slot == 0);
@@ -735,18 +739,41 @@ __device__ __forceinline__ double block_sum_strided(const double* __restrict__ p
 
 // Sums the {out^2, out.x1, out.x3} partials of the operator's expand sweep: loc = {alpha~, beta~, ||h||^2},
 // neg = {-alpha~, -beta~} (the scales with which q_i and q_{i-1} enter the vector of the full pass).
-// Partial w of slot i lives at parts[w * wstride + i * sstride].
-__global__ __launch_bounds__(kThreads) void k_reduce_local(const double* __restrict__ parts, int nslots, int64_t wstride,
-                                                           int64_t sstride, double* __restrict__ loc,
-                                                           double* __restrict__ neg, const int* __restrict__ stop) {
+// Partial w of slot i lives at parts[w * wstride + i * sstride].  One workgroup of 1024 threads: the partials
+// were written by other compute units, every load is a trip to memory, so all loads of a thread (a few slots
+// x 3) are issued before the first sum.
+constexpr int kLocalThreads = 1024;
+__global__ __launch_bounds__(kLocalThreads) void k_reduce_local(const double* __restrict__ parts, int nslots,
+                                                                 int64_t wstride, int64_t sstride,
+                                                                 double* __restrict__ loc, double* __restrict__ neg,
+                                                                 const int* __restrict__ stop) {
     if (stop != nullptr && *stop != 0) return;
-    __shared__ double red[4];
-    const double s0 = block_sum_strided(parts, nslots, sstride, red);
-    const double s1 = block_sum_strided(parts + wstride, nslots, sstride, red);
-    const double s3 = block_sum_strided(parts + 2 * wstride, nslots, sstride, red);
+    __shared__ double red[3][kLocalThreads / 64];
+    double s0 = 0.0, s1 = 0.0, s3 = 0.0;
+    int i = threadIdx.x;
+    for (; i + 3 * kLocalThreads < nslots; i += 4 * kLocalThreads) {       // 12 independent loads per trip
+        double v[4][3];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int w = 0; w < 3; ++w) v[u][w] = parts[w * wstride + (int64_t)(i + u * kLocalThreads) * sstride];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { s0 += v[u][0]; s1 += v[u][1]; s3 += v[u][2]; }
+    }
+    for (; i < nslots; i += kLocalThreads) {
+        const double v0 = parts[(int64_t)i * sstride], v1 = parts[wstride + (int64_t)i * sstride];
+        const double v2 = parts[2 * wstride + (int64_t)i * sstride];
+        s0 += v0; s1 += v1; s3 += v2;
+    }
+    s0 = wave_sum(s0); s1 = wave_sum(s1); s3 = wave_sum(s3);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { red[0][wave] = s0; red[1][wave] = s1; red[2][wave] = s3; }
+    __syncthreads();
     if (threadIdx.x == 0) {
-        loc[0] = s1; loc[1] = s3; loc[2] = s0;
-        neg[0] = -s1; neg[1] = -s3;
+        double t0 = 0.0, t1 = 0.0, t3 = 0.0;
+        for (int q = 0; q < kLocalThreads / 64; ++q) { t0 += red[0][q]; t1 += red[1][q]; t3 += red[2][q]; }
+        loc[0] = t1; loc[1] = t3; loc[2] = t0;
+        neg[0] = -t1; neg[1] = -t3;
     }
 }
 
@@ -1004,15 +1031,16 @@ void dot_columns_launch(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, c
     int JB = ctx->tun.dot_slot_cols;
     if (JB != 8 && JB != 16 && JB != 32) JB = n <= ((int64_t)1 << 22) ? 8 : 16;
     const int nslots = ncols > 0 ? (ncols + JB - 1) / JB : 1;
-    // row lanes: as many as the targeted number of resident waves allows, at most one per row group of 256 rows
-    int64_t lanes = ((int64_t)ctx->tun.dot_target_blocks * 4) / nslots;
+    // row lanes (a multiple of 8, one share per XCD): as many as the targeted number of resident waves allows, not
+    // more than the row groups of 256 rows (rounded up to 8; a row lane without rows contributes zeros)
+    int64_t per_xcd = ((int64_t)ctx->tun.dot_target_blocks * 4 / 8) / nslots;
     const int64_t groups = (n4 + 63) / 64;
-    if (lanes > groups) lanes = groups;
-    if (lanes > kMaxDotSlots) lanes = kMaxDotSlots;
-    if (lanes < 1) lanes = 1;
-    const int rowslots = (int)lanes;
-    const int64_t waves = lanes * nslots;
-    dim3 grid((unsigned)((waves + 3) / 4));
+    if (per_xcd > (groups + 7) / 8) per_xcd = (groups + 7) / 8;
+    if (per_xcd > kMaxDotSlots / 8) per_xcd = kMaxDotSlots / 8;
+    if (per_xcd < 1) per_xcd = 1;
+    const int rowslots = (int)per_xcd * 8;
+    const int64_t blocks_per_xcd = (per_xcd * nslots + 3) / 4;
+    dim3 grid((unsigned)(blocks_per_xcd * 8));
     if (prof_cls >= 0) prof_begin(ctx, prof_cls, prof_bytes);
     if (x2 != nullptr && xs == nullptr) xs = ctx->s.scal + 2;   // plain sum of the vectors: scales 1, 1
 #define FOSI_DOT(JB_, NX_)                                                                                          \
@@ -1118,11 +1146,11 @@ void launch_lanczos_finalize_early(fosi_ctx* ctx, int step, const double* coef, 
 void launch_reduce_local(fosi_ctx* ctx, int nslots, const int* stop, const double* parts) {
     // the expand sweep leaves [3][nslots]; a caller's buffer holds one {out^2, out.x1, out.x3} triple per slot
     if (parts == nullptr)
-        hipLaunchKernelGGL(k_reduce_local, dim3(1), dim3(kThreads), 0, ctx->stream, ctx->s.norm_partials, nslots,
+        hipLaunchKernelGGL(k_reduce_local, dim3(1), dim3(kLocalThreads), 0, ctx->stream, ctx->s.norm_partials, nslots,
                            (int64_t)nslots, (int64_t)1, ctx->s.loc, ctx->s.scal + 4, stop);
     else
-        hipLaunchKernelGGL(k_reduce_local, dim3(1), dim3(kThreads), 0, ctx->stream, parts, nslots, (int64_t)1, (int64_t)3,
-                           ctx->s.loc, ctx->s.scal + 4, stop);
+        hipLaunchKernelGGL(k_reduce_local, dim3(1), dim3(kLocalThreads), 0, ctx->stream, parts, nslots, (int64_t)1,
+                           (int64_t)3, ctx->s.loc, ctx->s.scal + 4, stop);
 }
 
 void launch_fold_partials(fosi_ctx* ctx, int nslots, int width, double* dst, const int* stop) {

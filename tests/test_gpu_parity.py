@@ -207,6 +207,31 @@ def test_repeat_is_bit_identical(fo, ctx, cfg1):
     assert torch.equal(g["V"].buf, g2["V"].buf)
 
 
+def test_many_repeats_are_bit_identical(fo, ctx):
+    """Every cross-workgroup sum has a fixed order and the step's scalars are finished by whichever workgroup of
+    the reduction arrives last (release fence, arrival counter, acquire fence): thirty runs of the same problem,
+    with other kernels of the same context in between, must agree in every bit."""
+    w = wl.planted_workload(2, n=70001)
+    ld = wl.padded_ld(w.n)
+    U = fo.ColMajor.from_numpy(w.U, ld)
+    op = ctx.hvp_planted(U, dev(w.lam), float(w.shift))
+    Q = fo.ColMajor(w.n, 25, ld)
+    v1, scratch = dev(w.v1), torch.zeros(w.n, device="cuda")
+    first = None
+    for rep in range(30):
+        Q.col(0).copy_(v1)
+        alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, 24)
+        got = (alpha.copy(), beta.copy(), m_eff, Q.buf.clone())
+        if first is None:
+            first = got
+        else:
+            assert got[2] == first[2] and np.array_equal(got[0], first[0]) and np.array_equal(got[1], first[1]), rep
+            assert torch.equal(got[3], first[3]), rep
+        if rep % 3 == 0:
+            op.apply(v1, scratch)     # unrelated work through the same reduction kernels
+    op.close()
+
+
 # ------------------------------------------------------------------ ragged sizes, single pass, small k+l
 @pytest.mark.parametrize("mode", [2, 3])      # two full passes; local pass + full pass (the default)
 @pytest.mark.parametrize("n,m,k,l", [(1000 + 3, 12, 1, 0), (4096 + 61, 20, 3, 2), (70001, 24, 4, 3)])
@@ -268,6 +293,13 @@ def test_update_step_against_oracle(fo, ctx, n, r, with_pi):
         w_ref, b_ref = oracle.fosi_step(w_ref, g, Vh, ev, b_ref, f32(0.1), f32(0.01), f32(0.9), f32(5e-4), pi=pi)
     assert rel_l2(wd.cpu().numpy(), w_ref) <= STEP_RTOL
     assert rel_l2(md.cpu().numpy(), b_ref) <= STEP_RTOL
+    # the update itself (Delta_1 + Delta_2), to the same bar: starting from w = 0 the new point IS the update, so
+    # the fp32 storage of an O(1) point does not mask its error
+    wz, mz = torch.zeros(n, device="cuda"), dev(b0)
+    fo.fosi_step(ctx, V, r, ev, dev(g), dev(pi) if with_pi else None, mz, wz, sp)
+    ctx.synchronize()
+    d_ref, _ = oracle.fosi_step(np.zeros(n), g, Vh, ev, b0, f32(0.1), f32(0.01), f32(0.9), f32(5e-4), pi=pi)
+    assert rel_l2(wz.cpu().numpy(), d_ref) <= STEP_RTOL
 
 
 @pytest.mark.parametrize("n,r", [(5, 1), (1025, 0), (50003, 15), (50003, 40), (9999, 200)])
