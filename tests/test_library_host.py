@@ -79,6 +79,33 @@ def test_tridiagonal_solver_special_cases(fo):
     assert np.abs(ev - (2 - 2 * np.cos(j * np.pi / (m + 1)))).max() < 1e-13
 
 
+def test_tridiagonal_solver_on_generated_matrices(fo):
+    """Property test over generated tridiagonals: sizes 1..40, entries spanning many orders of magnitude, exact
+    zeros on the off-diagonal (decoupled blocks), repeated diagonal entries, negative off-diagonal entries."""
+    from hypothesis import given, settings, strategies as st
+
+    magnitudes = st.sampled_from([0.0, 1e-12, 1e-3, 1.0, 7.5, 1e4, 1e9])
+    entry = st.tuples(st.sampled_from([-1.0, 1.0]), magnitudes, st.floats(0.5, 1.5)).map(lambda t: t[0] * t[1] * t[2])
+    repeated = st.sampled_from([2.0, 2.0, -3.0, 0.0])
+
+    @settings(max_examples=150, deadline=None, derandomize=True)
+    @given(st.integers(1, 40).flatmap(lambda m: st.tuples(
+        st.lists(st.one_of(entry, repeated), min_size=m, max_size=m),
+        st.lists(entry, min_size=max(m - 1, 0), max_size=max(m - 1, 0)))))
+    def check(ab):
+        a, b = np.array(ab[0], dtype=np.float64), np.array(ab[1], dtype=np.float64)
+        m = len(a)
+        ev, Z = fo.fosi_tridiag_eigh(a, b)
+        T = np.diag(a) + (np.diag(b, 1) + np.diag(b, -1) if m > 1 else 0)
+        scale = max(np.abs(T).sum(axis=1).max(), 1e-300)           # infinity norm bounds the spectrum
+        assert np.all(np.diff(ev) >= 0)
+        assert np.abs(ev - np.linalg.eigvalsh(T)).max() <= 1e-13 * scale
+        assert np.abs(T @ Z - Z * ev).max() <= 1e-12 * scale
+        assert np.abs(Z.T @ Z - np.eye(m)).max() <= 1e-12
+
+    check()
+
+
 def test_tridiagonal_solver_rejects_bad_input(fo):
     lib = fo.load_library()
     ev = np.zeros(3)
