@@ -417,6 +417,59 @@ def test_nonfinite_operator_is_reported(fo, ctx):
     op.close()
 
 
+def test_degenerate_inputs(fo, ctx):
+    """The degenerate cases of the method, each checked against what the oracle does with the same input:
+    a multiple of the identity (the Krylov space has dimension 1), the zero operator, a start vector that is
+    already an eigenvector, k + l equal to the number of steps taken, and a zero start vector (an error)."""
+    n = 1000 + 3
+    v1 = wl.normal_vector(1, 95, n)
+    # H = 2.5 I: one step, alpha = 2.5, beta = 0 -> breakdown, one Ritz pair, its vector is the start vector
+    for d_val, alpha_expect in ((2.5, 2.5), (0.0, 0.0)):
+        d = np.full(n, d_val, dtype=np.float32)
+        op = ctx.hvp_diag(dev(d))
+        Q = fo.ColMajor(n, 7)
+        Q.col(0).copy_(dev(v1))
+        alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, 6)
+        res = oracle.lanczos(lambda v: oracle.hvp_diag(d, v), v1, 6)
+        assert m_eff == res.m_eff == 1
+        assert abs(alpha[0] - alpha_expect) <= 1e-6 and abs(res.alpha[0] - alpha_expect) <= 1e-12
+        V = fo.ColMajor(n, 1)
+        evals, _ = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, 1, 0, V)
+        assert abs(evals[0] - alpha_expect) <= 1e-6
+        unit = v1.astype(np.float64) / np.linalg.norm(v1.astype(np.float64))
+        assert rel_l2(V.to_numpy()[:, 0], unit) <= 1e-6
+        with pytest.raises(fo.FosiError) as e:                       # more pairs than steps taken
+            fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, 1, 1, fo.ColMajor(n, 2))
+        assert e.value.status == -3
+        op.close()
+    # start vector = eigenvector of a diagonal operator: breakdown after the first step on both sides
+    d = np.linspace(1.0, 9.0, n).astype(np.float32)
+    e7 = np.zeros(n, dtype=np.float32)
+    e7[7] = 3.0
+    op = ctx.hvp_diag(dev(d))
+    Q = fo.ColMajor(n, 5)
+    Q.col(0).copy_(dev(e7))
+    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, 4)
+    assert m_eff == oracle.lanczos(lambda v: oracle.hvp_diag(d, v), e7, 4).m_eff == 1
+    assert abs(alpha[0] - float(d[7])) <= 1e-6 * float(d[7])
+    # k + l = m_eff exactly: every Ritz pair is requested (top 3 and bottom 2 of 5 steps)
+    Q = fo.ColMajor(n, 6)
+    Q.col(0).copy_(dev(v1))
+    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, 5)
+    V = fo.ColMajor(n, 5)
+    evals, _ = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, 3, 2, V)
+    res = oracle.lanczos(lambda v: oracle.hvp_diag(d, v), v1, 5)
+    rz = oracle.ritz(res.Q, res.alpha, res.beta, res.m_eff, 3, 2)
+    assert m_eff == 5 and np.max(np.abs(evals - rz.evals) / np.abs(rz.evals)) <= EVAL_RTOL
+    assert sin_principal_angles(rz.V, V.to_numpy().astype(np.float64)).max() < ANGLE_TOL
+    # zero start vector: nothing to normalise
+    Q.col(0).zero_()
+    with pytest.raises(fo.FosiError) as e:
+        fo.fosi_lanczos(ctx, op, Q, 3)
+    assert e.value.status == -4
+    op.close()
+
+
 def test_callback_operator_matches_builtin(fo, ctx):
     n = 3000
     d = dev(np.linspace(0.5, 9.0, n))
