@@ -331,6 +331,46 @@ __global__ __launch_bounds__(256) void k_softmax_jacobian(float* __restrict__ pa
     }
 }
 
+// The same for C <= 256 * ZPT: a thread keeps its ZPT entries of the row in registers, so the partial products
+// and p are read once and all loads of a row are in flight together (one memory round trip, then the row sum,
+// then the stores) instead of two dependent passes over the row.
+template <int ZPT>
+__global__ __launch_bounds__(256) void k_softmax_jacobian_reg(float* __restrict__ parts, int nsplit, int64_t pstride,
+                                                              int C, const float* __restrict__ P) {
+    __shared__ double red[4];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int64_t base = (int64_t)b * C;
+    float z[ZPT], pv[ZPT];
+#pragma unroll
+    for (int i = 0; i < ZPT; ++i) {
+        const int c = tid + 256 * i;
+        const int cc = c < C ? c : C - 1;                 // clamped: no branch around the loads
+        pv[i] = P[base + cc];
+        float acc = 0.f;
+        for (int s = 0; s < nsplit; ++s) acc += parts[s * pstride + base + cc];
+        z[i] = acc;
+    }
+    double dot = 0.0;
+#pragma unroll
+    for (int i = 0; i < ZPT; ++i)
+        if (tid + 256 * i < C) dot = fma((double)pv[i], (double)z[i], dot);
+    dot = block_sum_d(dot, red);
+#pragma unroll
+    for (int i = 0; i < ZPT; ++i) {
+        const int c = tid + 256 * i;
+        if (c < C) parts[base + c] = (float)((double)pv[i] * ((double)z[i] - dot));
+    }
+}
+
+void launch_softmax_jacobian(fosi_ctx* ctx, float* parts, int nsplit, int64_t pstride, int B, int C, const float* P) {
+    if (C <= 1024)
+        hipLaunchKernelGGL((k_softmax_jacobian_reg<4>), dim3(B), dim3(256), 0, ctx->stream, parts, nsplit, pstride, C, P);
+    else if (C <= 2048)
+        hipLaunchKernelGGL((k_softmax_jacobian_reg<8>), dim3(B), dim3(256), 0, ctx->stream, parts, nsplit, pstride, C, P);
+    else
+        hipLaunchKernelGGL(k_softmax_jacobian, dim3(B), dim3(256), 0, ctx->stream, parts, nsplit, pstride, C, P);
+}
+
 // ---------------------------------------------------------------- bf16 matrix cores, split operand
 // C[z] (M x N, row-major, ldc) = A[:, kz] * B[kz, :] with A given in bf16 (M x K row-major, k
 // contiguous) and the fp32 matrix B (K x N) given as two bf16 matrices, b = hi + lo with
@@ -671,7 +711,7 @@ fosi_status ggn_apply(fosi_hvp* op, const float* v, float* hv) {
         unsigned short* s2l = op->S2 + (size_t)C * ((B + 7) / 8 * 8);
         // Z = X V (split along d), Y = softmax-Jacobian rows of Z, hv = X^T Y / B (split along the batch)
         launch_gemm_bf16(ctx, op->Xb, d, v, C, s1h, s1l, op->Z, C, B, C, d, p1, bc, 1.f);
-        hipLaunchKernelGGL(k_softmax_jacobian, dim3(B), dim3(256), 0, ctx->stream, op->Z, p1.nsplit, bc, C, op->P);
+        launch_softmax_jacobian(ctx, op->Z, p1.nsplit, bc, B, C, op->P);
         if (p2.nsplit == 1) {
             launch_gemm_bf16(ctx, op->XTb, B, op->Z, C, s2h, s2l, hv, C, d, C, B, p2, 0, 1.f / (float)B);
         } else {
@@ -686,7 +726,7 @@ fosi_status ggn_apply(fosi_hvp* op, const float* v, float* hv) {
     const GemmPlan plan = plan_split(B, C, d, ctx->sm_count);
     // Z = X V (split along d), Y = softmax-Jacobian rows of Z, hv = X^T Y / B
     launch_gemm<false>(ctx, op->X, d, v, C, op->Z, C, B, C, d, plan, bc, 1.f);
-    hipLaunchKernelGGL(k_softmax_jacobian, dim3(B), dim3(256), 0, ctx->stream, op->Z, plan.nsplit, bc, C, op->P);
+    launch_softmax_jacobian(ctx, op->Z, plan.nsplit, bc, B, C, op->P);
     launch_gemm<true>(ctx, op->X, d, op->Z, C, hv, C, d, C, B, GemmPlan{1, (B + FK - 1) / FK * FK}, 0,
                       1.f / (float)B);
     return FOSI_OK;
