@@ -53,7 +53,16 @@ typedef struct fosi_hvp fosi_hvp;   /* a curvature operator v -> H v bound to a 
 /* ---- context ---------------------------------------------------------- */
 
 /* Creates a context on GPU `device`.  `hip_stream` is a hipStream_t passed as
- * a pointer (NULL = the default stream); the caller keeps the stream alive. */
+ * a pointer (NULL = the default stream); the caller keeps the stream alive.
+ * Launch shapes are fixed at creation; for experiments they can be overridden through environment variables
+ * read here (values outside a knob's range fall back to the default):
+ *   FOSI_DOT_BLOCKS   resident workgroups targeted by the transposed product (default 2 per compute unit)
+ *   FOSI_DOT_JB       columns per wave in that kernel: 8, 16, 32 (default 0: 8 up to 4 M rows, else 16)
+ *   FOSI_COMB_ROWS / FOSI_COMB_COLS / FOSI_COMB_BLOCKS   row groups per thread (4), columns loaded together (8)
+ *                     and grid cap (0: none) of the column-combination kernel
+ *   FOSI_STEP_WAVES   resident waves per compute unit aimed at by the update's fused second sweep (12)
+ *   FOSI_EARLY_BETA   1: beta from the Gram-Schmidt coefficients, normalisation inside the subtraction (default)
+ *   FOSI_RITZ_MFMA    1: Ritz vectors of up to 32 columns on the matrix cores (default) */
 fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream);
 /* Bytes of device memory the context holds for itself (partial sums, coefficient vectors, the tridiagonal,
  * flags): a fixed amount, independent of the problem sizes; every other buffer is the caller's.  Operators
