@@ -203,7 +203,8 @@ def bench_blocks(args, fo, torch, np) -> int:
         with torch.cuda.stream(b["stream"]):
             for _ in range(steps):
                 b["Q"].col(0).copy_(w.v1)
-                alpha, beta, m_eff = fo.fosi_lanczos(ctx, b["op"], b["Q"], w.m, reorth_mode=REORTH_MODES[args.reorth])
+                alpha, beta, m_eff = fo.fosi_lanczos(ctx, b["op"], b["Q"], w.m, reorth_mode=REORTH_MODES[args.reorth],
+                                                     graph_mode=int(args.graph))
                 evals, _ = fo.fosi_ritz(ctx, b["Q"], m_eff, alpha, beta, w.k, w.l, b["V"])
                 if w.admm:
                     fo.fosi_admm_begin(ctx, b["sp"].sigma, b["pi"], b["anchor"], b["wa"])
@@ -212,7 +213,31 @@ def bench_blocks(args, fo, torch, np) -> int:
                     fo.fosi_admm_end(ctx, b["sp"].sigma, b["anchor"], b["wa"], b["pi"])
                 b["m_eff"] = m_eff
 
+    def run_single_thread(steps):
+        # one host thread: start every block's Lanczos run (nothing waits for the GPU), then collect them in turn
+        for _ in range(steps):
+            for b in blocks:
+                with torch.cuda.stream(b["stream"]):
+                    b["Q"].col(0).copy_(b["w"].v1)
+                    fo.fosi_lanczos_begin(b["ctx"], b["op"], b["Q"], b["w"].m, reorth_mode=REORTH_MODES[args.reorth],
+                                          graph_mode=int(args.graph))
+            for b in blocks:
+                w, ctx = b["w"], b["ctx"]
+                with torch.cuda.stream(b["stream"]):
+                    alpha, beta, m_eff = fo.fosi_lanczos_end(ctx, w.m)
+                    evals, _ = fo.fosi_ritz(ctx, b["Q"], m_eff, alpha, beta, w.k, w.l, b["V"])
+                    if w.admm:
+                        fo.fosi_admm_begin(ctx, b["sp"].sigma, b["pi"], b["anchor"], b["wa"])
+                    fo.fosi_step(ctx, b["V"], w.k + w.l, evals, b["g"], b["pi"], b["mom"], b["wa"], b["sp"])
+                    if w.admm:
+                        fo.fosi_admm_end(ctx, b["sp"].sigma, b["anchor"], b["wa"], b["pi"])
+                    b["m_eff"] = m_eff
+
     def run_all(steps):
+        if args.block_driver == "begin_end":
+            run_single_thread(steps)
+            torch.cuda.synchronize()
+            return
         th = [threading.Thread(target=run, args=(b, steps)) for b in blocks]
         for t in th:
             t.start()
@@ -238,7 +263,7 @@ def bench_blocks(args, fo, torch, np) -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"cfg{args.config} x {K} blocks on {K} streams: planted spectrum n={w.n}, r={w.r}, "
                                f"Lanczos m={w.m} with '{args.reorth}' Gram-Schmidt, k={w.k}, l={w.l}, one update each",
-                   "blocks": K, "ms_per_block_step": round(ms_per_step / K, 3),
+                   "blocks": K, "driver": args.block_driver, "graph": bool(args.graph), "ms_per_block_step": round(ms_per_step / K, 3),
                    "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4)},
         "roofline": None}))
     for b in blocks:
@@ -262,6 +287,11 @@ def main() -> int:
                     help="also report max|Q^T Q - I| of the last Lanczos basis (library float64 matmuls, untimed)")
     ap.add_argument("--blocks", type=int, default=1,
                     help="run this many independent copies of a planted workload at once, one stream each (aggregate rate)")
+    ap.add_argument("--block-driver", choices=["threads", "begin_end"], default="threads",
+                    help="with --blocks: one host thread per block (blocking calls), or one thread that starts every "
+                         "block's Lanczos run with fosi_lanczos_begin and collects them with fosi_lanczos_end")
+    ap.add_argument("--graph", action="store_true",
+                    help="with --blocks: replay each block's Lanczos run from a captured HIP graph (library option graph_mode)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=1_600_000)
     ap.add_argument("--pmc-probe", action="store_true",

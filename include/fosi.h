@@ -153,6 +153,17 @@ fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q
                          double* alpha_host, double* beta_host, int32_t* m_eff,
                          const fosi_lanczos_opts* opts);
 
+/* The same run in two halves, for callers that drive several contexts (parameter blocks on streams of their own)
+ * from one host thread: fosi_lanczos_begin checks the arguments and enqueues the whole run without waiting for the
+ * GPU; fosi_lanczos_end waits for it and delivers alpha, beta (m doubles each, m as passed to begin) and m_eff.
+ * Between the two, other contexts may be used freely; on this context only fosi_lanczos_end (or fosi_ctx_destroy) may
+ * follow.  The start vector, Q_dev and the operator must stay untouched until fosi_lanczos_end returns.
+ * fosi_lanczos is begin followed by end.  Errors: a second begin while a run is pending, or an end without one, is
+ * FOSI_ERR_INVALID_ARG; a begin that fails leaves nothing pending. */
+fosi_status fosi_lanczos_begin(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q_dev, int64_t ldq,
+                               const fosi_lanczos_opts* opts);
+fosi_status fosi_lanczos_end(fosi_ctx* ctx, double* alpha_host, double* beta_host, int32_t* m_eff);
+
 /* Number of graph captures and graph replays fosi_lanczos has done on this context so far
  * (either pointer may be NULL). */
 fosi_status fosi_graph_stats(fosi_ctx* ctx, int64_t* captures, int64_t* replays);

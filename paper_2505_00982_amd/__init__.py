@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     ColMajor,
     StepParams,
     fosi_lanczos,
+    fosi_lanczos_begin,
+    fosi_lanczos_end,
     fosi_lanczos_row_sharded,
     fosi_lanczos_steps,
     REORTH_SINGLE,

@@ -26,7 +26,7 @@ PROF = {"hvp_project": 0, "hvp_expand": 1, "reorth_dot": 2, "reorth_sub": 3, "no
 EXPORTS = [
     "fosi_ctx_create", "fosi_ctx_destroy", "fosi_ctx_synchronize", "fosi_last_error", "fosi_status_string",
     "hvp_planted_create", "hvp_diag_create", "hvp_softmax_ggn_create", "hvp_softmax_ggn_bf16_create", "hvp_callback_create", "hvp_apply",
-    "hvp_destroy", "fosi_workspace_bytes", "fosi_lanczos", "fosi_graph_stats", "fosi_lanczos_row_sharded", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_step_adamw", "fosi_admm_begin",
+    "hvp_destroy", "fosi_workspace_bytes", "fosi_lanczos", "fosi_lanczos_begin", "fosi_lanczos_end", "fosi_graph_stats", "fosi_lanczos_row_sharded", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_step_adamw", "fosi_admm_begin",
     "fosi_admm_end", "fosi_profile_enable", "fosi_profile_reset", "fosi_profile_read",
 ]
 
@@ -83,6 +83,8 @@ def load_library() -> C.CDLL:
     lib.hvp_apply.argtypes = [vp, vp, vp]
     lib.hvp_destroy.argtypes = [vp]
     lib.fosi_lanczos.argtypes = [vp, vp, i64, C.c_int, vp, i64, dp, dp, C.POINTER(i32), C.POINTER(_LanczosOpts)]
+    lib.fosi_lanczos_begin.argtypes = [vp, vp, i64, C.c_int, vp, i64, C.POINTER(_LanczosOpts)]
+    lib.fosi_lanczos_end.argtypes = [vp, dp, dp, C.POINTER(i32)]
     lib.fosi_lanczos_row_sharded.argtypes = [vp, vp, i64, C.c_int, C.c_int, vp, i64, dp, dp, C.POINTER(i32),
                                              C.POINTER(_LanczosOpts)]
     lib.fosi_workspace_bytes.argtypes = [vp]
@@ -288,6 +290,22 @@ def fosi_lanczos(ctx: Context, op: Hvp, Q: ColMajor, m: int, reorth_mode: int = 
     opts = _LanczosOpts(reorth_mode, breakdown_tol, graph_mode)
     ctx.check(ctx.lib.fosi_lanczos(ctx.handle, op.handle, Q.n, m, Q.ptr, Q.ld, _dptr(alpha), _dptr(beta),
                                    C.byref(m_eff), C.byref(opts)))
+    return alpha, beta, int(m_eff.value)
+
+
+def fosi_lanczos_begin(ctx: Context, op: Hvp, Q: ColMajor, m: int, reorth_mode: int = 0, breakdown_tol: float = 1e-6,
+                       graph_mode: int = 0) -> int:
+    """Enqueues the whole run on the context's stream without waiting for the GPU; returns m for fosi_lanczos_end."""
+    opts = _LanczosOpts(reorth_mode, breakdown_tol, graph_mode)
+    ctx.check(ctx.lib.fosi_lanczos_begin(ctx.handle, op.handle, Q.n, m, Q.ptr, Q.ld, C.byref(opts)))
+    return m
+
+
+def fosi_lanczos_end(ctx: Context, m: int) -> Tuple[np.ndarray, np.ndarray, int]:
+    """Waits for the run started by fosi_lanczos_begin(..., m); returns (alpha, beta, m_eff)."""
+    alpha, beta = np.zeros(m), np.zeros(m)
+    m_eff = C.c_int32(0)
+    ctx.check(ctx.lib.fosi_lanczos_end(ctx.handle, _dptr(alpha), _dptr(beta), C.byref(m_eff)))
     return alpha, beta, int(m_eff.value)
 
 

@@ -489,15 +489,15 @@ static bool lanczos_by_graph(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, floa
     return true;
 }
 
-fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q_dev, int64_t ldq,
-                         double* alpha_host, double* beta_host, int32_t* m_eff, const fosi_lanczos_opts* opts) {
+fosi_status fosi_lanczos_begin(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q_dev, int64_t ldq,
+                               const fosi_lanczos_opts* opts) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
-    if (op == nullptr || alpha_host == nullptr || beta_host == nullptr || m_eff == nullptr)
-        return fail(ctx, FOSI_ERR_INVALID_ARG, "null argument");
+    if (op == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "null argument");
     if (op->ctx != ctx) return fail(ctx, FOSI_ERR_INVALID_ARG, "operator belongs to another context");
     if (n < 1 || m < 1) return fail(ctx, FOSI_ERR_INVALID_ARG, "n and m must be positive");
     if (op->n != n) return fail(ctx, FOSI_ERR_INVALID_ARG, "operator size differs from n");
     if (m + 1 > kMaxCols) return fail(ctx, FOSI_ERR_LIMIT, "m + 1 exceeds FOSI_MAX_COLS");
+    if (ctx->pending_m != 0) return fail(ctx, FOSI_ERR_INVALID_ARG, "a Lanczos run is already pending on this context");
     if (fosi_status s = check_matrix(ctx, "Q_dev", Q_dev, n, ldq, m + 1)) return s;
     int mode = FOSI_REORTH_LOCAL_FULL, graph_mode = FOSI_GRAPH_OFF;
     double tol = 1e-6;
@@ -510,7 +510,6 @@ fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q
         return fail(ctx, FOSI_ERR_INVALID_ARG, "unknown reorth_mode");
     if (graph_mode != FOSI_GRAPH_OFF && graph_mode != FOSI_GRAPH_ON)
         return fail(ctx, FOSI_ERR_INVALID_ARG, "unknown graph_mode");
-    *m_eff = 0;
 
     int* flags = ctx->s.flags;
     // (cleared outside the graph: memset nodes are kept out of captured work)
@@ -526,7 +525,19 @@ fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q
     }
     if (!done)
         if (fosi_status s = enqueue_lanczos(ctx, op, n, m, Q_dev, ldq, mode, tol)) return s;
+    ctx->pending_m = m;
+    return FOSI_OK;
+}
 
+fosi_status fosi_lanczos_end(fosi_ctx* ctx, double* alpha_host, double* beta_host, int32_t* m_eff) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (alpha_host == nullptr || beta_host == nullptr || m_eff == nullptr)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "null argument");
+    if (ctx->pending_m == 0) return fail(ctx, FOSI_ERR_INVALID_ARG, "no Lanczos run is pending on this context");
+    const int m = ctx->pending_m;
+    ctx->pending_m = 0;
+    *m_eff = 0;
+    int* flags = ctx->s.flags;
     int hflags[2] = {0, 0};
     if (fosi_status s = check_hip(ctx, hipMemcpyAsync(alpha_host, ctx->s.alpha, sizeof(double) * m, hipMemcpyDeviceToHost,
                                                       ctx->stream), "copy alpha")) return s;
@@ -540,6 +551,16 @@ fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q
     *m_eff = hflags[1];
     if (hflags[0] == 2) return fail(ctx, FOSI_ERR_NONFINITE, "non-finite value in the Lanczos recurrence");
     return FOSI_OK;
+}
+
+fosi_status fosi_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q_dev, int64_t ldq,
+                         double* alpha_host, double* beta_host, int32_t* m_eff, const fosi_lanczos_opts* opts) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (alpha_host == nullptr || beta_host == nullptr || m_eff == nullptr)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "null argument");
+    *m_eff = 0;
+    if (fosi_status s = fosi_lanczos_begin(ctx, op, n, m, Q_dev, ldq, opts)) return s;
+    return fosi_lanczos_end(ctx, alpha_host, beta_host, m_eff);
 }
 
 /* Number of graph captures and replays of this context so far (for tests and diagnostics). */

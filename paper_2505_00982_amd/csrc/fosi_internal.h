@@ -87,6 +87,7 @@ struct fosi_ctx {
     bool graph_unavailable = false;     // the stream refused capture once: do not try again
     int64_t graph_replays = 0, graph_captures = 0;
     int sm_count = 256;
+    int pending_m = 0;                  // steps of the Lanczos run enqueued by fosi_lanczos_begin and not yet collected
 };
 
 struct fosi_hvp {

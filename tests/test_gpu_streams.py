@@ -1,5 +1,6 @@
-"""Independent parameter blocks on separate streams: one context per stream, driven from host threads.  The
-contexts share nothing (each owns its scratch), so concurrent runs must give exactly the numbers of a run alone."""
+"""Independent parameter blocks on separate streams: one context per stream, driven from host threads or, through
+the begin / end halves of the Lanczos call, from one thread.  The contexts share nothing (each owns its scratch), so
+concurrent runs must give exactly the numbers of a run alone."""
 import threading
 
 import numpy as np
@@ -11,8 +12,7 @@ import workloads as wl
 pytestmark = pytest.mark.gpu
 
 
-def test_concurrent_contexts_reproduce_sequential_results():
-    import paper_2505_00982_amd as fo
+def make_blocks(fo):
     sizes = [(30011, 16), (65536, 20), (12345, 12), (50000, 18)]
     blocks = []
     for i, (n, m) in enumerate(sizes):
@@ -29,6 +29,12 @@ def test_concurrent_contexts_reproduce_sequential_results():
             v1 = torch.from_numpy(w.v1).cuda()
         stream.synchronize()
         blocks.append(dict(stream=stream, ctx=ctx, op=op, Q=Q, V=V, v1=v1, m=m, n=n, keep=(U, lam)))
+    return blocks
+
+
+def test_concurrent_contexts_reproduce_sequential_results():
+    import paper_2505_00982_amd as fo
+    blocks = make_blocks(fo)
 
     def curvature(b, out):
         with torch.cuda.stream(b["stream"]):
@@ -57,6 +63,38 @@ def test_concurrent_contexts_reproduce_sequential_results():
         assert g[2] == ref[2]
         assert np.array_equal(g[0], ref[0]) and np.array_equal(g[1], ref[1]) and np.array_equal(g[3], ref[3])
         assert torch.equal(g[4], ref[4])
+    for b in blocks:
+        b["op"].close()
+        b["ctx"].close()
+
+
+def test_begin_end_halves_from_one_thread():
+    """fosi_lanczos_begin on every block first (nothing waits for the GPU), then fosi_lanczos_end on each: same bits
+    as the blocking call, and the misuse cases are rejected."""
+    import paper_2505_00982_amd as fo
+    blocks = make_blocks(fo)
+    ref = []
+    for b in blocks:
+        with torch.cuda.stream(b["stream"]):
+            b["Q"].col(0).copy_(b["v1"])
+            a, be, me = fo.fosi_lanczos(b["ctx"], b["op"], b["Q"], b["m"])
+            ref.append((a, be, me, b["Q"].buf.clone()))
+    for rep in range(2):
+        for b in blocks:
+            with torch.cuda.stream(b["stream"]):
+                b["Q"].col(0).copy_(b["v1"])
+                fo.fosi_lanczos_begin(b["ctx"], b["op"], b["Q"], b["m"])
+        with pytest.raises(fo.FosiError) as e:                       # a second run on a context that has one pending
+            fo.fosi_lanczos_begin(blocks[0]["ctx"], blocks[0]["op"], blocks[0]["Q"], blocks[0]["m"])
+        assert e.value.status == -1
+        for b, r in zip(reversed(blocks), reversed(ref)):            # collected in another order than started
+            a, be, me = fo.fosi_lanczos_end(b["ctx"], b["m"])
+            assert me == r[2] and np.array_equal(a, r[0]) and np.array_equal(be, r[1])
+            b["ctx"].synchronize()
+            assert torch.equal(b["Q"].buf, r[3])
+    with pytest.raises(fo.FosiError) as e:                           # nothing pending
+        fo.fosi_lanczos_end(blocks[0]["ctx"], blocks[0]["m"])
+    assert e.value.status == -1
     for b in blocks:
         b["op"].close()
         b["ctx"].close()
