@@ -231,8 +231,7 @@ __global__ __launch_bounds__(kThreads) void k_dot_columns(
     }
 }
 
-// What the last workgroup of the second stage does once every column sum is in memory (saves a launch
-// and the ~6 us between two dependent launches).
+// What the last workgroup of the second stage does once every column sum is in memory (saves a launch).
 struct ReduceTail {
     int kind;          // 0 none; 1 scalars of the local Gram-Schmidt pass; 2 end of a Lanczos step
     int step;          // kind 2: Lanczos step index
