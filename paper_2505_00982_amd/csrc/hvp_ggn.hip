@@ -160,7 +160,10 @@ __device__ __forceinline__ float4 mask4(const float4 v, const unsigned int keep)
     return __builtin_bit_cast(float4, x);
 }
 
-template <bool A_KM>
+// FULLK: K and the split length are multiples of FK, so every K-step of a split is whole: the addresses then
+// advance by a constant per K-step and the bounds masks do not depend on k (computed once); otherwise every load
+// clamps its k index and every LDS write masks it, ~40 more vector instructions per K-step.
+template <bool A_KM, bool FULLK>
 __global__ __launch_bounds__(256) void k_gemm_f32_aligned(const float* __restrict__ A, int lda,
                                                           const float* __restrict__ Bm, int ldb,
                                                           float* __restrict__ Cout, int ldc, int M, int N, int K,
@@ -174,6 +177,7 @@ __global__ __launch_bounds__(256) void k_gemm_f32_aligned(const float* __restric
     const int m0 = tm * TM, n0 = tn * TN;
     const int kbeg = tz * klen;
     const int kend = min(K, kbeg + klen);
+    const int nk = (kend - kbeg + FK - 1) / FK;
 
     // k-major tiles (B always, A when it is stored K x M): rows kr and kr + 16, four columns from c4
     const int kr = tid >> 4, c4 = (tid & 15) * 4;
@@ -181,34 +185,56 @@ __global__ __launch_bounds__(256) void k_gemm_f32_aligned(const float* __restric
     const int am = tid >> 3, ak4 = (tid & 7) * 4;
     float4 ra[FPF][2], rb[FPF][2];
 
-    auto load = [&](int k0, float4* qa, float4* qb) {
+    // k-independent parts: clamped column / row offsets and the masks of the m and n bounds
+    const int nb = n0 + c4, ma = m0 + c4;
+    const unsigned int keep_n = nb < N ? 0xffffffffu : 0u;
+    const unsigned int keep_mk = ma < M ? 0xffffffffu : 0u;                       // A stored K x M
+    const unsigned int keep_m0 = m0 + am < M ? 0xffffffffu : 0u, keep_m1 = m0 + am + 32 < M ? 0xffffffffu : 0u;
+    const float* pB = Bm + (nb < N ? nb : 0);
+    const float* pAk = A + (ma < M ? ma : 0);                                      // A stored K x M: + k * lda
+    const float* pAm0 = A + (int64_t)(m0 + am < M ? m0 + am : 0) * lda;            // A stored M x K: + k
+    const float* pAm1 = A + (int64_t)(m0 + am + 32 < M ? m0 + am + 32 : 0) * lda;
+
+    auto load = [&](int kt, float4* qa, float4* qb) {
+        if (FULLK) {
+            const int k0 = kbeg + min(kt, nk - 1) * FK;      // past the end: the last K-step again (never stored)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int k = k0 + kr + 16 * j;
-            const int kc = k < kend ? k : 0;
-            const int nb = n0 + c4;
-            qb[j] = *reinterpret_cast<const float4*>(Bm + (int64_t)kc * ldb + (nb < N ? nb : 0));
-            if (A_KM) {
-                const int ma = m0 + c4;
-                qa[j] = *reinterpret_cast<const float4*>(A + (int64_t)kc * lda + (ma < M ? ma : 0));
-            } else {
-                const int m = m0 + am + 32 * j, ka = k0 + ak4;
-                qa[j] = *reinterpret_cast<const float4*>(A + (int64_t)(m < M ? m : 0) * lda + (ka < kend ? ka : 0));
+            for (int j = 0; j < 2; ++j) {
+                const int k = k0 + kr + 16 * j;
+                qb[j] = *reinterpret_cast<const float4*>(pB + (int64_t)k * ldb);
+                if (A_KM) qa[j] = *reinterpret_cast<const float4*>(pAk + (int64_t)k * lda);
+                else qa[j] = *reinterpret_cast<const float4*>((j == 0 ? pAm0 : pAm1) + k0 + ak4);
+            }
+        } else {
+            const int k0 = kbeg + kt * FK;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int k = k0 + kr + 16 * j;
+                const int kc = k < kend ? k : 0;
+                qb[j] = *reinterpret_cast<const float4*>(pB + (int64_t)kc * ldb);
+                if (A_KM) {
+                    qa[j] = *reinterpret_cast<const float4*>(pAk + (int64_t)kc * lda);
+                } else {
+                    const int ka = k0 + ak4;
+                    qa[j] = *reinterpret_cast<const float4*>((j == 0 ? pAm0 : pAm1) + (ka < kend ? ka : 0));
+                }
             }
         }
     };
-    auto store = [&](int k0, int buf, const float4* qa, const float4* qb) {
+    auto store = [&](int kt, int buf, const float4* qa, const float4* qb) {
+        const int k0 = kbeg + kt * FK;
+        // (FULLK: a K-step past the range, reached only through the rounded-up trip count, must store zeros too)
+        const unsigned int in_range = kt < nk ? 0xffffffffu : 0u;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int k = k0 + kr + 16 * j;
-            const unsigned int keep_b = (k < kend && n0 + c4 < N) ? 0xffffffffu : 0u;
-            *reinterpret_cast<float4*>(&Bs[buf][kr + 16 * j][c4]) = mask4(qb[j], keep_b);
+            const unsigned int keep_k = FULLK ? in_range : (k < kend ? 0xffffffffu : 0u);
+            *reinterpret_cast<float4*>(&Bs[buf][kr + 16 * j][c4]) = mask4(qb[j], keep_k & keep_n);
             if (A_KM) {
-                const unsigned int keep_a = (k < kend && m0 + c4 < M) ? 0xffffffffu : 0u;
-                *reinterpret_cast<float4*>(&As[buf][kr + 16 * j][c4]) = mask4(qa[j], keep_a);
+                *reinterpret_cast<float4*>(&As[buf][kr + 16 * j][c4]) = mask4(qa[j], keep_k & keep_mk);
             } else {
-                const unsigned int keep_a = (m0 + am + 32 * j < M && k0 + ak4 < kend) ? 0xffffffffu : 0u;
-                const float4 v = mask4(qa[j], keep_a);
+                const unsigned int keep_ka = FULLK ? in_range : (k0 + ak4 < kend ? 0xffffffffu : 0u);
+                const float4 v = mask4(qa[j], keep_ka & (j == 0 ? keep_m0 : keep_m1));
                 As[buf][ak4 + 0][am + 32 * j] = v.x;
                 As[buf][ak4 + 1][am + 32 * j] = v.y;
                 As[buf][ak4 + 2][am + 32 * j] = v.z;
@@ -222,33 +248,34 @@ __global__ __launch_bounds__(256) void k_gemm_f32_aligned(const float* __restric
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
 
     const int half = lane >> 5, l32 = lane & 31;
-    const int nk = (kend - kbeg + FK - 1) / FK;
-    // (K-steps past the end of the range load clamped addresses and are never stored)
+    // (K-steps past the end of the range load clamped addresses and store zeros)
     // the fences keep the issue order of the register sets (oldest first), so that waiting for one set
     // leaves the younger one in flight, and keep the refill in front of the matrix instructions
 #pragma unroll
     for (int u = 0; u < FPF; ++u) {
-        load(kbeg + u * FK, ra[u], rb[u]);
+        load(u, ra[u], rb[u]);
         __builtin_amdgcn_sched_barrier(0);
     }
-    for (int kt0 = 0; kt0 < nk; kt0 += FPF) {
+    // The trip count is rounded up to a multiple of FPF (a K-step past the range stores zeros: its masks are all
+    // off), so that the unrolled body has no branch: with one, the compiler merges the paths' outstanding-load
+    // counts and ends up waiting for the younger register set as well, which halves the lookahead.
+    const int nk_even = (nk + FPF - 1) / FPF * FPF;
+    for (int kt0 = 0; kt0 < nk_even; kt0 += FPF) {
 #pragma unroll
         for (int u = 0; u < FPF; ++u) {
             const int kt = kt0 + u;
-            if (kt < nk) {                                          // uniform
-                const int buf = u & 1;                              // FPF is even: kt and u have the same parity
-                // this buffer was last read two K-steps ago, and every wave has passed the barrier of the
-                // K-step in between since
-                store(kbeg + kt * FK, buf, ra[u], rb[u]);
-                lds_barrier();
-                load(kbeg + (kt + FPF) * FK, ra[u], rb[u]);         // refill the registers just consumed
-                __builtin_amdgcn_sched_barrier(0);
+            const int buf = u & 1;                                  // FPF is even: kt and u have the same parity
+            // this buffer was last read two K-steps ago, and every wave has passed the barrier of the
+            // K-step in between since
+            store(kt, buf, ra[u], rb[u]);
+            lds_barrier();
+            load(kt + FPF, ra[u], rb[u]);                           // refill the registers just consumed
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int kk = 0; kk < FK; kk += 2) {
-                    const float a = As[buf][kk + half][wm + l32];
-                    const float b = Bs[buf][kk + half][wn + l32];
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
-                }
+            for (int kk = 0; kk < FK; kk += 2) {
+                const float a = As[buf][kk + half][wm + l32];
+                const float b = Bs[buf][kk + half][wn + l32];
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
             }
         }
     }
@@ -617,9 +644,12 @@ void launch_gemm(fosi_ctx* ctx, const float* A, int lda, const float* Bm, int ld
                      ((reinterpret_cast<uintptr_t>(Bm) & 15) == 0);
     // whole 16-byte groups only: N (columns of B) and the contiguous extent of A (M if stored K x M, else K)
     const bool aligned = vec && N % 4 == 0 && (A_KM ? M : K) % 4 == 0 && plan.klen % FK == 0;
-    if (aligned)
-        hipLaunchKernelGGL((k_gemm_f32_aligned<A_KM>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N,
-                           K, plan.klen, plan.nsplit, cstride, scale);
+    if (aligned && K % FK == 0)
+        hipLaunchKernelGGL((k_gemm_f32_aligned<A_KM, true>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M,
+                           N, K, plan.klen, plan.nsplit, cstride, scale);
+    else if (aligned)
+        hipLaunchKernelGGL((k_gemm_f32_aligned<A_KM, false>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M,
+                           N, K, plan.klen, plan.nsplit, cstride, scale);
     else if (vec)
         hipLaunchKernelGGL((k_gemm_f32<A_KM, true>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N, K,
                            plan.klen, plan.nsplit, cstride, scale);

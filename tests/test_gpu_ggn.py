@@ -37,9 +37,11 @@ def dev(a):
 
 # (70, 200, 132), (130, 260, 100), (4, 4, 4): every extent a multiple of 4, so both products take the kernel for
 # aligned shapes with ragged tiles in M, N and K; the odd shapes take the generic kernel
-# C = 1500, 2500: the softmax-Jacobian row kept in 8 registers per thread / too long for registers (two-pass kernel)
+# C = 1500, 2500: the softmax-Jacobian row kept in 8 registers per thread / too long for registers (two-pass kernel);
+# (96, 64, 36), (32, 32, 4): both contraction lengths multiples of 32 (whole K-steps: the variant with constant address
+# increments), ragged in M and N
 @pytest.mark.parametrize("B,d,C", [(16, 8, 5), (1, 1, 1), (70, 200, 132), (130, 260, 100), (4, 4, 4), (100, 301, 130),
-                                   (65, 17, 64), (9, 12, 1500), (9, 12, 2500), (512, 2048, 1000)])
+                                   (65, 17, 64), (9, 12, 1500), (9, 12, 2500), (96, 64, 36), (32, 32, 4), (512, 2048, 1000)])
 def test_ggn_operator_matches_oracle(fo, ctx, B, d, C):
     g = wl.ggn_workload(B=B, d=d, C=C)
     op = ctx.hvp_softmax_ggn(dev(g.X), dev(g.W))
