@@ -42,11 +42,16 @@ __device__ __forceinline__ void store_stream4(float* p, const float4 v) {
 // (the Gram-Schmidt subtraction before the operator's project sweep): with the plain streaming store that next
 // sweep runs ~1.5 % slower while the L2s still write back (1.949 -> 1.921 ms on the 128-column project sweep of the
 // n = 25.6 M workload; for the expand sweep's own output the two policies measure the same).  No builtin
-// selects this combination of cache bits for a 16-byte store, hence the one line of assembly.
+// selects this combination of cache bits for a 16-byte store, hence the assembly.  The s_nop belongs to it: on
+// gfx940-class hardware a vector instruction must not overwrite the data registers of a store of more than 8 bytes
+// within two wait states of it; the compiler pads its own stores but cannot see into an asm statement, and in the
+// kernels that go on computing with the stored value (sum of squares, local dot products) it did schedule such a
+// write right behind the store -- corrupted vector elements under memory pressure, non-finite recurrences at
+// n = 25.6 M -- until the padding was added here.
 __device__ __forceinline__ void store_through4(float* p, const float4 v) {
     f32x4 t;
     t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
-    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" : : "v"(p), "v"(t) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(t) : "memory");
 }
 
 __device__ __forceinline__ double wave_sum(double v) {

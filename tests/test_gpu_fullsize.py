@@ -212,6 +212,39 @@ def test_workload4_full_size(fo, ctx):
     _full_size_planted(fo, ctx, 4)
 
 
+@pytest.mark.parametrize("mode_name", ["single", "twice"])
+def test_workload4_other_schemes_full_size(fo, ctx, mode_name):
+    """The printed single pass and the twice-repeated pass at n = 25.6 M (40 steps): these schemes run the kernel
+    variants that keep computing with a stored value (sum of squares of the subtraction's output), at a size where
+    the memory system is under full load.  The tridiagonal must match the independent fp64 route."""
+    from workloads.device import planted_workload_device
+    w = planted_workload_device(4)
+    n, r, m = w.n, w.r, 40
+    U = fo.ColMajor(n, r, w.ld, buf=w.U)
+    op = ctx.hvp_planted(U, w.lam, w.shift)
+    Q = fo.ColMajor(n, m + 1, w.ld)
+    Q.col(0).copy_(w.v1)
+    mode = {"single": fo.REORTH_SINGLE, "twice": fo.REORTH_TWICE}[mode_name]
+    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, m, reorth_mode=mode)
+    ctx.synchronize()
+    assert m_eff == m and np.all(np.isfinite(alpha)) and np.all(np.isfinite(beta))
+    lam = w.lam.cpu().numpy().astype(np.float64)
+    scale = np.abs(lam).max()
+    G = _gram_f64(w.U.view(r, w.ld), n, w.v1)
+    a_ref, b_ref = reduced_tridiagonal_from_gram(G, lam, w.shift)
+    assert np.max(np.abs(alpha[:m] - a_ref[:m])) < 1e-5 * scale
+    assert np.max(np.abs(beta[: m - 1] - b_ref[: m - 1])) < 1e-5 * scale
+    # orthonormal basis (the single pass drifts, cf. the scheme study; two passes stay at rounding level)
+    Qm = Q.buf[: m * w.ld].view(m, w.ld)
+    gram = torch.zeros(m, m, dtype=torch.float64, device="cuda")
+    for lo in range(0, n, 1 << 20):
+        blk = Qm[:, lo:min(n, lo + (1 << 20))].double()
+        gram += blk @ blk.T
+    dev_ = float((gram - torch.eye(m, dtype=torch.float64, device="cuda")).abs().max())
+    assert dev_ < (1e-5 if mode_name == "single" else 1e-7), dev_
+    op.close()
+
+
 def test_workload5_full_size(fo, ctx):
     """n = 125 M, r = 128, m = 100, k = 20, l = 20: the largest block (138 GB of the 288 GB HBM)."""
     torch.cuda.empty_cache()
