@@ -212,6 +212,49 @@ def test_workload4_full_size(fo, ctx):
     _full_size_planted(fo, ctx, 4)
 
 
+def test_update_rules_at_four_million_rows(fo, ctx):
+    """Both update rules (heavy ball and AdamW as base optimiser) with a dual variable at n = 4 M + 3 rows and 30
+    columns, two consecutive steps each, against the complete oracle on the host: large enough that every sweep runs
+    with the memory system under load and many workgroups in flight, small enough for the fp64 oracle (1 GB basis)."""
+    n, r = (1 << 22) + 3, 30
+    rng = np.random.default_rng(41)
+    ld = wl.padded_ld(n)
+    # an orthonormal basis without a 4 M x 30 QR: orthonormalise Gaussian columns by two rounds of Cholesky-QR in fp64
+    A = rng.standard_normal((n, r))
+    for _ in range(2):
+        A = A @ np.linalg.inv(np.linalg.cholesky(A.T @ A).T)
+    Vh = A.astype(np.float32)
+    ev = np.concatenate([rng.uniform(1, 50, 20), -rng.uniform(0.5, 5, 10)])
+    w0, g, b0 = (rng.standard_normal(n).astype(np.float32) for _ in range(3))
+    pi = (0.1 * rng.standard_normal(n)).astype(np.float32)
+    V = fo.ColMajor.from_numpy(Vh, ld)
+    f32 = lambda x: float(np.float32(x))
+    # heavy ball
+    wd_, md_ = dev(w0), dev(b0)
+    sp = fo.StepParams(0.1, 0.01, 0.9, 5e-4, 0)
+    for _ in range(2):
+        fo.fosi_step(ctx, V, r, ev, dev(g), dev(pi), md_, wd_, sp)
+    ctx.synchronize()
+    w_ref, b_ref = w0, b0
+    for _ in range(2):
+        w_ref, b_ref = oracle.fosi_step(w_ref, g, Vh, ev, b_ref, f32(0.1), f32(0.01), f32(0.9), f32(5e-4), pi=pi)
+    assert rel_l2(wd_.cpu().numpy(), w_ref) <= 1e-5
+    assert rel_l2(md_.cpu().numpy(), b_ref) <= 1e-5
+    # AdamW
+    ap = fo.AdamwParams(alpha=0.1, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.05, sigma=5e-4, curv_mode=0)
+    wd_, m1, v1, work = dev(w0), torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda")
+    for t in (1, 2):
+        fo.fosi_step_adamw(ctx, V, r, ev, dev(g), dev(pi), m1, v1, work, wd_, t, ap)
+    ctx.synchronize()
+    w_ref, m_ref, v_ref = w0, np.zeros(n), np.zeros(n)
+    for t in (1, 2):
+        w_ref, m_ref, v_ref = oracle.fosi_step_adamw(w_ref, g, Vh, ev, m_ref, v_ref, t, f32(0.1), f32(1e-3), f32(0.9),
+                                                     f32(0.999), f32(1e-8), f32(0.05), sigma=f32(5e-4), pi=pi)
+    assert rel_l2(wd_.cpu().numpy(), w_ref) <= 1e-5
+    assert rel_l2(m1.cpu().numpy(), m_ref) <= 1e-5
+    assert rel_l2(v1.cpu().numpy(), v_ref) <= 1e-5
+
+
 @pytest.mark.parametrize("mode_name", ["single", "twice"])
 def test_workload4_other_schemes_full_size(fo, ctx, mode_name):
     """The printed single pass and the twice-repeated pass at n = 25.6 M (40 steps): these schemes run the kernel
