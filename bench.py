@@ -26,17 +26,19 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
-REORTH_MODES = {"single": 1, "twice": 2, "local_full": 3}
+REORTH_MODES = {"single": 1, "twice": 2, "local_full": 3, "selective": 4}
 
 
-def algorithmic_vectors(m_eff: int, r: int, r_v: int, reorth: str, with_pi: bool) -> dict:
+def algorithmic_vectors(m_eff: int, r: int, r_v: int, reorth: str, with_pi: bool, second_passes: int = 0) -> dict:
     """Vectors (4n bytes each) the variant that is run must move, per phase.
     Per Lanczos step with c = i+1 live columns: operator (r+1) + (r+2); a
     Gram-Schmidt pass against all columns (c+1) + (c+2) -- "single": once,
     "twice": two times; "local_full": the local pass rides on the operator's
     expand sweep (+1 vector, q_{i-1}, when i > 0), the full pass reads h, q_i and
     q_{i-1} to form its vector (c + 2 + [i > 0]) and one subtraction follows
-    (c+2) that also normalises (the other schemes: a normalisation sweep, 2).  Start vector 3.  Ritz vectors m_eff + r_v.  Update:
+    (c+2) that also normalises (the other schemes: a normalisation sweep, 2); "selective": a pass whose
+    subtraction normalises, and in `second_passes` of the steps a second one (which steps is decided on the
+    device: priced at the average pass).  Start vector 3.  Ritz vectors m_eff + r_v.  Update:
     3 sweeps of V-hat plus 7 vector accesses (+2 with a dual variable)."""
     hvp = m_eff * (2 * r + 3)
     if reorth == "local_full":
@@ -46,10 +48,12 @@ def algorithmic_vectors(m_eff: int, r: int, r_v: int, reorth: str, with_pi: bool
         full = 2 * c + 3
         if reorth == "local_full":
             return full + 1 + (1 if c > 1 else 0)
-        return {"single": full, "twice": 2 * full}[reorth]
+        return {"single": full, "twice": 2 * full, "selective": full}[reorth]
     reorth_name = reorth
     reorth = sum(gs(i + 1) for i in range(m_eff))
-    norm = (0 if reorth_name == "local_full" else 2 * m_eff) + 3   # 'local_full' normalises inside the subtraction
+    if reorth_name == "selective" and m_eff > 0:
+        reorth += round(reorth * second_passes / m_eff)
+    norm = (0 if reorth_name in ("local_full", "selective") else 2 * m_eff) + 3   # those normalise inside the subtraction
     ritz = m_eff + r_v
     step = 3 * r_v + 7 + (2 if with_pi else 0)
     return dict(hvp=hvp, reorth=reorth, normalise=norm, ritz=ritz, step=step,
@@ -118,7 +122,8 @@ def bench_ggn(args, fo, torch, np) -> int:
 
     def one_step():
         Q.col(0).copy_(v1)
-        alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, g.m, reorth_mode=REORTH_MODES[args.reorth])
+        alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, g.m, reorth_mode=REORTH_MODES[args.reorth],
+                                             reorth_eta=args.reorth_eta)
         fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, g.k, 0, V)
         state["m_eff"] = m_eff
 
@@ -204,7 +209,7 @@ def bench_blocks(args, fo, torch, np) -> int:
             for _ in range(steps):
                 b["Q"].col(0).copy_(w.v1)
                 alpha, beta, m_eff = fo.fosi_lanczos(ctx, b["op"], b["Q"], w.m, reorth_mode=REORTH_MODES[args.reorth],
-                                                     graph_mode=int(args.graph))
+                                                     graph_mode=int(args.graph), reorth_eta=args.reorth_eta)
                 evals, _ = fo.fosi_ritz(ctx, b["Q"], m_eff, alpha, beta, w.k, w.l, b["V"])
                 if w.admm:
                     fo.fosi_admm_begin(ctx, b["sp"].sigma, b["pi"], b["anchor"], b["wa"])
@@ -220,7 +225,7 @@ def bench_blocks(args, fo, torch, np) -> int:
                 with torch.cuda.stream(b["stream"]):
                     b["Q"].col(0).copy_(b["w"].v1)
                     fo.fosi_lanczos_begin(b["ctx"], b["op"], b["Q"], b["w"].m, reorth_mode=REORTH_MODES[args.reorth],
-                                          graph_mode=int(args.graph))
+                                          graph_mode=int(args.graph), reorth_eta=args.reorth_eta)
             for b in blocks:
                 w, ctx = b["w"], b["ctx"]
                 with torch.cuda.stream(b["stream"]):
@@ -282,6 +287,8 @@ def main() -> int:
     ap.add_argument("--n", type=int, default=None, help="override the row count (debugging)")
     ap.add_argument("--reorth", choices=sorted(REORTH_MODES), default="local_full",
                     help="Gram-Schmidt scheme of the Lanczos run (library default: local_full)")
+    ap.add_argument("--reorth-eta", type=float, default=0.0,
+                    help="threshold of the second pass of --reorth selective (0: the library's 1/sqrt 2)")
     ap.add_argument("--m", type=int, default=None, help="override the number of Lanczos steps")
     ap.add_argument("--accuracy", action="store_true",
                     help="also report max|Q^T Q - I| of the last Lanczos basis (library float64 matmuls, untimed)")
@@ -337,7 +344,9 @@ def main() -> int:
 
     def one_step():
         Q.col(0).copy_(w.v1)
-        alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, w.m, reorth_mode=REORTH_MODES[args.reorth])
+        alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, w.m, reorth_mode=REORTH_MODES[args.reorth],
+                                             reorth_eta=args.reorth_eta)
+        state.update(second_passes=fo.fosi_lanczos_second_passes(ctx))
         evals, resid = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, w.k, w.l, V)
         if w.admm:
             fo.fosi_admm_begin(ctx, sp.sigma, pi, anchor, wa)
@@ -378,7 +387,7 @@ def main() -> int:
 
     ms_per_step = dt / args.steps * 1e3
     vec_bytes = 4.0 * w.n
-    vecs = algorithmic_vectors(state["m_eff"], w.r, r_v, args.reorth, w.admm)
+    vecs = algorithmic_vectors(state["m_eff"], w.r, r_v, args.reorth, w.admm, state["second_passes"])
     if w.admm:
         vecs["total"] += 8
     step_bytes = vecs["total"] * vec_bytes
@@ -417,6 +426,8 @@ def main() -> int:
                                f"{' with ADMM begin/end' if w.admm else ''}",
                    "accumulation": "f64 products and sums, one rounding per stored fp32 vector",
                    "m_eff": state["m_eff"], "algorithmic_GB_per_step": round(step_bytes / 1e9, 1),
+                   **({"second_passes": state["second_passes"], "reorth_eta": args.reorth_eta or round(2 ** -0.5, 4)}
+                      if args.reorth == "selective" else {}),
                    "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
                    "device": device_name(torch), "hip": getattr(torch.version, "hip", None)},
         "roofline": roofline,

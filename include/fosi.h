@@ -116,6 +116,11 @@ fosi_status hvp_destroy(fosi_hvp* op);
 #define FOSI_REORTH_LOCAL_FULL  3   /* default: a pass against the last two columns (the only ones  */
                                     /* h is not orthogonal to in exact arithmetic), then the        */
                                     /* printed pass against all columns                             */
+#define FOSI_REORTH_SELECTIVE   4   /* the printed pass, and a second one only in the steps where    */
+                                    /* the first left less than reorth_eta * ||H q_i|| (the test of  */
+                                    /* Daniel, Gragg, Kaufman and Stewart): a pass in fp32 storage   */
+                                    /* leaves an error of ~1e-7 ||H q_i||, which only matters        */
+                                    /* against a small remainder                                     */
 typedef struct {
     /* 0 selects the default.  fp32 storage needs a second pass of some kind to keep Q orthonormal:
      * TWICE and LOCAL_FULL reach the same orthogonality (~1e-8), LOCAL_FULL with about half the
@@ -134,6 +139,12 @@ typedef struct {
      * faster than eager launches (75 us per step at n = 65 536 both ways): below a few million rows
      * a step is bound by the GPU's own latency between dependent kernels, not by the host. */
     int32_t graph_mode;
+    /* FOSI_REORTH_SELECTIVE only: threshold of the second pass, in (0, 1); 0 selects 1/sqrt(2), the value the
+     * test's analysis asks for: a step that skips the pass multiplies the loss of orthogonality already present
+     * by up to 1/eta^2 - 1, so below 1/sqrt(2) the errors can compound from step to step (measured at
+     * n = 25.6 M, m = 80: max |Q^T Q - I| 3.6e-11 with the default, 7e-7 with 0.3, 6e-3 with 0.1).  Smaller
+     * values are accepted for studying the scheme; other values are FOSI_ERR_INVALID_ARG. */
+    double reorth_eta;
 } fosi_lanczos_opts;
 #define FOSI_GRAPH_OFF  0
 #define FOSI_GRAPH_ON   1
@@ -168,6 +179,10 @@ fosi_status fosi_lanczos_end(fosi_ctx* ctx, double* alpha_host, double* beta_hos
  * (either pointer may be NULL). */
 fosi_status fosi_graph_stats(fosi_ctx* ctx, int64_t* captures, int64_t* replays);
 
+/* Number of steps of the context's last completed Lanczos run in which FOSI_REORTH_SELECTIVE took its second
+ * pass (0 for the other schemes).  Host-only. */
+fosi_status fosi_lanczos_second_passes(fosi_ctx* ctx, int32_t* count);
+
 /* Algorithm 2 (row-sharded Lanczos) emulated on one GPU: the n rows are cut into `shards` contiguous
  * blocks ("virtual devices", boundaries at multiples of 64 rows).  Every sweep runs once per block on
  * that block's rows of Q (and of U for the planted operator) and leaves its partial sums in one row of
@@ -176,7 +191,8 @@ fosi_status fosi_graph_stats(fosi_ctx* ctx, int64_t* captures, int64_t* replays)
  * other than the planted one are applied to the whole vector (the algorithm's all-gather of v_i is the
  * identity when all blocks live in one memory).  Same arguments, outputs and error behaviour as
  * fosi_lanczos; 1 <= shards <= FOSI_MAX_SHARDS.  Results agree with fosi_lanczos up to the summation
- * order of the partial sums.  Meant for validating the sharded scheme, not for speed. */
+ * order of the partial sums.  FOSI_REORTH_SELECTIVE is not available here (FOSI_ERR_INVALID_ARG).  Meant for
+ * validating the sharded scheme, not for speed. */
 #define FOSI_MAX_SHARDS 64
 fosi_status fosi_lanczos_row_sharded(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, int shards, float* Q_dev,
                                      int64_t ldq, double* alpha_host, double* beta_host, int32_t* m_eff,

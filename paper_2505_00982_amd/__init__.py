@@ -15,9 +15,11 @@ from .binding import (  # noqa: F401
     fosi_lanczos_end,
     fosi_lanczos_row_sharded,
     fosi_lanczos_steps,
+    fosi_lanczos_second_passes,
     REORTH_SINGLE,
     REORTH_TWICE,
     REORTH_LOCAL_FULL,
+    REORTH_SELECTIVE,
     GRAPH_OFF,
     GRAPH_ON,
     fosi_ritz,

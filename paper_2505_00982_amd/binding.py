@@ -26,7 +26,8 @@ PROF = {"hvp_project": 0, "hvp_expand": 1, "reorth_dot": 2, "reorth_sub": 3, "no
 EXPORTS = [
     "fosi_ctx_create", "fosi_ctx_destroy", "fosi_ctx_synchronize", "fosi_last_error", "fosi_status_string",
     "hvp_planted_create", "hvp_diag_create", "hvp_softmax_ggn_create", "hvp_softmax_ggn_bf16_create", "hvp_callback_create", "hvp_apply",
-    "hvp_destroy", "fosi_workspace_bytes", "fosi_lanczos", "fosi_lanczos_begin", "fosi_lanczos_end", "fosi_graph_stats", "fosi_lanczos_row_sharded", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_step_adamw", "fosi_admm_begin",
+    "hvp_destroy", "fosi_workspace_bytes", "fosi_lanczos", "fosi_lanczos_begin", "fosi_lanczos_end", "fosi_graph_stats", "fosi_lanczos_second_passes",
+    "fosi_lanczos_row_sharded", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_step_adamw", "fosi_admm_begin",
     "fosi_admm_end", "fosi_profile_enable", "fosi_profile_reset", "fosi_profile_read",
 ]
 
@@ -38,7 +39,8 @@ class FosiError(RuntimeError):
 
 
 class _LanczosOpts(C.Structure):
-    _fields_ = [("reorth_mode", C.c_int32), ("breakdown_tol", C.c_double), ("graph_mode", C.c_int32)]
+    _fields_ = [("reorth_mode", C.c_int32), ("breakdown_tol", C.c_double), ("graph_mode", C.c_int32),
+                ("reorth_eta", C.c_double)]
 
 
 class _StepParams(C.Structure):
@@ -90,6 +92,7 @@ def load_library() -> C.CDLL:
     lib.fosi_workspace_bytes.argtypes = [vp]
     lib.fosi_workspace_bytes.restype = C.c_size_t
     lib.fosi_graph_stats.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    lib.fosi_lanczos_second_passes.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.fosi_lanczos_steps.argtypes = [i64, C.c_int, C.c_int]
     lib.fosi_tridiag_eigh.argtypes = [C.c_int, dp, dp, dp, dp]
     lib.fosi_ritz.argtypes = [vp, i64, C.c_int, vp, i64, dp, dp, C.c_int, C.c_int, vp, i64, dp, dp]
@@ -277,26 +280,28 @@ class Hvp:
             self.handle = None
 
 
-REORTH_SINGLE, REORTH_TWICE, REORTH_LOCAL_FULL = 1, 2, 3
+REORTH_SINGLE, REORTH_TWICE, REORTH_LOCAL_FULL, REORTH_SELECTIVE = 1, 2, 3, 4
 GRAPH_OFF, GRAPH_ON = 0, 1
 
 
 def fosi_lanczos(ctx: Context, op: Hvp, Q: ColMajor, m: int, reorth_mode: int = 0,
-                 breakdown_tol: float = 1e-6, graph_mode: int = 0) -> Tuple[np.ndarray, np.ndarray, int]:
+                 breakdown_tol: float = 1e-6, graph_mode: int = 0,
+                 reorth_eta: float = 0.0) -> Tuple[np.ndarray, np.ndarray, int]:
     """Q.col(0) holds the start vector.  reorth_mode 0 = library default; graph_mode 1 = capture the
-    run into a HIP graph and replay it (0, default: eager launches).  Returns (alpha, beta, m_eff)."""
+    run into a HIP graph and replay it (0, default: eager launches); reorth_eta: threshold of the second pass
+    of REORTH_SELECTIVE (0 = 1/sqrt 2).  Returns (alpha, beta, m_eff)."""
     alpha, beta = np.zeros(m), np.zeros(m)
     m_eff = C.c_int32(0)
-    opts = _LanczosOpts(reorth_mode, breakdown_tol, graph_mode)
+    opts = _LanczosOpts(reorth_mode, breakdown_tol, graph_mode, reorth_eta)
     ctx.check(ctx.lib.fosi_lanczos(ctx.handle, op.handle, Q.n, m, Q.ptr, Q.ld, _dptr(alpha), _dptr(beta),
                                    C.byref(m_eff), C.byref(opts)))
     return alpha, beta, int(m_eff.value)
 
 
 def fosi_lanczos_begin(ctx: Context, op: Hvp, Q: ColMajor, m: int, reorth_mode: int = 0, breakdown_tol: float = 1e-6,
-                       graph_mode: int = 0) -> int:
+                       graph_mode: int = 0, reorth_eta: float = 0.0) -> int:
     """Enqueues the whole run on the context's stream without waiting for the GPU; returns m for fosi_lanczos_end."""
-    opts = _LanczosOpts(reorth_mode, breakdown_tol, graph_mode)
+    opts = _LanczosOpts(reorth_mode, breakdown_tol, graph_mode, reorth_eta)
     ctx.check(ctx.lib.fosi_lanczos_begin(ctx.handle, op.handle, Q.n, m, Q.ptr, Q.ld, C.byref(opts)))
     return m
 
@@ -314,10 +319,17 @@ def fosi_lanczos_row_sharded(ctx: Context, op: Hvp, Q: ColMajor, m: int, shards:
     """Algorithm 2 emulated on one GPU with `shards` row blocks.  Same contract as fosi_lanczos."""
     alpha, beta = np.zeros(m), np.zeros(m)
     m_eff = C.c_int32(0)
-    opts = _LanczosOpts(reorth_mode, breakdown_tol, 0)
+    opts = _LanczosOpts(reorth_mode, breakdown_tol, 0, 0.0)
     ctx.check(ctx.lib.fosi_lanczos_row_sharded(ctx.handle, op.handle, Q.n, m, shards, Q.ptr, Q.ld, _dptr(alpha),
                                                _dptr(beta), C.byref(m_eff), C.byref(opts)))
     return alpha, beta, int(m_eff.value)
+
+
+def fosi_lanczos_second_passes(ctx: Context) -> int:
+    """Steps of the context's last completed run in which REORTH_SELECTIVE took its second pass."""
+    c = C.c_int32(0)
+    ctx.check(ctx.lib.fosi_lanczos_second_passes(ctx.handle, C.byref(c)))
+    return int(c.value)
 
 
 def fosi_lanczos_steps(n: int, k: int, l: int) -> int:

@@ -420,6 +420,22 @@ static fosi_status enqueue_lanczos(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m
                                                 0.0, nullptr, false, -1.0, h, n, true, flags, FOSI_PROF_REORTH_SUB,
                                                 (ncols + 2) * vec);
             launch_lanczos_finalize(ctx, i, norm_slots, ctx->s.coef_b, ncols, nullptr, 0, ctx->s.loc + 2, tol);
+        } else if (mode == FOSI_REORTH_SELECTIVE) {
+            if (fosi_status s = apply_operator(op, q, h, nullptr, false)) return s;
+            // first pass; the last workgroup of its second stage either ends the step (beta from the
+            // coefficients, the subtraction writes the normalised vector) or, when much was cancelled, leaves
+            // the subtraction unscaled and clears flags[3], on which the kernels of the second pass wait
+            launch_dot_columns(ctx, Q_dev, ldq, ncols, h, nullptr, nullptr, nullptr, n, ctx->s.coef_a, nullptr, 0, 1.0,
+                               nullptr, flags, FOSI_PROF_REORTH_DOT, (ncols + 1) * vec, kTailSelectFirst, i, tol);
+            launch_combine_columns(ctx, Q_dev, ldq, ncols, ctx->s.coef_a, h, 1.0, nullptr, 0.0, nullptr, 0.0, nullptr,
+                                   false, -1.0, h, n, false, flags, FOSI_PROF_REORTH_SUB, (ncols + 2) * vec, ctx->s.scal);
+            launch_dot_columns(ctx, Q_dev, ldq, ncols, h, nullptr, nullptr, nullptr, n, ctx->s.coef_b, nullptr, 0, 1.0,
+                               nullptr, flags + 3, FOSI_PROF_REORTH_DOT, (ncols + 1) * vec, kTailSelectSecond, i, tol);
+            launch_combine_columns(ctx, Q_dev, ldq, ncols, ctx->s.coef_b, h, 1.0, nullptr, 0.0, nullptr, 0.0, nullptr,
+                                   false, -1.0, h, n, false, flags + 3, FOSI_PROF_REORTH_SUB, (ncols + 2) * vec,
+                                   ctx->s.scal);
+            if (fosi_status s = launch_status(ctx, "lanczos step")) return s;
+            continue;
         } else {
             if (fosi_status s = apply_operator(op, q, h, nullptr, false)) return s;
             double* coef[2] = {ctx->s.coef_a, ctx->s.coef_b};
@@ -456,6 +472,7 @@ static bool lanczos_by_graph(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, floa
     *st = FOSI_OK;
     fosi_ctx::GraphKey key;
     key.op = op; key.Q = Q_dev; key.n = n; key.ldq = ldq; key.m = m; key.mode = mode; key.tol = tol;
+    key.eta = ctx->reorth_eta;
     if (ctx->graph_exec == nullptr || !(ctx->graph_key == key)) {
         drop_graph(ctx);
         if (hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeRelaxed) != hipSuccess) {
@@ -506,10 +523,15 @@ fosi_status fosi_lanczos_begin(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, fl
         if (opts->breakdown_tol > 0.0) tol = opts->breakdown_tol;
         graph_mode = opts->graph_mode;
     }
-    if (mode != FOSI_REORTH_SINGLE && mode != FOSI_REORTH_TWICE && mode != FOSI_REORTH_LOCAL_FULL)
+    if (mode != FOSI_REORTH_SINGLE && mode != FOSI_REORTH_TWICE && mode != FOSI_REORTH_LOCAL_FULL &&
+        mode != FOSI_REORTH_SELECTIVE)
         return fail(ctx, FOSI_ERR_INVALID_ARG, "unknown reorth_mode");
     if (graph_mode != FOSI_GRAPH_OFF && graph_mode != FOSI_GRAPH_ON)
         return fail(ctx, FOSI_ERR_INVALID_ARG, "unknown graph_mode");
+    double eta = 0.70710678118654752;
+    if (opts != nullptr && opts->reorth_eta != 0.0) eta = opts->reorth_eta;
+    if (!(eta > 0.0 && eta < 1.0)) return fail(ctx, FOSI_ERR_INVALID_ARG, "reorth_eta must lie in (0, 1)");
+    ctx->reorth_eta = eta;
 
     int* flags = ctx->s.flags;
     // (cleared outside the graph: memset nodes are kept out of captured work)
@@ -538,7 +560,7 @@ fosi_status fosi_lanczos_end(fosi_ctx* ctx, double* alpha_host, double* beta_hos
     ctx->pending_m = 0;
     *m_eff = 0;
     int* flags = ctx->s.flags;
-    int hflags[2] = {0, 0};
+    int hflags[5] = {0, 0, 0, 0, 0};
     if (fosi_status s = check_hip(ctx, hipMemcpyAsync(alpha_host, ctx->s.alpha, sizeof(double) * m, hipMemcpyDeviceToHost,
                                                       ctx->stream), "copy alpha")) return s;
     if (fosi_status s = check_hip(ctx, hipMemcpyAsync(beta_host, ctx->s.beta, sizeof(double) * m, hipMemcpyDeviceToHost,
@@ -549,6 +571,7 @@ fosi_status fosi_lanczos_end(fosi_ctx* ctx, double* alpha_host, double* beta_hos
     // leave the stop flag clear so that later operator applications run
     if (fosi_status s = check_hip(ctx, hipMemsetAsync(flags, 0, 8 * sizeof(int), ctx->stream), "clear flags")) return s;
     *m_eff = hflags[1];
+    ctx->second_passes = hflags[4];
     if (hflags[0] == 2) return fail(ctx, FOSI_ERR_NONFINITE, "non-finite value in the Lanczos recurrence");
     return FOSI_OK;
 }
@@ -568,6 +591,13 @@ fosi_status fosi_graph_stats(fosi_ctx* ctx, int64_t* captures, int64_t* replays)
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
     if (captures != nullptr) *captures = ctx->graph_captures;
     if (replays != nullptr) *replays = ctx->graph_replays;
+    return FOSI_OK;
+}
+
+fosi_status fosi_lanczos_second_passes(fosi_ctx* ctx, int32_t* count) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (count == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "null argument");
+    *count = ctx->second_passes;
     return FOSI_OK;
 }
 
@@ -671,6 +701,8 @@ fosi_status fosi_lanczos_row_sharded(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int
         if (opts->reorth_mode != 0) mode = opts->reorth_mode;
         if (opts->breakdown_tol > 0.0) tol = opts->breakdown_tol;
     }
+    if (mode == FOSI_REORTH_SELECTIVE)
+        return fail(ctx, FOSI_ERR_INVALID_ARG, "the selective scheme is not available in the row-sharded run");
     if (mode != FOSI_REORTH_SINGLE && mode != FOSI_REORTH_TWICE && mode != FOSI_REORTH_LOCAL_FULL)
         return fail(ctx, FOSI_ERR_INVALID_ARG, "unknown reorth_mode");
     const int passes = mode == FOSI_REORTH_SINGLE ? 1 : 2;
@@ -721,7 +753,7 @@ fosi_status fosi_lanczos_row_sharded(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int
         if (fosi_status s = launch_status(ctx, "sharded lanczos step")) return s;
     }
 
-    int hflags[2] = {0, 0};
+    int hflags[5] = {0, 0, 0, 0, 0};
     if (fosi_status s = check_hip(ctx, hipMemcpyAsync(alpha_host, ctx->s.alpha, sizeof(double) * m, hipMemcpyDeviceToHost,
                                                       ctx->stream), "copy alpha")) return s;
     if (fosi_status s = check_hip(ctx, hipMemcpyAsync(beta_host, ctx->s.beta, sizeof(double) * m, hipMemcpyDeviceToHost,
@@ -731,6 +763,7 @@ fosi_status fosi_lanczos_row_sharded(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int
     if (fosi_status s = check_hip(ctx, hipStreamSynchronize(ctx->stream), "lanczos synchronize")) return s;
     if (fosi_status s = check_hip(ctx, hipMemsetAsync(flags, 0, 8 * sizeof(int), ctx->stream), "clear flags")) return s;
     *m_eff = hflags[1];
+    ctx->second_passes = hflags[4];
     if (hflags[0] == 2) return fail(ctx, FOSI_ERR_NONFINITE, "non-finite value in the Lanczos recurrence");
     return FOSI_OK;
 }

@@ -78,9 +78,10 @@ struct fosi_ctx {
         const void* Q = nullptr;
         int64_t n = 0, ldq = 0;
         int m = 0, mode = 0;
-        double tol = 0.0;
+        double tol = 0.0, eta = 0.0;
         bool operator==(const GraphKey& o) const {
-            return op == o.op && Q == o.Q && n == o.n && ldq == o.ldq && m == o.m && mode == o.mode && tol == o.tol;
+            return op == o.op && Q == o.Q && n == o.n && ldq == o.ldq && m == o.m && mode == o.mode && tol == o.tol &&
+                   eta == o.eta;
         }
     } graph_key;
     hipGraphExec_t graph_exec = nullptr;
@@ -88,6 +89,8 @@ struct fosi_ctx {
     int64_t graph_replays = 0, graph_captures = 0;
     int sm_count = 256;
     int pending_m = 0;                  // steps of the Lanczos run enqueued by fosi_lanczos_begin and not yet collected
+    double reorth_eta = 0.70710678118654752;   // 'selective' Gram-Schmidt scheme: threshold of the run being enqueued
+    int second_passes = 0;              // ... and how many steps of the last completed run took the second pass
 };
 
 struct fosi_hvp {
@@ -143,8 +146,10 @@ struct ProfScope {
 //   kTailNone;  kTailLocal: ctx->s.loc = {coef[ncols-1], ncols > 1 ? coef[0] : 0, coef[ncols]} and their negatives
 //   in ctx->s.scal[4..5] (transposed product against [q_{i-1}, q_i] or [q_i]);  kTailLanczosStep: end of step
 //   tail_step of a 'local_full' run (alpha, beta, flags and 1/beta from the coefficients and ctx->s.loc, before
-//   the subtraction sweep; same arithmetic as launch_lanczos_finalize_early).
-constexpr int kTailNone = 0, kTailLocal = 1, kTailLanczosStep = 2;
+//   the subtraction sweep; same arithmetic as launch_lanczos_finalize_early);  kTailSelectFirst / kTailSelectSecond:
+//   the two passes of the 'selective' scheme (the first decides, with ctx->reorth_eta, whether it ends the step
+//   or ctx->s.flags[3] lets the second pass's kernels run).
+constexpr int kTailNone = 0, kTailLocal = 1, kTailLanczosStep = 2, kTailSelectFirst = 3, kTailSelectSecond = 4;
 void launch_dot_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, const float* x,
                         const float* x2, const float* x3, const double* xs, int64_t n, double* coef,
                         const float* scale, int nscale, double gscale, const double* add_last2,

@@ -238,16 +238,20 @@ __global__ __launch_bounds__(kThreads) void k_dot_columns(
 
 // What the last workgroup of the second stage does once every column sum is in memory (saves a launch).
 struct ReduceTail {
-    int kind;          // 0 none; 1 scalars of the local Gram-Schmidt pass; 2 end of a Lanczos step
-    int step;          // kind 2: Lanczos step index
-    double tol;        // kind 2: breakdown tolerance
+    int kind;          // 0 none; 1 scalars of the local Gram-Schmidt pass; 2 end of a Lanczos step;
+                       // 3 / 4: first / second pass of the 'selective' scheme
+    int step;          // kinds 2-4: Lanczos step index
+    double tol;        // kinds 2-4: breakdown tolerance
+    double eta;        // kind 3: a second pass follows when the first one leaves less than eta * ||h||
     double* loc;       // kind 1: written {alpha~, beta~, ||h||^2}; kind 2: read
     double* neg;       // kind 1: written {-alpha~, -beta~}
     double* alpha;     // kind 2 outputs
     double* beta;
     double* hnorm;
     double* scal;      // kind 2: scal[0] = 1 / beta
-    int* flags;        // [0] stop flag, [1] completed steps, [2] arrival counter of this kernel
+    int* flags;        // [0] stop flag, [1] completed steps, [2] arrival counter of this kernel,
+                       // [3] 'selective' scheme: non-zero = the second pass of this step is skipped,
+                       // [4] 'selective' scheme: second passes done so far
 };
 
 // Second stage: one wavefront per output column sums the row-slot partials in a fixed order and applies
@@ -262,6 +266,12 @@ struct ReduceTail {
 //          x - Q c_full has squared norm ||x||^2 - ||c_full||^2 up to (Q^T Q - I) c_full . c_full, far below
 //          fp64 rounding here, so beta is known BEFORE the subtraction sweep, which can then write the
 //          normalised vector directly (no separate scaling sweep).
+//   kind 3 (first pass of the 'selective' scheme, out = Q^T h and ||h||^2): the pass leaves
+//          rho^2 = ||h||^2 - ||c||^2.  rho > eta ||h||: little was cancelled, the single pass is as good as it gets
+//          in fp32 storage; the step ends here as in kind 2 and flags[3] = 1 makes the second pass's kernels
+//          return at once.  Otherwise (the rounding error of the pass, ~eps ||h||, is large against what is
+//          left) the subtraction writes h - Q c unscaled (scal[0] = 1), flags[3] = 0, and
+//   kind 4 (second pass, out = Q^T h' and ||h'||^2) ends the step: alpha += c_i, beta from ||h'||^2 - ||c||^2.
 __global__ __launch_bounds__(64) void k_reduce_columns(
     const double* __restrict__ partials, int nslots, int64_t slot_stride, int64_t col_stride, double* out,
     const float* __restrict__ scale, int nscale, double gscale, int ncols, const double* __restrict__ add_last2,
@@ -308,19 +318,32 @@ __global__ __launch_bounds__(64) void k_reduce_columns(
         return;
     }
     if (tail.flags[0] != 0) return;
+    const bool with_local = tail.kind == 2;
     double q = 0.0;
     for (int c = lane; c < ncols; c += 64) {
         double cf = out[c];
-        if (c == ncols - 1) cf -= tail.loc[0];
-        if (c == ncols - 2) cf -= tail.loc[1];
+        if (with_local && c == ncols - 1) cf -= tail.loc[0];
+        if (with_local && c == ncols - 2) cf -= tail.loc[1];
         q = fma(cf, cf, q);
     }
     q = wave_sum(q);
     if (lane == 0) {
-        const double a = out[ncols - 1];
+        double a = out[ncols - 1];
         const double b2 = out[ncols] - q;
         const double b = b2 > 0.0 ? sqrt(b2) : (b2 == b2 ? 0.0 : b2);     // NaN stays NaN
-        const double hn = sqrt(tail.loc[2]);
+        double hn;
+        if (tail.kind == 2) hn = sqrt(tail.loc[2]);
+        else if (tail.kind == 3) hn = sqrt(out[ncols]);
+        else { hn = tail.hnorm[tail.step]; a += tail.alpha[tail.step]; }
+        if (tail.kind == 3 && (b - b == 0.0) && (hn - hn == 0.0) && !(b > tail.eta * hn)) {
+            // much was cancelled: the step ends in the second pass
+            tail.alpha[tail.step] = a;
+            tail.hnorm[tail.step] = hn;
+            tail.scal[0] = 1.0;
+            tail.flags[3] = 0;
+            tail.flags[4] += 1;
+            return;
+        }
         tail.alpha[tail.step] = a;
         tail.beta[tail.step] = b;
         tail.hnorm[tail.step] = hn;
@@ -329,6 +352,9 @@ __global__ __launch_bounds__(64) void k_reduce_columns(
         if (!finite) tail.flags[0] = 2;
         else if (!(b > tail.tol * hn)) tail.flags[0] = 1;
         tail.scal[0] = 1.0 / b;
+        // 'selective': after a first pass that ends the step, or once the run has stopped, the second pass's
+        // kernels (which test flags[3]) return at once; after a second pass its subtraction must still run
+        if (tail.kind == 3 || (tail.kind == 4 && (!finite || !(b > tail.tol * hn)))) tail.flags[3] = 1;
     }
 }
 
@@ -1026,6 +1052,7 @@ ReduceTail make_tail(fosi_ctx* ctx, int kind, int step, double tol) {
     t.kind = kind;
     t.step = step;
     t.tol = tol;
+    t.eta = ctx->reorth_eta;
     t.loc = ctx->s.loc;
     t.neg = ctx->s.scal + 4;
     t.alpha = ctx->s.alpha;

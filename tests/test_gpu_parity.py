@@ -233,7 +233,7 @@ def test_many_repeats_are_bit_identical(fo, ctx):
 
 
 # ------------------------------------------------------------------ ragged sizes, single pass, small k+l
-@pytest.mark.parametrize("mode", [2, 3])      # two full passes; local pass + full pass (the default)
+@pytest.mark.parametrize("mode", [2, 3, 4])   # two full passes; local pass + full pass (the default); selective
 @pytest.mark.parametrize("n,m,k,l", [(1000 + 3, 12, 1, 0), (4096 + 61, 20, 3, 2), (70001, 24, 4, 3)])
 def test_ragged_sizes(fo, ctx, n, m, k, l, mode):
     w = wl.planted_workload(2, n=n)
@@ -262,6 +262,88 @@ def test_single_pass_option(fo, ctx):
     # a single classical Gram-Schmidt pass in fp32 loses orthogonality quickly (the error grows ~30x per
     # step on this operator), which is why two passes are the default: only the early entries are compared
     assert np.max(np.abs(alpha[:6] - res.alpha[:6])) < 1e-6 and np.max(np.abs(beta[:6] - res.beta[:6])) < 1e-6
+    op.close()
+
+
+def test_selective_second_pass(fo, ctx):
+    """The 'selective' scheme: one full pass, and a second one only in the steps whose first pass left less than
+    eta * ||H q_i||.  On this operator (eigenvalues in [1, 2]) every step cancels most of H q_i, so the default
+    threshold takes the second pass everywhere and all ten entries agree with the fp64 oracle (the single pass
+    above holds six); a tiny threshold never takes it, a threshold close to 1 always does."""
+    n = 5000
+    d = np.linspace(1.0, 2.0, n).astype(np.float32)
+    v1 = wl.normal_vector(1, 98, n)
+    op = ctx.hvp_diag(dev(d))
+    res = oracle.lanczos(lambda v: oracle.hvp_diag(d, v), v1, 10)
+    ratios = res.beta / res.hnorm                                # what the first pass leaves, relative to ||H q_i||
+    out = {}
+    for eta in (0.0, 1e-3, 0.999):
+        Q = fo.ColMajor(n, 11)
+        Q.col(0).copy_(dev(v1))
+        alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, 10, reorth_mode=fo.REORTH_SELECTIVE, reorth_eta=eta)
+        assert m_eff == 10
+        out[eta] = (alpha, beta, fo.fosi_lanczos_second_passes(ctx), Q.to_numpy(10).astype(np.float64))
+    thr = 2.0 ** -0.5
+    assert np.all(np.abs(ratios - thr) > 0.01)                   # no step sits on the threshold
+    assert out[0.0][2] == int(np.sum(ratios < thr)) == 10
+    assert out[1e-3][2] == 0 and out[0.999][2] == 10
+    for eta in (0.0, 0.999):
+        alpha, beta, _, Q = out[eta]
+        assert np.max(np.abs(alpha - res.alpha)) < 1e-6 and np.max(np.abs(beta - res.beta)) < 1e-6
+        assert np.abs(Q.T @ Q - np.eye(10)).max() < 1e-5
+    # never a second pass although every step cancels 97 % of ||H q_i||^2: orthogonality is lost at ~30x per step,
+    # and beta taken from the coefficients suffers from it before the vectors do; only the first entries hold
+    alpha, beta = out[1e-3][:2]
+    assert np.max(np.abs(alpha[:2] - res.alpha[:2])) < 1e-6 and np.max(np.abs(beta[:2] - res.beta[:2])) < 1e-6
+    # the other schemes leave the counter at zero; thresholds outside (0, 1) are refused
+    Q = fo.ColMajor(n, 11)
+    Q.col(0).copy_(dev(v1))
+    fo.fosi_lanczos(ctx, op, Q, 10)
+    assert fo.fosi_lanczos_second_passes(ctx) == 0
+    for bad in (1.0, -0.5, float("nan")):
+        with pytest.raises(fo.FosiError):
+            fo.fosi_lanczos(ctx, op, Q, 10, reorth_mode=fo.REORTH_SELECTIVE, reorth_eta=bad)
+    op.close()
+
+
+def test_selective_takes_the_second_pass_only_where_needed(fo, ctx):
+    """Planted workload: the steps that take the second pass are those in which beta_i / ||H q_i|| is below the
+    threshold, with ||H q_i||^2 = alpha_i^2 + beta_{i-1}^2 + beta_i^2 from the returned tridiagonal matrix (steps
+    closer to the threshold than 2 % may go either way).  With the default threshold the result keeps the parity
+    bars of the default scheme, breakdown step included.  A low threshold (0.3) gives a real mix of both kinds of
+    step, but a step without second pass multiplies the loss of orthogonality already present by up to 1 / eta^2
+    (the classical analysis of the test, which is why its threshold is 1/sqrt 2): only the count and the
+    well-conditioned leading entries are checked there."""
+    w = wl.planted_workload(1)
+    res_or = oracle.lanczos(planted_op(w), w.v1, w.m)
+    assert res_or.m_eff == 33
+    ld = wl.padded_ld(w.n)
+    U = fo.ColMajor.from_numpy(w.U, ld)
+    op = ctx.hvp_planted(U, dev(w.lam), float(w.shift))
+    for eta in (0.3, 0.0):
+        thr = eta if eta else 2.0 ** -0.5
+        Q = fo.ColMajor(w.n, w.m + 1, ld)
+        Q.col(0).copy_(dev(w.v1))
+        alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, w.m, reorth_mode=fo.REORTH_SELECTIVE, reorth_eta=eta)
+        count = fo.fosi_lanczos_second_passes(ctx)
+        assert m_eff in (33, 34)
+        a, b = alpha[:m_eff], beta[:m_eff]
+        ratios = b / np.sqrt(a ** 2 + np.concatenate([[0.0], b[:-1]]) ** 2 + b ** 2)
+        sure, maybe = int(np.sum(ratios < 0.98 * thr)), int(np.sum(np.abs(ratios - thr) <= 0.02 * thr))
+        assert sure <= count <= sure + maybe, (eta, sure, maybe, count)
+        if eta:
+            assert 5 <= sure < m_eff - 5                         # a real mix of both kinds of step
+        else:
+            assert count == m_eff - 1                            # all but the first step (ratio 0.999)
+        ratios_or = res_or.beta[:16] / res_or.hnorm[:16]         # the well-conditioned leading part, from the oracle
+        assert np.array_equal(ratios_or < thr, ratios[:16] < thr)
+        assert np.max(np.abs(alpha[:16] - res_or.alpha[:16])) < 2e-4 * 1e3
+    Qh = Q.to_numpy(m_eff).astype(np.float64)
+    assert np.abs(Qh.T @ Qh - np.eye(m_eff)).max() < 1e-5
+    V = fo.ColMajor(w.n, w.k + w.l, ld)
+    evals, resid = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, w.k, w.l, V)
+    ctx.synchronize()
+    check_ritz_parity(w, dict(V=V, evals=evals, k=w.k, l=w.l, m_eff=m_eff), res_or)
     op.close()
 
 
