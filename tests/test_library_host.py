@@ -124,6 +124,8 @@ def test_null_context_is_rejected_without_touching_a_gpu(fo):
     assert lib.hvp_apply(None, None, None) == -1
     assert lib.fosi_profile_enable(None, 1) == -1
     assert lib.fosi_admm_begin(None, 10, 0.1, None, None, None) == -1
+    assert lib.fosi_lanczos_second_passes(None, None) == -1
+    assert lib.fosi_lanczos_end(None, None, None, None) == -1
 
 
 def test_bench_refuses_more_than_one_gpu():
