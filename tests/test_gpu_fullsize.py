@@ -255,11 +255,12 @@ def test_update_rules_at_four_million_rows(fo, ctx):
     assert rel_l2(v1.cpu().numpy(), v_ref) <= 1e-5
 
 
-@pytest.mark.parametrize("mode_name", ["single", "twice"])
+@pytest.mark.parametrize("mode_name", ["single", "twice", "selective"])
 def test_workload4_other_schemes_full_size(fo, ctx, mode_name):
-    """The printed single pass and the twice-repeated pass at n = 25.6 M (40 steps): these schemes run the kernel
-    variants that keep computing with a stored value (sum of squares of the subtraction's output), at a size where
-    the memory system is under full load.  The tridiagonal must match the independent fp64 route."""
+    """The printed single pass, the twice-repeated pass and the selective second pass at n = 25.6 M (40 steps): the
+    first two run the kernel variants that keep computing with a stored value (sum of squares of the subtraction's
+    output), the third switches its second pass on the device, at a size where the memory system is under full load.
+    The tridiagonal must match the independent fp64 route."""
     from workloads.device import planted_workload_device
     w = planted_workload_device(4)
     n, r, m = w.n, w.r, 40
@@ -267,10 +268,16 @@ def test_workload4_other_schemes_full_size(fo, ctx, mode_name):
     op = ctx.hvp_planted(U, w.lam, w.shift)
     Q = fo.ColMajor(n, m + 1, w.ld)
     Q.col(0).copy_(w.v1)
-    mode = {"single": fo.REORTH_SINGLE, "twice": fo.REORTH_TWICE}[mode_name]
+    mode = {"single": fo.REORTH_SINGLE, "twice": fo.REORTH_TWICE, "selective": fo.REORTH_SELECTIVE}[mode_name]
     alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, m, reorth_mode=mode)
     ctx.synchronize()
     assert m_eff == m and np.all(np.isfinite(alpha)) and np.all(np.isfinite(beta))
+    if mode_name == "selective":
+        # second pass exactly in the steps that cancelled much (a step within 2 % of the threshold may go either way)
+        hn = np.sqrt(alpha ** 2 + np.concatenate([[0.0], beta[:-1]]) ** 2 + beta ** 2)
+        thr = 2.0 ** -0.5
+        sure, maybe = int(np.sum(beta / hn < 0.98 * thr)), int(np.sum(np.abs(beta / hn - thr) <= 0.02 * thr))
+        assert sure <= fo.fosi_lanczos_second_passes(ctx) <= sure + maybe and sure >= m // 2
     lam = w.lam.cpu().numpy().astype(np.float64)
     scale = np.abs(lam).max()
     G = _gram_f64(w.U.view(r, w.ld), n, w.v1)

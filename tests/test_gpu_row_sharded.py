@@ -121,4 +121,6 @@ def test_sharded_argument_errors(fo, ctx):
         fo.fosi_lanczos_row_sharded(ctx, op, Q, 4, 0)
     with pytest.raises(fo.FosiError):
         fo.fosi_lanczos_row_sharded(ctx, op, Q, 4, 65)
+    with pytest.raises(fo.FosiError, match="selective"):
+        fo.fosi_lanczos_row_sharded(ctx, op, Q, 4, 2, reorth_mode=fo.REORTH_SELECTIVE)
     op.close()
