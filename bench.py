@@ -82,9 +82,12 @@ def cpu_baseline(cfg_id: int, n_sample: int) -> dict:
     g = w.grad(0)
     t0 = time.perf_counter()
     res = oracle.lanczos(op, w.v1, w.m)
+    t1 = time.perf_counter()
     rz = oracle.ritz(res.Q, res.alpha, res.beta, res.m_eff, w.k, w.l)
+    t2 = time.perf_counter()
     oracle.fosi_step(w.w0, g, rz.V, rz.evals, np.zeros(w.n), float(p.alpha), float(p.lr), float(p.momentum))
-    dt = time.perf_counter() - t0
+    t3 = time.perf_counter()
+    dt = t3 - t0
     vecs = algorithmic_vectors(res.m_eff, w.r, w.k + w.l, "single", False)   # the oracle does one Gram-Schmidt pass
     gbs = vecs["total"] * 4.0 * n_sample / dt / 1e9
     try:
@@ -96,7 +99,8 @@ def cpu_baseline(cfg_id: int, n_sample: int) -> dict:
             "sample": f"numpy fp64 oracle, same workload with n={n_sample} rows (1/{max(1, wl.CONFIGS[cfg_id]['n'] // n_sample)} of the "
                       f"block), full m={w.m}, one Lanczos+Ritz+update pass, {dt:.1f} s; bytes counted as fp32 "
                       f"algorithmic traffic of its single-pass variant",
-            "seconds": round(dt, 2)}
+            "seconds": round(dt, 2),
+            "phase_seconds": {"lanczos": round(t1 - t0, 2), "ritz": round(t2 - t1, 2), "step": round(t3 - t2, 3)}}
 
 
 def bench_ggn(args, fo, torch, np) -> int:
