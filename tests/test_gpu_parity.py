@@ -614,3 +614,49 @@ def test_maximum_lanczos_length_and_planted_rank(fo, ctx):
         # every Ritz vector is Q S with orthonormal S: unit norm and mutually orthogonal to fp32 accuracy
         assert np.abs(Vg.T @ Vg - np.eye(k + l)).max() < 1e-5
     op.close()
+
+
+# ------------------------------------------------------------------ launch-shape knobs
+@pytest.mark.parametrize("env", [
+    {"FOSI_DOT_JB": "16"}, {"FOSI_DOT_JB": "32"},                 # slot widths the library picks only above 4 M rows / never
+    {"FOSI_DOT_BLOCKS": "8"}, {"FOSI_DOT_BLOCKS": "100000"},      # one row lane per XCD; more lanes than row groups
+    {"FOSI_EARLY_BETA": "0"},                                     # beta from the subtraction's own sum of squares
+    {"FOSI_RITZ_MFMA": "0"},                                      # vector-ALU Ritz kernel below 33 columns
+    {"FOSI_COMB_ROWS": "1", "FOSI_COMB_COLS": "16"}, {"FOSI_COMB_ROWS": "2", "FOSI_COMB_COLS": "4"},
+    {"FOSI_COMB_ROWS": "8", "FOSI_COMB_COLS": "2"}, {"FOSI_COMB_BLOCKS": "3"},
+    {"FOSI_STEP_WAVES": "1"},
+], ids=lambda e: ",".join(f"{k[5:]}={v}" for k, v in e.items()))
+def test_launch_shape_knobs_keep_the_results(fo, env, monkeypatch):
+    """The environment knobs read at context creation select other compiled variants and launch shapes of the
+    same kernels (used by the library at other sizes, or kept for tuning): each must reproduce the oracle on a
+    ragged size to the bars of the default shapes."""
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    ctx = fo.Context(0)
+    try:
+        w = wl.planted_workload(2, n=70001)
+        m, k, l = 24, 4, 3
+        g = gpu_curvature(fo, ctx, w, m=m, k=k, l=l)
+        res_or = oracle.lanczos(planted_op(w), w.v1, m)
+        assert g["m_eff"] == res_or.m_eff == m
+        scale = np.abs(w.lam).max()
+        assert np.max(np.abs(g["alpha"] - res_or.alpha)) < 1e-5 * scale
+        assert np.max(np.abs(g["beta"] - res_or.beta)) < 1e-5 * scale
+        Q = g["Q"].to_numpy(m).astype(np.float64)
+        assert np.abs(Q.T @ Q - np.eye(m)).max() < 1e-5
+        check_ritz_parity(w, g, res_or)
+        # one update with a dual variable on the GPU's own Ritz pairs
+        p = w.params
+        grad, pi = w.grad(0), 0.01 * wl.normal_vector(2, 77, w.n)
+        wd, md = dev(w.w0), torch.zeros(w.n, device="cuda")
+        sp = fo.StepParams(float(p.alpha), float(p.lr), float(p.momentum), float(p.sigma), 1)
+        fo.fosi_step(ctx, g["V"], k + l, g["evals"], dev(grad), dev(pi), md, wd, sp)
+        ctx.synchronize()
+        Vg = g["V"].to_numpy().astype(np.float64)
+        w_ref, b_ref = oracle.fosi_step(w.w0, grad, Vg, g["evals"], np.zeros(w.n), float(p.alpha), float(p.lr),
+                                        float(p.momentum), sigma=float(p.sigma), pi=pi.astype(np.float64), curv_mode="abs")
+        assert rel_l2(wd.cpu().numpy().astype(np.float64) - w.w0, w_ref - w.w0) <= 5e-5
+        assert rel_l2(md.cpu().numpy(), b_ref) <= STEP_RTOL
+        g["op"].close()
+    finally:
+        ctx.close()
