@@ -236,6 +236,27 @@ __global__ __launch_bounds__(kThreads) void k_dot_columns(
     }
 }
 
+// End of one Lanczos step (Algorithm 1), shared by every kernel that finishes one: stores the diagonal entry a, the
+// off-diagonal entry b and ||H q_step|| = hn, counts the step, raises the stop flag on a non-finite value (2) or
+// on breakdown (1: b <= tol * hn) and leaves 1 / b for the normalisation.  Returns true when the run stops here.
+__device__ __forceinline__ bool store_step_scalars(double a, double b, double hn, int step, double tol,
+                                                   double* alpha, double* beta, double* hnorm, double* scal,
+                                                   int* flags) {
+    alpha[step] = a;
+    beta[step] = b;
+    hnorm[step] = hn;
+    flags[1] = step + 1;
+    const bool finite = (a - a == 0.0) && (b - b == 0.0) && (hn - hn == 0.0);
+    const bool stops = !finite || !(b > tol * hn);
+    if (!finite) flags[0] = 2;
+    else if (stops) flags[0] = 1;
+    scal[0] = 1.0 / b;
+    return stops;
+}
+
+// sqrt of a difference of squares that rounding may have pushed below zero; NaN stays NaN
+__device__ __forceinline__ double sqrt_clamped(double b2) { return b2 > 0.0 ? sqrt(b2) : (b2 == b2 ? 0.0 : b2); }
+
 // What the last workgroup of the second stage does once every column sum is in memory (saves a launch).
 struct ReduceTail {
     int kind;          // 0 none; 1 scalars of the local Gram-Schmidt pass; 2 end of a Lanczos step;
@@ -329,8 +350,7 @@ __global__ __launch_bounds__(64) void k_reduce_columns(
     q = wave_sum(q);
     if (lane == 0) {
         double a = out[ncols - 1];
-        const double b2 = out[ncols] - q;
-        const double b = b2 > 0.0 ? sqrt(b2) : (b2 == b2 ? 0.0 : b2);     // NaN stays NaN
+        const double b = sqrt_clamped(out[ncols] - q);
         double hn;
         if (tail.kind == 2) hn = sqrt(tail.loc[2]);
         else if (tail.kind == 3) hn = sqrt(out[ncols]);
@@ -344,17 +364,11 @@ __global__ __launch_bounds__(64) void k_reduce_columns(
             tail.flags[4] += 1;
             return;
         }
-        tail.alpha[tail.step] = a;
-        tail.beta[tail.step] = b;
-        tail.hnorm[tail.step] = hn;
-        tail.flags[1] = tail.step + 1;
-        const bool finite = (a - a == 0.0) && (b - b == 0.0) && (hn - hn == 0.0);
-        if (!finite) tail.flags[0] = 2;
-        else if (!(b > tail.tol * hn)) tail.flags[0] = 1;
-        tail.scal[0] = 1.0 / b;
+        const bool stops = store_step_scalars(a, b, hn, tail.step, tail.tol, tail.alpha, tail.beta, tail.hnorm,
+                                              tail.scal, tail.flags);
         // 'selective': after a first pass that ends the step, or once the run has stopped, the second pass's
         // kernels (which test flags[3]) return at once; after a second pass its subtraction must still run
-        if (tail.kind == 3 || (tail.kind == 4 && (!finite || !(b > tail.tol * hn)))) tail.flags[3] = 1;
+        if (tail.kind == 3 || (tail.kind == 4 && stops)) tail.flags[3] = 1;
     }
 }
 
@@ -719,14 +733,7 @@ __global__ __launch_bounds__(kThreads) void k_lanczos_finalize(
         const double b = sqrt(s);
         // ||H q_step||^2 before orthogonalisation: by-product of the first pass, or handed in
         const double hn = sqrt(hh_ptr != nullptr ? hh_ptr[0] : coef_a[cols_a]);
-        alpha[step] = a;
-        beta[step] = b;
-        hnorm[step] = hn;
-        flags[1] = step + 1;
-        const bool finite = (a - a == 0.0) && (b - b == 0.0) && (hn - hn == 0.0);
-        if (!finite) flags[0] = 2;
-        else if (!(b > tol * hn)) flags[0] = 1;
-        scal[0] = 1.0 / b;
+        store_step_scalars(a, b, hn, step, tol, alpha, beta, hnorm, scal, flags);
     }
 }
 
@@ -751,18 +758,8 @@ __global__ __launch_bounds__(kThreads) void k_lanczos_finalize_early(
     }
     s = block_sum(s, red);
     if (threadIdx.x == 0) {
-        const double a = c[cols - 1];
-        const double b2 = c[cols] - s;
-        const double b = b2 > 0.0 ? sqrt(b2) : (b2 == b2 ? 0.0 : b2);     // NaN stays NaN
-        const double hn = sqrt(loc[2]);
-        alpha[step] = a;
-        beta[step] = b;
-        hnorm[step] = hn;
-        flags[1] = step + 1;
-        const bool finite = (a - a == 0.0) && (b - b == 0.0) && (hn - hn == 0.0);
-        if (!finite) flags[0] = 2;
-        else if (!(b > tol * hn)) flags[0] = 1;
-        scal[0] = 1.0 / b;
+        store_step_scalars(c[cols - 1], sqrt_clamped(c[cols] - s), sqrt(loc[2]), step, tol, alpha, beta, hnorm, scal,
+                           flags);
     }
 }
 
