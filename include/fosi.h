@@ -130,7 +130,7 @@ typedef struct {
     /* The step count stops early (m_eff < m) when ||h after orthogonalisation||
      * <= breakdown_tol * ||H q_i||: the Krylov space is exhausted.  Default 1e-6. */
     double breakdown_tol;
-    /* FOSI_GRAPH_OFF (0, default): the ~9 kernels of every step are launched one by one.
+    /* FOSI_GRAPH_OFF (0, default): the seven kernels of every step (default scheme) are launched one by one.
      * FOSI_GRAPH_ON (1): when the context's stream can be captured (it is not the null stream),
      * profiling is off and the operator is not a callback, the launches of the whole run are captured
      * once into a HIP graph, kept in the context and replayed for as long as the operator, sizes,
