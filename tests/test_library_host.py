@@ -156,3 +156,30 @@ def test_bf16_rounding_of_the_generator_matches_torch():
     x = np.concatenate([x, ties, np.nextafter(ties, np.float32(0)), np.nextafter(ties, np.float32(4))])
     ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
     assert np.array_equal(wl.generators.round_to_bf16(x), ref)
+
+
+def test_header_is_plain_c_and_links_from_c(fo, tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 (pedantic, no C++), and a C program links against the
+    library and calls a host-only entry point."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "fosi.h"\n'
+                   "int main(void) {\n"
+                   "    fosi_lanczos_opts o = {0};\n"
+                   "    double a[3] = {2.0, 2.0, 2.0}, b[2] = {-1.0, -1.0}, ev[3];\n"
+                   "    (void)o;\n"
+                   "    if (fosi_lanczos_steps(4096, 10, 0) != 40) return 1;\n"
+                   "    if (fosi_tridiag_eigh(3, a, b, ev, 0) != FOSI_OK) return 2;\n"
+                   "    return (ev[0] < ev[1] && ev[1] < ev[2] && ev[1] > 1.999999 && ev[1] < 2.000001) ? 0 : 3;\n"
+                   "}\n")
+    libdir = os.path.dirname(fo.library_path())
+    exe = tmp_path / "use_header"
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"),
+                        str(src), "-o", str(exe), "-L", libdir, "-lfosi_hip", f"-Wl,-rpath,{libdir}"],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, (r.returncode, r.stderr)
