@@ -456,6 +456,52 @@ def test_admm_outer_iteration_cfg2_reduced(fo, ctx):
     assert rel_l2(pi.cpu().numpy(), pi_ref) <= 1e-6
 
 
+def test_three_outer_iterations_from_zero_multiplier(fo, ctx):
+    """Algorithm 3 as a loop: three outer iterations from pi = 0, each with a curvature refresh (new start vector,
+    so a different Krylov space), the anchor step, four updates with fresh gradients and the multiplier rule; the
+    momentum and the multiplier carry over.  The oracle runs the same sequence in fp64 on the GPU's Ritz pairs of
+    each refresh and on its own multiplier and anchor, so this is end to end over all twelve updates."""
+    w = wl.planted_workload(2, n=(1 << 15) + 3)
+    p = w.params
+    sig = float(p.sigma)
+    sp = fo.StepParams(float(p.alpha), float(p.lr), float(p.momentum), sig, 1)
+    ld = wl.padded_ld(w.n)
+    U = fo.ColMajor.from_numpy(w.U, ld)
+    op = ctx.hvp_planted(U, dev(w.lam), float(w.shift))
+    Q, V = fo.ColMajor(w.n, w.m + 1, ld), fo.ColMajor(w.n, w.k + w.l, ld)
+    wa, pi = dev(w.w0), torch.zeros(w.n, device="cuda")
+    mom, anchor = torch.zeros(w.n, device="cuda"), torch.zeros(w.n, device="cuda")
+    wa_ref, pi_ref, b_ref = w.w0.astype(np.float64), np.zeros(w.n), np.zeros(w.n)
+    for outer in range(3):
+        Q.col(0).copy_(dev(wl.normal_vector(2, 300 + outer, w.n)))
+        alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, w.m)
+        evals, _ = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, w.k, w.l, V)
+        ctx.synchronize()
+        Vg = V.to_numpy().astype(np.float64)
+        fo.fosi_admm_begin(ctx, sig, pi, anchor, wa)
+        a_ref, wa_ref = oracle.admm_begin(wa_ref, pi_ref, sig)
+        for t in range(4):
+            grad = w.grad(4 * outer + t)
+            fo.fosi_step(ctx, V, w.k + w.l, evals, dev(grad), pi, mom, wa, sp)
+            wa_ref, b_ref = oracle.fosi_step(wa_ref, grad, Vg, evals, b_ref, float(p.alpha), float(p.lr),
+                                             float(p.momentum), sig, pi=pi_ref, curv_mode="abs")
+        fo.fosi_admm_end(ctx, sig, anchor, wa, pi)
+        pi_ref = oracle.admm_end(a_ref, wa_ref, pi_ref, sig)
+        ctx.synchronize()
+        assert rel_l2(anchor.cpu().numpy(), a_ref) <= STEP_RTOL, outer
+        assert rel_l2(wa.cpu().numpy(), wa_ref) <= STEP_RTOL, outer
+        assert rel_l2(mom.cpu().numpy(), b_ref) <= 5 * STEP_RTOL, outer
+        # the multiplier is sigma times a difference of two stored fp32 vectors of size |w|: its error is measured
+        # against sigma * |w| * 2^-24, the rounding of those vectors, not against its own (small) size
+        err = np.linalg.norm(pi.cpu().numpy().astype(np.float64) - pi_ref)
+        assert err <= 8 * sig * np.linalg.norm(wa_ref) * 2.0 ** -24 * (outer + 1), (outer, err)
+        if outer == 0:
+            # first outer from pi = 0: the anchor is the start point and pi = sigma (w_a - w)
+            assert rel_l2(a_ref, w.w0.astype(np.float64)) == 0.0
+            assert np.allclose(pi_ref, sig * (wa_ref - a_ref), rtol=0, atol=1e-18)
+    op.close()
+
+
 # ------------------------------------------------------------------ error paths (host checks; every kernel exits normally)
 def test_argument_errors(fo, ctx):
     w = wl.planted_workload(1, n=256)
