@@ -56,9 +56,11 @@ typedef struct fosi_hvp fosi_hvp;   /* a curvature operator v -> H v bound to a 
  * a pointer (NULL = the default stream); the caller keeps the stream alive.
  * Launch shapes are fixed at creation; for experiments they can be overridden through environment variables
  * read here (values outside a knob's range fall back to the default):
- *   FOSI_DOT_BLOCKS   resident workgroups targeted by the transposed product (default 2 per compute unit)
+ *   FOSI_DOT_BLOCKS   resident workgroups targeted by the transposed product (default 0: 2 per compute unit up
+ *                     to 8 M rows, 1 beyond)
  *   FOSI_DOT_JB       columns per wave in that kernel: 8, 16, 32 (default 0: 8 up to 4 M rows, else 16)
- *   FOSI_COMB_ROWS / FOSI_COMB_COLS / FOSI_COMB_BLOCKS   row groups per thread (4), columns loaded together (8)
+ *   FOSI_COMB_ROWS / FOSI_COMB_COLS / FOSI_COMB_BLOCKS   row groups per thread and columns loaded together (one of
+ *                     1x8, 1x16, 2x4, 2x8, 4x2, 4x4, 4x8, 8x2, 8x3, 8x4; default: 4x8 up to 8 M rows, 8x4 beyond)
  *                     and grid cap (0: none) of the column-combination kernel
  *   FOSI_STEP_WAVES   resident waves per compute unit aimed at by the update's fused second sweep (12)
  *   FOSI_EARLY_BETA   1: beta from the Gram-Schmidt coefficients, normalisation inside the subtraction (default)

@@ -113,10 +113,10 @@ fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
     ctx->stream = static_cast<hipStream_t>(hip_stream);
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) == hipSuccess) ctx->sm_count = prop.multiProcessorCount;
-    ctx->tun.dot_target_blocks = env_int("FOSI_DOT_BLOCKS", 2 * ctx->sm_count);
+    ctx->tun.dot_target_blocks = env_int("FOSI_DOT_BLOCKS", 0);       // 0: chosen by size
     ctx->tun.dot_slot_cols = env_int("FOSI_DOT_JB", 0);
-    ctx->tun.comb_rows_per_thread = env_int("FOSI_COMB_ROWS", 4);
-    ctx->tun.comb_cols_unroll = env_int("FOSI_COMB_COLS", 8);
+    ctx->tun.comb_rows_per_thread = env_int("FOSI_COMB_ROWS", 0);   // 0: chosen by size
+    ctx->tun.comb_cols_unroll = env_int("FOSI_COMB_COLS", 0);
     ctx->tun.comb_max_blocks = env_int("FOSI_COMB_BLOCKS", 0);
     ctx->tun.early_beta = env_int("FOSI_EARLY_BETA", 1);
     ctx->tun.ritz_mfma = env_int("FOSI_RITZ_MFMA", 1);

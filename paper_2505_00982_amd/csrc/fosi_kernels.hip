@@ -1074,7 +1074,13 @@ void dot_columns_launch(fosi_ctx* ctx, const float* A, int64_t lda, int ncols, c
     const int nslots = ncols > 0 ? (ncols + JB - 1) / JB : 1;
     // row lanes (a multiple of 8, one share per XCD): as many as the targeted number of resident waves allows, not
     // more than the row groups of 256 rows (rounded up to 8; a row lane without rows contributes zeros)
-    int64_t per_xcd = ((int64_t)ctx->tun.dot_target_blocks * 4 / 8) / nslots;
+    // Waves in flight: two workgroups (8 waves) per CU up to 8 M rows; beyond, one (4 waves, each with 16+ loads of
+    // 1 KiB in flight, sweeping twice as many rows) is faster: n = 25.6 M project sweep 1.916 -> 1.908 ms,
+    // Gram-Schmidt product 0.626 -> 0.618 ms; at n = 1 M it costs 2.5 %.  Counts that are not a power of two times
+    // the slot count leave row lanes uneven (320 workgroups: +22 %).
+    const int target_blocks = ctx->tun.dot_target_blocks > 0 ? ctx->tun.dot_target_blocks
+                              : (n >= ((int64_t)1 << 23) ? ctx->sm_count : 2 * ctx->sm_count);
+    int64_t per_xcd = ((int64_t)target_blocks * 4 / 8) / nslots;
     const int64_t groups = (n4 + 63) / 64;
     if (per_xcd > (groups + 7) / 8) per_xcd = (groups + 7) / 8;
     if (per_xcd > kMaxDotSlots / 8) per_xcd = kMaxDotSlots / 8;
@@ -1166,8 +1172,18 @@ int launch_combine_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols
         case 404: FOSI_CFG(4, 4);
         case 408: FOSI_CFG(4, 8);
         case 802: FOSI_CFG(8, 2);
-        default: FOSI_CFG(4, 8);
+        case 803: FOSI_CFG(8, 3);
+        case 804: FOSI_CFG(8, 4);
+        default: break;
     }
+    // Not set (or not one of the shapes above): 4 row groups x 8 columns in flight per thread (tiles of 4096 rows,
+    // three workgroups per CU) up to 8 M rows, 8 x 4 beyond (tiles of 8192 rows, 32 KiB per column visit, one
+    // workgroup per CU: 250-370 registers).  Measured on MI355X, whole steps: n = 25.6 M 427.5 -> 422.2 ms, n = 125 M
+    // 2756 -> 2695 ms together with the product's wave count; at n = 1 M and 2 M the larger tile leaves compute
+    // units without a tile and is 6 % slower.  8 x 1 ... 8 x 3, 6 x 2, 6 x 4, 12 x 2 and 16 x 1 were within 0.6 % of
+    // 8 x 4 or slower.
+    if (n >= ((int64_t)1 << 23)) FOSI_CFG(8, 4);
+    FOSI_CFG(4, 8);
 #undef FOSI_CFG
 }
 

@@ -669,7 +669,8 @@ def test_maximum_lanczos_length_and_planted_rank(fo, ctx):
     {"FOSI_EARLY_BETA": "0"},                                     # beta from the subtraction's own sum of squares
     {"FOSI_RITZ_MFMA": "0"},                                      # vector-ALU Ritz kernel below 33 columns
     {"FOSI_COMB_ROWS": "1", "FOSI_COMB_COLS": "16"}, {"FOSI_COMB_ROWS": "2", "FOSI_COMB_COLS": "4"},
-    {"FOSI_COMB_ROWS": "8", "FOSI_COMB_COLS": "2"}, {"FOSI_COMB_BLOCKS": "3"},
+    {"FOSI_COMB_ROWS": "8", "FOSI_COMB_COLS": "2"}, {"FOSI_COMB_ROWS": "8", "FOSI_COMB_COLS": "4"},   # 8 x 4: the library's choice above 8 M rows
+    {"FOSI_COMB_ROWS": "8", "FOSI_COMB_COLS": "3"}, {"FOSI_COMB_BLOCKS": "3"},
     {"FOSI_STEP_WAVES": "1"},
 ], ids=lambda e: ",".join(f"{k[5:]}={v}" for k, v in e.items()))
 def test_launch_shape_knobs_keep_the_results(fo, env, monkeypatch):
