@@ -1176,13 +1176,22 @@ int launch_combine_columns(fosi_ctx* ctx, const float* A, int64_t lda, int ncols
         case 804: FOSI_CFG(8, 4);
         default: break;
     }
-    // Not set (or not one of the shapes above): 4 row groups x 8 columns in flight per thread (tiles of 4096 rows,
-    // three workgroups per CU) up to 8 M rows, 8 x 4 beyond (tiles of 8192 rows, 32 KiB per column visit, one
-    // workgroup per CU: 250-370 registers).  Measured on MI355X, whole steps: n = 25.6 M 427.5 -> 422.2 ms, n = 125 M
-    // 2756 -> 2695 ms together with the product's wave count; at n = 1 M and 2 M the larger tile leaves compute
-    // units without a tile and is 6 % slower.  8 x 1 ... 8 x 3, 6 x 2, 6 x 4, 12 x 2 and 16 x 1 were within 0.6 % of
-    // 8 x 4 or slower.
-    if (n >= ((int64_t)1 << 23)) FOSI_CFG(8, 4);
+    // Not set (or not one of the shapes above): two shapes.  Small: 4 row groups x 8 columns in flight per thread,
+    // tiles of 4096 rows, three workgroups per CU.  Large: 8 x 4, tiles of 8192 rows (32 KiB per column visit), one
+    // workgroup per CU (250-370 registers).  The large shape streams 1.5-3 % faster per byte (MI355X, whole steps:
+    // n = 25.6 M 427.5 -> 422.2 ms, n = 125 M 2756 -> 2695 ms together with the product's wave count; n = 2-12 M
+    // 0.5-3 %), but with one workgroup per CU its tiles come in rounds of one per CU: at n = 1 M half the CUs would
+    // get no tile (6 % slower), and a count just above a whole number of rounds wastes most of a round.  So: large
+    // when there are many rounds (the hardware's dispatch evens them out), or when its rounds cost no more than the
+    // small shape's half-size tiles spread over the CUs (2 % dearer per byte).
+    // Other shapes measured at n = 25.6 M: 8 x 1 ... 8 x 3, 6 x 2, 6 x 4, 12 x 2, 16 x 1 within 0.6 % of 8 x 4 or slower.
+    {
+        const int64_t cus = ctx->sm_count > 0 ? ctx->sm_count : 1;
+        const int64_t large_tiles = (n + 8191) / 8192;
+        const int64_t large_rounds = (large_tiles + cus - 1) / cus;              // in large-tile times
+        const int64_t small_halves = (2 * large_tiles + cus - 1) / cus;          // half-size tiles on the busiest CU
+        if (large_rounds >= 8 || 100 * large_rounds <= 51 * small_halves) FOSI_CFG(8, 4);
+    }
     FOSI_CFG(4, 8);
 #undef FOSI_CFG
 }
