@@ -1,15 +1,27 @@
-"""Algorithm 1 (Lanczos with full Gram-Schmidt orthogonalisation), float64.
+"""Algorithm 1 (Lanczos with full Gram-Schmidt orthogonalisation) and its
+row-sharded form (Algorithm 2), float64.  Test infrastructure only.
 
 Notation: the paper's D (n x m, orthonormal columns) is `Q` here and its
-tridiagonal B is held as the two diagonals `alpha` (B[i,i]) and `beta`
-(B[i+1,i] = B[i,i+1]).  Test infrastructure only.
+tridiagonal B is held as a band: `alpha` (B[i,i]) and `beta`
+(B[i+1,i] = B[i,i+1]).
+
+How the code is organised.  One trip of the algorithm is "apply the operator
+to the newest column, remove from the result its components along every column
+built so far, normalise what is left and append it".  The only places where
+the rows of D meet are inner products, so the driver takes the two reductions
+(`inner`: D^T h, `sqnorm`: ||h||^2) as arguments: the single-device algorithm
+passes the plain ones, the row-sharded algorithm passes sums of per-block
+partial results (its all-reduces), and both share everything else.
 
 Readings of points the paper leaves open (all listed in the design notes):
   * Algorithm 1 writes column m+1 of D and entry B[m+1,m] in its last trip while
     declaring D with m columns: Q gets m+1 columns, B stays m x m, and the last
     beta is kept as the residual norm.
   * The Gram-Schmidt line subtracts the projections onto *all* columns filled
-    so far (columns that are still zero contribute nothing).
+    so far (columns that are still zero contribute nothing).  `passes` repeats
+    that line; the diagonal entry is then the sum of the coefficients removed
+    along the current column (Eq. 5 names the first of them; the later ones
+    vanish in exact arithmetic).
   * Breakdown (the new direction vanishes because the Krylov space is
     exhausted) is not mentioned: the iteration stops when
     ||h after orthogonalisation|| <= breakdown_tol * ||H v_i||, and B is the
@@ -18,11 +30,19 @@ Readings of points the paper leaves open (all listed in the design notes):
     at an exhausted Krylov space (about 1e-8 in float64 after the error of the
     recurrence has been amplified over some thirty steps).
   * v_1 is handed in (a seeded Gaussian vector) and normalised here.
+  * The paper does not state the precision in which D is kept.  `storage`
+    (None = float64) names the format of the *stored* vectors: with
+    `storage=numpy.float32` every vector the algorithm writes to memory -- the
+    operator's output h and each new column of D -- is rounded to that format
+    once, while all arithmetic stays float64.  This is what a device
+    implementation with fp32 vectors and wide accumulators does, and it is how
+    the tests find out which deviations from the float64 run belong to the
+    storage format rather than to a particular kernel.
 """
 from __future__ import annotations
 
 from dataclasses import dataclass
-from typing import Callable
+from typing import Callable, Optional
 
 import numpy as np
 
@@ -36,31 +56,49 @@ class LanczosResult:
     hnorm: np.ndarray    # m float64, ||H v_i|| (used by the breakdown rule)
 
 
-def lanczos(hvp: Callable[[np.ndarray], np.ndarray], v1: np.ndarray, m: int,
-            passes: int = 1, breakdown_tol: float = 1e-6) -> LanczosResult:
+def _stored_as(storage) -> Callable[[np.ndarray], np.ndarray]:
+    """What writing a vector to memory does to it: nothing (float64), or one rounding to `storage`."""
+    if storage is None or np.dtype(storage) == np.float64:
+        return lambda x: x
+    fmt = np.dtype(storage)
+    return lambda x: np.asarray(x, dtype=np.float64).astype(fmt).astype(np.float64)
+
+
+def _remove_components(filled: np.ndarray, h: np.ndarray, inner) -> tuple:
+    """The Gram-Schmidt line once: h minus its projections onto the columns of `filled`.
+    Returns (new h, coefficient that was removed along the last column)."""
+    coeff = inner(filled, h)                      # D^T h
+    return h - filled @ coeff, coeff[-1]
+
+
+def _run(hvp, v1: np.ndarray, m: int, passes: int, breakdown_tol: float, storage, inner, sqnorm) -> LanczosResult:
+    keep = _stored_as(storage)
     v1 = np.asarray(v1, dtype=np.float64)
     n = v1.shape[0]
     Q = np.zeros((n, m + 1), order="F")
-    alpha = np.zeros(m)
-    beta = np.zeros(m)
+    band = np.zeros((2, m))                       # row 0: diagonal of B, row 1: its off-diagonal
     hnorm = np.zeros(m)
-    # initialisation: first column is the normalised random vector
-    Q[:, 0] = v1 / np.linalg.norm(v1)
+    Q[:, 0] = keep(v1 / np.sqrt(sqnorm(v1)))      # first column: the normalised random vector
     m_eff = m
     for i in range(m):
-        v_i = Q[:, i]
-        h = np.asarray(hvp(v_i), dtype=np.float64)
-        hnorm[i] = np.linalg.norm(h)
-        alpha[i] = h @ v_i                               # B[i,i] (Eq. 5)
-        for _ in range(passes):                          # Gram-Schmidt against all filled columns
-            D = Q[:, : i + 1]
-            h = h - D @ (D.T @ h)
-        beta[i] = np.linalg.norm(h)                      # B[i+1,i] = B[i,i+1] (Eq. 6)
-        if not beta[i] > breakdown_tol * hnorm[i]:
+        h = keep(np.asarray(hvp(Q[:, i]), dtype=np.float64))
+        hnorm[i] = np.sqrt(sqnorm(h))
+        for _ in range(passes):                   # against all filled columns; Eq. 5: the part along v_i is B[i,i]
+            h, along_current = _remove_components(Q[:, : i + 1], h, inner)
+            band[0, i] += along_current
+        band[1, i] = np.sqrt(sqnorm(h))           # B[i+1,i] = B[i,i+1] (Eq. 6)
+        if not band[1, i] > breakdown_tol * hnorm[i]:
             m_eff = i + 1
             break
-        Q[:, i + 1] = h / beta[i]
-    return LanczosResult(Q=Q, alpha=alpha, beta=beta, m_eff=m_eff, hnorm=hnorm)
+        Q[:, i + 1] = keep(h / band[1, i])
+    return LanczosResult(Q=Q, alpha=band[0], beta=band[1], m_eff=m_eff, hnorm=hnorm)
+
+
+def lanczos(hvp: Callable[[np.ndarray], np.ndarray], v1: np.ndarray, m: int,
+            passes: int = 1, breakdown_tol: float = 1e-6, storage: Optional[type] = None) -> LanczosResult:
+    """Algorithm 1 on one device: the reductions are the plain ones."""
+    return _run(hvp, v1, m, passes, breakdown_tol, storage,
+                inner=lambda D, h: D.T @ h, sqnorm=lambda h: float(h @ h))
 
 
 def tridiagonal(alpha: np.ndarray, beta: np.ndarray, m_eff: int) -> np.ndarray:
@@ -72,36 +110,27 @@ def tridiagonal(alpha: np.ndarray, beta: np.ndarray, m_eff: int) -> np.ndarray:
     return B
 
 
-def lanczos_row_sharded(hvp: Callable[[np.ndarray], np.ndarray], v1: np.ndarray, m: int, C: int,
-                        breakdown_tol: float = 1e-6) -> LanczosResult:
-    """Algorithm 2 emulated in one process: C virtual devices each own a
-    contiguous row block [s_c, e_c) of D and of h.  The collectives become
-    plain Python: all_gather = concatenation of the blocks, all_reduce = sum of
-    the per-device partial results.  Returns the same structure as `lanczos`,
-    with Q assembled from the blocks."""
-    v1 = np.asarray(v1, dtype=np.float64)
-    n = v1.shape[0]
+def row_blocks(n: int, C: int) -> list:
+    """C contiguous row ranges [s_c, e_c) covering 0..n (the virtual devices of Algorithm 2)."""
     edges = np.linspace(0, n, C + 1).astype(int)
-    blocks = [slice(edges[c], edges[c + 1]) for c in range(C)]
-    v1 = v1 / np.linalg.norm(v1)                        # same seed, same vector on every device
-    D = [np.zeros((b.stop - b.start, m + 1)) for b in blocks]
-    for c, b in enumerate(blocks):
-        D[c][:, 0] = v1[b]
-    alpha = np.zeros(m)
-    beta = np.zeros(m)
-    hnorm = np.zeros(m)
-    m_eff = m
-    for i in range(m):
-        v_i = np.concatenate([D[c][:, i] for c in range(C)])            # all_gather
-        h = np.asarray(hvp(v_i), dtype=np.float64)
-        hnorm[i] = np.linalg.norm(h)
-        alpha[i] = h @ v_i
-        mvec = sum(D[c][:, : i + 1].T @ h[b] for c, b in enumerate(blocks))   # all_reduce
-        h_loc = [h[b] - D[c][:, : i + 1] @ mvec for c, b in enumerate(blocks)]
-        beta[i] = np.sqrt(sum(float(x @ x) for x in h_loc))             # all_reduce
-        if not beta[i] > breakdown_tol * hnorm[i]:
-            m_eff = i + 1
-            break
-        for c in range(C):
-            D[c][:, i + 1] = h_loc[c] / beta[i]
-    return LanczosResult(Q=np.concatenate(D, axis=0), alpha=alpha, beta=beta, m_eff=m_eff, hnorm=hnorm)
+    return [slice(int(edges[c]), int(edges[c + 1])) for c in range(C)]
+
+
+def lanczos_row_sharded(hvp: Callable[[np.ndarray], np.ndarray], v1: np.ndarray, m: int, C: int,
+                        passes: int = 1, breakdown_tol: float = 1e-6, storage: Optional[type] = None) -> LanczosResult:
+    """Algorithm 2 emulated in one process: C virtual devices each own a
+    contiguous row block of D and of h.  A device can only form the part of an
+    inner product that its own rows contribute; the all-reduce of the algorithm
+    adds those parts, device 0 first.  The operator sees the whole current
+    vector (the algorithm's all-gather is the identity in one address space).
+    Same result structure as `lanczos`."""
+    blocks = row_blocks(np.asarray(v1).shape[0], C)
+
+    def all_reduced_inner(D, h):
+        partial = [D[b].T @ h[b] for b in blocks]            # what each device computes from its rows
+        return np.sum(partial, axis=0)                       # all-reduce
+
+    def all_reduced_sqnorm(h):
+        return float(sum(float(h[b] @ h[b]) for b in blocks))  # all-reduce of the local squared norms
+
+    return _run(hvp, v1, m, passes, breakdown_tol, storage, inner=all_reduced_inner, sqnorm=all_reduced_sqnorm)

@@ -43,29 +43,32 @@ HVP_PINS = [pins.test_hvp_planted_matches_dense_matrix, pins.test_hvp_planted_ei
 # (module, function, text in the function's source, replacement, pins that must notice)
 MUTANTS = [
     # ---- Algorithm 1
-    ("oracle.lanczos", "lanczos", "Q[:, 0] = v1 / np.linalg.norm(v1)", "Q[:, 0] = v1", LANCZOS_PINS),
-    ("oracle.lanczos", "lanczos", "alpha[i] = h @ v_i", "alpha[i] = h @ h", LANCZOS_PINS),
-    ("oracle.lanczos", "lanczos", "alpha[i] = h @ v_i", "alpha[i] = h @ Q[:, max(i - 1, 0)]", LANCZOS_PINS),
-    ("oracle.lanczos", "lanczos", "D = Q[:, : i + 1]", "D = Q[:, i: i + 1]", LANCZOS_PINS),      # only the current column
-    ("oracle.lanczos", "lanczos", "D = Q[:, : i + 1]", "D = Q[:, : i]", LANCZOS_PINS),            # current column left out
-    ("oracle.lanczos", "lanczos", "h = h - D @ (D.T @ h)", "h = h + D @ (D.T @ h)", LANCZOS_PINS),
-    ("oracle.lanczos", "lanczos", "h = h - D @ (D.T @ h)", "h = h - D @ (D.T @ v_i)", LANCZOS_PINS),
-    ("oracle.lanczos", "lanczos", "beta[i] = np.linalg.norm(h)", "beta[i] = h @ h", LANCZOS_PINS),
-    ("oracle.lanczos", "lanczos", "Q[:, i + 1] = h / beta[i]", "Q[:, i + 1] = h", LANCZOS_PINS),
-    ("oracle.lanczos", "lanczos", "Q[:, i + 1] = h / beta[i]", "Q[:, i + 1] = h / alpha[i]", LANCZOS_PINS),
-    ("oracle.lanczos", "lanczos", "if not beta[i] > breakdown_tol * hnorm[i]:", "if not beta[i] > 0.0:", LANCZOS_PINS),
-    ("oracle.lanczos", "lanczos", "m_eff = i + 1\n", "m_eff = i\n", LANCZOS_PINS),
+    ("oracle.lanczos", "_run", "Q[:, 0] = keep(v1 / np.sqrt(sqnorm(v1)))", "Q[:, 0] = keep(v1)", LANCZOS_PINS),
+    ("oracle.lanczos", "_run", "band[0, i] += along_current", "band[0, i] += float(h @ h)", LANCZOS_PINS),
+    ("oracle.lanczos", "_remove_components", "coeff[-1]", "coeff[max(len(coeff) - 2, 0)]", LANCZOS_PINS),   # previous column's
+    ("oracle.lanczos", "_run", "Q[:, : i + 1], h, inner", "Q[:, i: i + 1], h, inner", LANCZOS_PINS),      # only the current column
+    ("oracle.lanczos", "_run", "Q[:, : i + 1], h, inner", "Q[:, : max(i, 1)], h, inner", LANCZOS_PINS),   # current column left out
+    ("oracle.lanczos", "_remove_components", "h - filled @ coeff", "h + filled @ coeff", LANCZOS_PINS),
+    ("oracle.lanczos", "_remove_components", "coeff = inner(filled, h)", "coeff = inner(filled, filled[:, -1])", LANCZOS_PINS),
+    ("oracle.lanczos", "_remove_components", "h - filled @ coeff", "h - filled @ coeff[::-1]", LANCZOS_PINS),
+    ("oracle.lanczos", "_run", "band[1, i] = np.sqrt(sqnorm(h))", "band[1, i] = sqnorm(h)", LANCZOS_PINS),
+    ("oracle.lanczos", "_run", "Q[:, i + 1] = keep(h / band[1, i])", "Q[:, i + 1] = keep(h)", LANCZOS_PINS),
+    ("oracle.lanczos", "_run", "Q[:, i + 1] = keep(h / band[1, i])", "Q[:, i + 1] = keep(h / band[0, i])", LANCZOS_PINS),
+    ("oracle.lanczos", "_run", "if not band[1, i] > breakdown_tol * hnorm[i]:", "if not band[1, i] > 0.0:", LANCZOS_PINS),
+    ("oracle.lanczos", "_run", "m_eff = i + 1\n", "m_eff = i\n", LANCZOS_PINS),
+    ("oracle.lanczos", "_run", "alpha=band[0], beta=band[1]", "alpha=band[1], beta=band[0]", LANCZOS_PINS),
+    ("oracle.lanczos", "lanczos", "inner=lambda D, h: D.T @ h", "inner=lambda D, h: np.abs(D).T @ h", LANCZOS_PINS),
     ("oracle.lanczos", "tridiagonal", "off = np.asarray(beta[: m_eff - 1]", "off = np.asarray(beta[1: m_eff]", LANCZOS_PINS),
     ("oracle.lanczos", "tridiagonal", "np.diag(off, 1) + np.diag(off, -1)", "np.diag(off, 1)", LANCZOS_PINS),
     ("oracle.lanczos", "tridiagonal", "B = np.diag(np.asarray(alpha[:m_eff]", "B = np.diag(np.asarray(alpha[:m_eff][::-1]",
      LANCZOS_PINS),
     # ---- Algorithm 2 emulation
-    ("oracle.lanczos", "lanczos_row_sharded", "beta[i] = np.sqrt(sum(float(x @ x) for x in h_loc))",
-     "beta[i] = sum(np.sqrt(float(x @ x)) for x in h_loc)", SHARDED_PINS),
-    ("oracle.lanczos", "lanczos_row_sharded", "mvec = sum(D[c][:, : i + 1].T @ h[b] for c, b in enumerate(blocks))",
-     "mvec = D[0][:, : i + 1].T @ h[blocks[0]]", SHARDED_PINS),                                     # no all-reduce
-    ("oracle.lanczos", "lanczos_row_sharded", "D[c][:, i + 1] = h_loc[c] / beta[i]",
-     "D[c][:, i + 1] = h_loc[c] / np.linalg.norm(h_loc[c])", SHARDED_PINS),                         # local norm
+    ("oracle.lanczos", "lanczos_row_sharded", "return float(sum(float(h[b] @ h[b]) for b in blocks))",
+     "return float(sum(np.sqrt(float(h[b] @ h[b])) for b in blocks)) ** 2", SHARDED_PINS),          # local norms added
+    ("oracle.lanczos", "lanczos_row_sharded", "return np.sum(partial, axis=0)", "return partial[0]", SHARDED_PINS),   # no all-reduce
+    ("oracle.lanczos", "lanczos_row_sharded", "float(h[b] @ h[b]) for b in blocks))",
+     "float(h[b] @ h[b]) for b in blocks[:1])) * len(blocks)", SHARDED_PINS),                       # local norm only
+    ("oracle.lanczos", "row_blocks", "int(edges[c + 1]))", "int(edges[c + 1]) - 1)", SHARDED_PINS),    # a row lost per device
     # ---- Eq. 8 and the selection after it
     ("oracle.ritz", "ritz", "top = np.arange(m_eff - 1, m_eff - 1 - k, -1)", "top = np.arange(m_eff - k, m_eff)", LANCZOS_PINS),
     ("oracle.ritz", "ritz", "top = np.arange(m_eff - 1, m_eff - 1 - k, -1)", "top = np.arange(m_eff - 2, m_eff - 2 - k, -1)",
@@ -85,7 +88,8 @@ MUTANTS = [
     ("oracle.step", "fosi_step", "else np.abs(a_hat) + sig", "else np.abs(a_hat + sig)", STEP_PINS),
     ("oracle.step", "fosi_step", "g_tilde, sig = g + np.asarray(pi, dtype=np.float64), float(sigma)",
      "g_tilde, sig = g - np.asarray(pi, dtype=np.float64), float(sigma)", STEP_PINS),
-    ("oracle.step", "fosi_step", "c = V.T @ g_tilde", "c = V.T @ g", STEP_PINS),
+    ("oracle.step", "fosi_step", "in_span = V @ (V.T @ g_tilde)", "in_span = V @ (V.T @ g)", STEP_PINS),
+    ("oracle.step", "fosi_step", "c = V.T @ in_span", "c = V.T @ (g_tilde - in_span)", STEP_PINS),
     ("oracle.step", "fosi_step", "x = g_tilde - g1", "x = g_tilde", STEP_PINS),
     ("oracle.step", "fosi_step", "x = g_tilde - g1", "x = g - g1", STEP_PINS),
     ("oracle.step", "fosi_step", "b_new = momentum * b + x", "b_new = momentum * (b + x)", STEP_PINS),
@@ -102,7 +106,8 @@ MUTANTS = [
     ("oracle.step", "fosi_step_adamw", "(1.0 - beta2) * x * x", "(1.0 - beta2) * x", ADAMW_PINS),
     ("oracle.step", "fosi_step_adamw", "(np.sqrt(v_hat) + eps)", "np.sqrt(v_hat + eps)", ADAMW_PINS),
     ("oracle.step", "fosi_step_adamw", "+ weight_decay * w)", "- weight_decay * w)", ADAMW_PINS),
-    ("oracle.step", "fosi_step_adamw", "x = g_tilde - V @ c", "x = g_tilde", ADAMW_PINS),
+    ("oracle.step", "fosi_step_adamw", "x = g_tilde - in_span", "x = g_tilde", ADAMW_PINS),
+    ("oracle.step", "fosi_step_adamw", "c = V.T @ in_span", "c = V.T @ (g_tilde - in_span)", ADAMW_PINS),
     ("oracle.step", "fosi_step_adamw", "delta2 = o - V @ (V.T @ o)", "delta2 = o", ADAMW_PINS),
     ("oracle.step", "fosi_step_adamw", "denom = a_hat + sig if curv_mode", "denom = a_hat if curv_mode", ADAMW_PINS),
     ("oracle.step", "fosi_step_adamw", "delta1 = -alpha * (V @ (c / denom))", "delta1 = alpha * (V @ (c / denom))", ADAMW_PINS),
