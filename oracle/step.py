@@ -40,13 +40,15 @@ def fosi_step(w: np.ndarray, g: np.ndarray, V: np.ndarray, evals: np.ndarray, mo
     else:
         g_tilde, sig = g + np.asarray(pi, dtype=np.float64), float(sigma)
 
-    # Delta_1: alpha-scaled Newton step inside span(V-hat)
-    c = V.T @ g_tilde
+    # Delta_1: alpha-scaled Newton step inside span(V-hat).  As printed (Eq. 4, Eq. 14) the inverse acts on
+    # V^T applied to the projected gradient V (V^T g~), not on V^T g~ itself.
+    in_span = V @ (V.T @ g_tilde)
+    c = V.T @ in_span
     denom = a_hat + sig if curv_mode == "signed" else np.abs(a_hat) + sig
     delta1 = -alpha * (V @ (c / denom))
 
     # Delta_2: base optimiser on the complement, re-projected
-    g1 = V @ c if g1_reading == "projected" else V @ (V.T @ g)
+    g1 = in_span if g1_reading == "projected" else V @ (V.T @ g)
     x = g_tilde - g1
     b_new = momentum * b + x
     o = -lr * b_new
@@ -74,10 +76,11 @@ def fosi_step_adamw(w: np.ndarray, g: np.ndarray, V: np.ndarray, evals: np.ndarr
         g_tilde, sig = g, 0.0
     else:
         g_tilde, sig = g + np.asarray(pi, dtype=np.float64), float(sigma)
-    c = V.T @ g_tilde
+    in_span = V @ (V.T @ g_tilde)                 # g_1 of Eq. 3 (with the dual variable added, Eq. 14)
+    c = V.T @ in_span                             # Eq. 4 / Eq. 14 as printed
     denom = a_hat + sig if curv_mode == "signed" else np.abs(a_hat) + sig
     delta1 = -alpha * (V @ (c / denom))
-    x = g_tilde - V @ c
+    x = g_tilde - in_span
     m_new = beta1 * np.asarray(exp_avg, dtype=np.float64) + (1.0 - beta1) * x
     v_new = beta2 * np.asarray(exp_avg_sq, dtype=np.float64) + (1.0 - beta2) * x * x
     m_hat = m_new / (1.0 - beta1 ** step_index)

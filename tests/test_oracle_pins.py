@@ -501,3 +501,24 @@ def test_second_pass_option_on_a_long_run():
     one = oracle.lanczos(hv, v1, m, passes=1)
     Q1 = one.Q[:, : one.m_eff]
     assert np.abs(Q1.T @ Q1 - np.eye(one.m_eff)).max() > 1e-6
+
+
+def test_newton_term_printed_and_simplified_forms_agree_on_an_fp32_basis():
+    """Eq. 4 / Eq. 14 print the Newton term with V^T applied to the projected gradient V (V^T g~); for orthonormal V
+    that is V^T g~.  The device uses the short form on a basis stored in fp32 (orthonormal to ~1e-7): the two
+    forms must then agree far inside the 1e-5 bar of the update."""
+    rng = np.random.default_rng(17)
+    n, r = 20000, 30
+    V = np.linalg.qr(rng.standard_normal((n, r)))[0].astype(np.float32).astype(np.float64)
+    assert 1e-9 < np.abs(V.T @ V - np.eye(r)).max() < 1e-6            # rounded: no longer exactly orthonormal
+    ev = np.concatenate([rng.uniform(1, 50, 20), -rng.uniform(0.5, 5, 10)])
+    w0, g, b0, pi = (rng.standard_normal(n) for _ in range(4))
+    alpha, lr, mu, sigma = 0.1, 0.01, 0.9, 5e-4
+    w1, b1 = oracle.fosi_step(w0, g, V, ev, b0, alpha, lr, mu, sigma, pi=pi)
+    gt = g + pi
+    c = V.T @ gt                                                     # short form
+    b_s = mu * b0 + gt - V @ c
+    o = -lr * b_s
+    w_s = w0 - alpha * (V @ (c / (ev + sigma))) + o - V @ (V.T @ o)
+    assert rel_l2(w_s - w0, w1 - w0) < 1e-6 and rel_l2(b_s, b1) < 1e-6
+    assert rel_l2(w_s - w0, w1 - w0) > 0.0                           # ... and they are two different computations
