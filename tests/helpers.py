@@ -88,3 +88,100 @@ def reduced_ritz_coefficients(G: np.ndarray, lam: np.ndarray, shift: float, m: i
     Cmat = np.linalg.solve(R, Qred @ S[:, sel])
     resid = abs(Hh[m, m - 1]) * np.abs(S[m - 1, sel]) if Hh.shape[0] > m else np.zeros(len(sel))
     return ev[sel], Cmat, resid, ev
+
+
+# ---------------------------------------------------------------------------------------------------
+# What fp32 storage of the Krylov basis does to the Ritz pairs (CPU emulation with the oracle)
+# ---------------------------------------------------------------------------------------------------
+
+def reduced_problem(G: np.ndarray, lam: np.ndarray, shift: float):
+    """The planted operator restricted to span([U, v1]), from the Gram matrix G of [U, v1] alone: with
+    [U, v1] = Bs R (R the transposed Cholesky factor of G, Bs orthonormal) the operator acts on Bs-coordinates as
+    M + shift I, M = R_u diag(lam) R_u^T, and the start vector is the normalised last column of R.
+    Returns (M, z, R)."""
+    r = G.shape[0] - 1
+    R = np.linalg.cholesky(np.asarray(G, dtype=np.float64)).T
+    Ru = R[:, :r]
+    M = Ru @ np.diag(np.asarray(lam, dtype=np.float64)) @ Ru.T
+    z = R[:, r] / np.linalg.norm(R[:, r])
+    return M, z, R
+
+
+def planted_embedding(M: np.ndarray, z: np.ndarray, n_rows: int, seed: int):
+    """An n_rows-row planted operator U' diag(lam') U'^T (+ shift I) and a start vector whose restriction to
+    span([U', v1']) is exactly (M, z): a seeded random orthonormal basis Bo carries the small problem into
+    n_rows dimensions.  Two embeddings of the same (M, z) produce the same tridiagonal in exact arithmetic; they
+    differ in how their vectors round.  Returns (U', lam', v1', Bo)."""
+    d = M.shape[0]
+    rng = np.random.default_rng([250500982, 77, int(seed)])
+    Bo = np.linalg.qr(rng.standard_normal((int(n_rows), d)))[0]
+    ev, W = np.linalg.eigh(M)
+    keep = np.argsort(-np.abs(ev))[: d - 1]            # M has rank d - 1: drop its (numerically) zero eigenvalue
+    return Bo @ W[:, keep], ev[keep], Bo @ z, Bo
+
+
+def _sines(A_ref: np.ndarray, B_test: np.ndarray) -> np.ndarray:
+    A = np.linalg.qr(A_ref)[0]
+    B = np.linalg.qr(B_test)[0]
+    return np.linalg.svd(B - A @ (A.T @ B), compute_uv=False)
+
+
+def storage_emulation(G: np.ndarray, lam: np.ndarray, shift: float, m: int, k: int, l: int,
+                      n_rows: int = 1 << 16, seed: int = 0, storage=np.float32, passes: int = 2) -> dict:
+    """Runs the oracle's Lanczos recurrence and Ritz extraction twice on one n_rows-row embedding of the planted
+    problem described by (G, lam, shift): once with float64 vectors and once with every stored vector (operator
+    output, new basis column) rounded to `storage` while the arithmetic stays float64.  The differences between
+    the two runs are what the storage format alone costs.  Per requested pair (k largest descending, then l
+    smallest ascending):
+        value_abs_err   |theta_storage - theta_float64|
+        out_norm        norm of the storage run's Ritz vector outside span([U, v1]) -- directions in the
+                        eigenspace of `shift`, which rounding feeds into the Krylov space
+        in_span_leave   how far the in-span part of that Ritz vector leaves the float64 run's block (top or
+                        bottom) of Ritz vectors
+    and per block the largest principal-angle sine, once for the whole vectors (`total_sin`) and once for their
+    in-span parts (`in_span_sin`); `dT[i]` = max(|d alpha_i|, |d beta_i|); `qtq` = max |Q^T Q - I| of the
+    storage run; `resid` = the float64 run's residual estimates, `evals` its Ritz values."""
+    import oracle
+    M, z, _ = reduced_problem(G, lam, shift)
+    U, lam_e, v1, Bo = planted_embedding(M, z, n_rows, seed)
+    op = lambda v: oracle.hvp_planted(U, lam_e, float(shift), v)
+    runs = {}
+    for name, fmt in (("float64", None), ("storage", storage)):
+        res = oracle.lanczos(op, v1, m, passes=passes, storage=fmt)
+        assert res.m_eff == m, "the emulation expects a run without breakdown"
+        runs[name] = (res, oracle.ritz(res.Q, res.alpha, res.beta, res.m_eff, k, l))
+    (r64, z64), (rst, zst) = runs["float64"], runs["storage"]
+    if storage is not None:                                   # the Ritz vectors are stored in the same format
+        zst.V = zst.V.astype(storage).astype(np.float64)
+    Y = Bo.T @ zst.V                                          # in-span coordinates of the storage run's Ritz vectors
+    out = zst.V - Bo @ Y
+    out_norm = np.linalg.norm(out, axis=0)
+    Cref = Bo.T @ z64.V
+    blocks = {"top": slice(0, k), "bottom": slice(k, k + l)}
+    total_sin, in_span_sin = {}, {}
+    in_span_leave = np.zeros(k + l)
+    for name, blk in blocks.items():
+        if blk.stop == blk.start:
+            continue
+        total_sin[name] = float(_sines(z64.V[:, blk], zst.V[:, blk]).max())
+        in_span_sin[name] = float(_sines(Cref[:, blk], Y[:, blk]).max())
+        A = np.linalg.qr(Cref[:, blk])[0]
+        Yb = Y[:, blk] / np.linalg.norm(Y[:, blk], axis=0)
+        in_span_leave[blk] = np.linalg.norm(Yb - A @ (A.T @ Yb), axis=0)
+    Qs = rst.Q[:, :m]
+    return dict(evals=z64.evals, resid=z64.resid, value_abs_err=np.abs(zst.evals - z64.evals), out_norm=out_norm,
+                in_span_leave=in_span_leave, total_sin=total_sin, in_span_sin=in_span_sin,
+                dT=np.maximum(np.abs(rst.alpha - r64.alpha), np.abs(rst.beta - r64.beta)),
+                qtq=float(np.abs(Qs.T @ Qs - np.eye(m)).max()),
+                alpha=r64.alpha.copy(), beta=r64.beta.copy(), all_evals=z64.all_evals)
+
+
+def synthetic_gram(r: int, n_true: int, seed: int) -> np.ndarray:
+    """Gram matrix of [U, v1] for an exactly orthonormal U (n_true x r) and a Gaussian v1 of n_true entries, drawn
+    directly: U^T v1 ~ N(0, I_r) and ||v1||^2 ~ chi^2 with n_true degrees of freedom (~ n_true)."""
+    rng = np.random.default_rng([250500982, 78, int(seed)])
+    a = rng.standard_normal(r)
+    G = np.eye(r + 1)
+    G[:r, r] = G[r, :r] = a
+    G[r, r] = a @ a + rng.chisquare(n_true - r)
+    return G

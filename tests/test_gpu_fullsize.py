@@ -8,6 +8,8 @@ needs only a small Gram matrix, accumulated in float64 by library matmuls),
 (b) invariants evaluated with library float64 operations, and (c) sampled rows
 of the Ritz vectors and of the update, which the oracle's formulas give one by
 one."""
+import json
+
 import numpy as np
 import pytest
 import torch
@@ -16,7 +18,7 @@ import oracle
 import workloads as wl
 from oracle.lanczos import tridiagonal
 from tests.helpers import (reduced_ritz_coefficients, reduced_tridiagonal_from_gram, rel_l2,
-                           sin_principal_angles)
+                           sin_principal_angles, storage_emulation)
 
 pytestmark = pytest.mark.gpu
 
@@ -57,6 +59,19 @@ def test_workload2_full_size_against_complete_oracle(fo, ctx):
     scale = np.abs(w.lam).max()
     assert np.max(np.abs(alpha - res.alpha)) < 1e-5 * scale and np.max(np.abs(beta - res.beta)) < 1e-5 * scale
     assert np.max(np.abs(evals - rz.evals) / np.abs(rz.evals)) <= 1e-4
+    # all m entries of the tridiagonal against the oracle run in the device's storage format (float64 arithmetic,
+    # every stored vector rounded to fp32, two passes): the device may differ from that run by the order of its
+    # float64 sums only, so the two must agree to 1e-3 of what the storage format itself costs
+    emu = oracle.lanczos(lambda v: oracle.hvp_planted(w.U, w.lam, float(w.shift), v), w.v1, w.m, passes=2,
+                         storage=np.float32)
+    cost = np.maximum(np.abs(emu.alpha - res.alpha), np.abs(emu.beta - res.beta))
+    diff = np.maximum(np.abs(alpha - emu.alpha), np.abs(beta - emu.beta))
+    print("[workload 2] |T_fp32storage - T_float64|", np.array2string(cost, precision=1, max_line_width=100000))
+    print("[workload 2] |T_gpu - T_fp32storage|   ", np.array2string(diff, precision=1, max_line_width=100000))
+    assert np.all(diff <= 1e-3 * np.maximum.accumulate(cost))
+    Qg = Q.to_numpy(w.m).astype(np.float64)
+    print("[workload 2] max |Q_gpu - Q_fp32storage| by column",
+          np.array2string(np.abs(Qg - emu.Q[:, : w.m]).max(axis=0), precision=1, max_line_width=100000))
     Vg = V.to_numpy().astype(np.float64)
     assert sin_principal_angles(rz.V[:, : w.k], Vg[:, : w.k]).max() < 1e-3
     assert sin_principal_angles(rz.V[:, w.k:], Vg[:, w.k:]).max() < 1e-3
@@ -96,6 +111,61 @@ def _gram_f64(M: torch.Tensor, n: int, extra: torch.Tensor, chunk: int = 1 << 20
     return G.cpu().numpy()
 
 
+def _deviation_from_reference(Vm, Um, v1, n, G, Cmat, k, l, chunk: int = 1 << 19) -> dict:
+    """Deviation of the device's Ritz vectors (rows of Vm) from V_ref = [U, v1] Cmat (orthonormal columns), by
+    library float64 operations on row chunks.  Returns the per-block principal-angle sines of the whole vectors
+    and of their parts inside span([U, v1]), the per-pair norm of the part outside that span, and per pair how far
+    the normalised in-span part leaves the reference block."""
+    r_v, r = Vm.shape[0], Um.shape[0]
+    dev_ = Vm.device
+    C_t = torch.from_numpy(np.ascontiguousarray(Cmat)).to(dev_)
+    R = np.linalg.cholesky(G).T                                   # [U, v1] = Bs R with orthonormal Bs
+    Rinv_t = torch.from_numpy(np.linalg.inv(R)).to(dev_)
+    blocks = {"top": slice(0, k), "bottom": slice(k, k + l)}
+
+    def basis(lo, hi):
+        return torch.cat([Um[:, lo:hi].double(), v1[lo:hi].double()[None, :]], dim=0).T     # rows x (r+1)
+
+    cross = torch.zeros(r + 1, r_v, dtype=torch.float64, device=dev_)                       # [U, v1]^T V
+    gram = torch.zeros(r_v, r_v, dtype=torch.float64, device=dev_)
+    for lo in range(0, n, chunk):
+        hi = min(n, lo + chunk)
+        Vc = Vm[:, lo:hi].double().T
+        cross += basis(lo, hi).T @ Vc
+        gram += Vc.T @ Vc
+    Y = Rinv_t.T @ cross                                          # Bs^T V: in-span coordinates
+    W = C_t.T @ cross                                             # V_ref^T V
+    e_out = torch.zeros(r_v, dtype=torch.float64, device=dev_)
+    e_blk = {name: torch.zeros(b.stop - b.start, b.stop - b.start, dtype=torch.float64, device=dev_)
+             for name, b in blocks.items()}
+    for lo in range(0, n, chunk):
+        hi = min(n, lo + chunk)
+        Bc = basis(lo, hi)
+        Vc = Vm[:, lo:hi].double().T
+        out = Vc - (Bc @ Rinv_t) @ Y
+        e_out += (out * out).sum(dim=0)
+        Vref = Bc @ C_t
+        for name, b in blocks.items():
+            if b.stop > b.start:
+                E = Vc[:, b] - Vref[:, b] @ W[b, b]
+                e_blk[name] += E.T @ E
+    gram_h, Y_h = gram.cpu().numpy(), Y.cpu().numpy()
+    Cref = R @ Cmat
+    res = {"out_norm": np.sqrt(e_out.cpu().numpy() / np.diag(gram_h)), "total_sin": {}, "in_span_sin": {},
+           "in_span_leave": np.zeros(r_v)}
+    for name, b in blocks.items():
+        if b.stop == b.start:
+            continue
+        L = np.linalg.cholesky(gram_h[b, b])
+        Li = np.linalg.inv(L)
+        res["total_sin"][name] = float(np.sqrt(max(0.0, np.linalg.eigvalsh(Li @ e_blk[name].cpu().numpy() @ Li.T).max())))
+        res["in_span_sin"][name] = float(sin_principal_angles(Cref[:, b], Y_h[:, b]).max())
+        A = np.linalg.qr(Cref[:, b])[0]
+        Yb = Y_h[:, b] / np.linalg.norm(Y_h[:, b], axis=0)
+        res["in_span_leave"][b] = np.linalg.norm(Yb - A @ (A.T @ Yb), axis=0)
+    return res
+
+
 def _full_size_planted(fo, ctx, cfg_id):
     from workloads.device import planted_workload_device
     w = planted_workload_device(cfg_id)
@@ -113,46 +183,67 @@ def _full_size_planted(fo, ctx, cfg_id):
     lam = w.lam.cpu().numpy().astype(np.float64)
     scale = np.abs(lam).max()
 
-    # (a) tridiagonal by the independent route
+    # Reference: the independent fp64 route (Householder reduction of the operator restricted to span([U, v1]), from
+    # the Gram matrix of [U, v1] accumulated by library float64 matmuls): the whole tridiagonal, the Ritz values and
+    # the Ritz vectors V_ref = [U, v1] Cmat.
+    # Bars: the tolerances the workloads state (Ritz values 1e-4 relative, principal angles 1e-3 rad) wherever an
+    # implementation with fp32 vectors can meet them, and otherwise twice what the CPU emulation of the storage
+    # format shows for THIS problem: the oracle's recurrence, float64 arithmetic, every stored vector rounded to
+    # fp32, run on two 65 536-row embeddings of this instance's restricted problem (tests/helpers.storage_emulation;
+    # tests/test_fp32_storage_emulation.py pins what that emulation finds and why).
     G = _gram_f64(w.U.view(r, w.ld), n, w.v1)
     a_ref, b_ref = reduced_tridiagonal_from_gram(G, lam, w.shift)
-    assert np.max(np.abs(alpha[:40] - a_ref[:40])) < 1e-5 * scale
-    assert np.max(np.abs(beta[:40] - b_ref[:40])) < 1e-5 * scale
-    # Ritz values and the reference Ritz vectors V_ref = [U, v1] C from the same independent route.  Pairs the
-    # fp64 reference has resolved (residual estimate <= 1e-2 |theta|) must agree to 1e-4 relative.  For the
-    # others the bar follows from the arithmetic: storing the basis in fp32 perturbs the operator by about
-    # u32 ||H|| per step, and an unresolved Ritz value can move by that much (4 u32 ||H|| allowed).
-    u32 = 2.0 ** -24
     ev_ref, Cmat, resid_ref, all_ref = reduced_ritz_coefficients(G, lam, w.shift, m, w.k, w.l)
-    resolved_all = resid_ref <= 1e-2 * np.abs(ev_ref)
+    emus = [storage_emulation(G, lam, w.shift, m, w.k, w.l, n_rows=1 << 16, seed=sd) for sd in (0, 1)]
+    emu = {key: np.maximum(emus[0][key], emus[1][key]) for key in ("value_abs_err", "out_norm", "in_span_leave", "dT")}
+    for key in ("total_sin", "in_span_sin"):
+        emu[key] = {b: max(e[key][b] for e in emus) for b in emus[0][key]}
+    assert np.max(np.abs(emus[0]["evals"] - ev_ref)) < 1e-8 * scale     # the emulation runs this very problem
+
+    # (a) the whole tridiagonal, all m entries of both diagonals: within twice the emulated deviation, taken as an
+    # envelope (largest deviation up to that index, since the recurrence carries its errors forward)
+    dT = np.maximum(np.abs(alpha - a_ref[:m]), np.abs(beta - b_ref[:m]))
+    envelope = np.maximum.accumulate(emu["dT"])
+    print(f"[workload {cfg_id}] |T_gpu - T_ref| by index {np.array2string(dT, precision=1, max_line_width=100000)}")
+    print(f"[workload {cfg_id}] emulated envelope    {np.array2string(envelope, precision=1, max_line_width=100000)}")
+    assert np.all(dT <= 2.0 * envelope), np.flatnonzero(dT > 2.0 * envelope)
+
+    # (b) Ritz values: 1e-4 relative, or twice the emulated error of that pair
     err = np.abs(evals - ev_ref)
-    print(f"[workload {cfg_id}] Ritz value relative errors {np.array2string(err / np.abs(ev_ref), precision=1)}; "
-          f"resolved by the reference: {resolved_all.sum()} of {r_v}")
+    resolved_all = resid_ref <= 1e-2 * np.abs(ev_ref)
+    print(f"[workload {cfg_id}] Ritz value errors {np.array2string(err, precision=1, max_line_width=100000)}; emulated "
+          f"{np.array2string(emu['value_abs_err'], precision=1, max_line_width=100000)}; resolved by the reference: "
+          f"{resolved_all.sum()} of {r_v}")
     assert resolved_all.sum() >= w.k
     assert np.max(err[resolved_all] / np.abs(ev_ref[resolved_all])) <= 1e-4
-    assert np.max(err) <= max(1e-4 * np.abs(ev_ref).min(), 4 * u32 * scale)
+    assert np.all(err <= np.maximum(1e-4 * np.abs(ev_ref), 2.0 * emu["value_abs_err"]))
+
+    # (c) Ritz vectors against V_ref, evaluated in float64 row chunk by row chunk (differences are formed element by
+    # element, so angles far below 1e-8 rad are resolved).  Three figures: the principal angles of each block as
+    # whole vectors; the norm of each Ritz vector's component outside span([U, v1]) -- rounding noise inside the
+    # (n - r)-dimensional eigenspace of the shift, where every direction is an exact eigenvector, so that part is
+    # valid but not unique; and the principal angles of the in-span parts, which are unique.
     Vm_ = V.buf[: r_v * w.ld].view(r_v, w.ld)
     Um_ = w.U.view(r, w.ld)
-    cross = torch.zeros(r_v, r + 1, dtype=torch.float64, device="cuda")
-    for lo in range(0, n, 1 << 20):
-        hi = min(n, lo + (1 << 20))
-        basis = torch.cat([Um_[:, lo:hi].double(), w.v1[lo:hi].double()[None, :]], dim=0)
-        cross += Vm_[:, lo:hi].double() @ basis.T
-    overlap = cross.cpu().numpy() @ Cmat                       # V_gpu^T V_ref, r_v x r_v
-    for name, blk, outside in (("top", slice(0, w.k), all_ref[m - 1 - w.k]), ("bottom", slice(w.k, r_v), all_ref[w.l])):
-        sv = np.linalg.svd(overlap[blk, blk], compute_uv=False)
-        sines = np.sqrt(np.maximum(0.0, 1.0 - np.minimum(sv, 1.0) ** 2))
-        # per pair: how far the GPU's Ritz vector leaves the reference block
-        leave = np.sqrt(np.maximum(0.0, 1.0 - np.sum(overlap[blk, blk] ** 2, axis=1)))
-        gap = np.min(np.abs(ev_ref[blk] - outside))
-        print(f"[workload {cfg_id}] {name} block: max sin(angle) {sines.max():.2e}; per pair {np.array2string(leave, precision=1)}; "
-              f"reference residuals {np.array2string(resid_ref[blk], precision=1)}; gap to the next Ritz value {gap:.3f}")
-        resolved = resid_ref[blk] <= 1e-2 * np.abs(ev_ref[blk])
-        # pairs the fp64 reference has resolved: the 1e-3 rad bar
-        assert leave[resolved].max() < 1e-3
-        # the whole block, unresolved pairs included: fp32 storage of the basis perturbs the operator by
-        # ~u32 ||H|| per step, and a Ritz vector moves by about that over the gap to the next Ritz value
-        assert sines.max() < max(1e-3, 16 * u32 * scale / gap)
+    dev_rep = _deviation_from_reference(Vm_, Um_, w.v1, n, G, Cmat, w.k, w.l)
+    record = {"workload": cfg_id, "n": n, "m": m, "evals_ref": ev_ref, "resid_ref": resid_ref, "value_abs_err": err,
+              "out_norm": dev_rep["out_norm"], "in_span_leave": dev_rep["in_span_leave"],
+              "total_sin": dev_rep["total_sin"], "in_span_sin": dev_rep["in_span_sin"], "dT": dT,
+              "emulated": emu}
+    print("PARITY_RECORD " + json.dumps(record, default=lambda o: np.asarray(o).tolist()))
+    for name in dev_rep["total_sin"]:
+        print(f"[workload {cfg_id}] {name} block: whole-vector sin {dev_rep['total_sin'][name]:.2e} (emulated "
+              f"{emu['total_sin'][name]:.2e}), in-span sin {dev_rep['in_span_sin'][name]:.2e} (emulated "
+              f"{emu['in_span_sin'][name]:.2e})")
+        assert dev_rep["total_sin"][name] <= max(1e-3, 2.0 * emu["total_sin"][name])
+        assert dev_rep["in_span_sin"][name] <= max(1e-3, 2.0 * emu["in_span_sin"][name])
+    print(f"[workload {cfg_id}] out-of-span norm per pair {np.array2string(dev_rep['out_norm'], precision=1, max_line_width=100000)}; "
+          f"emulated {np.array2string(emu['out_norm'], precision=1, max_line_width=100000)}")
+    # per pair; the emulation forms its Ritz vectors in float64 and rounds them once, the device accumulates the m
+    # products of V = Q S in fp32: up to u32 sqrt(m) more (measured ~1e-7, and only visible on the converged pairs)
+    assert np.all(dev_rep["out_norm"] <= 2.0 * emu["out_norm"] + 2.0 ** -24 * np.sqrt(m))
+    moved = np.hypot(dev_rep["out_norm"], dev_rep["in_span_leave"])
+    assert moved[resolved_all].max() < 1e-3                       # every pair the reference has resolved: the stated bar
 
     # (b) invariants with library float64 operations
     Qm = Q.buf[: (m + 1) * w.ld].view(m + 1, w.ld)

@@ -158,6 +158,19 @@ def test_cfg1_tridiagonal_and_breakdown(cfg1):
     assert np.max(np.abs(g["beta"][:16] - res_or.beta[:16])) < 2e-4 * 1e3
     a_h, b_h = reduced_tridiagonal(w.U, w.lam, w.shift, w.v1)
     assert np.max(np.abs(g["alpha"][:16] - a_h[:16])) < 2e-4 * 1e3
+    # Every entry up to the exhausted step.  The late entries are ill-determined (the recurrence amplifies any
+    # perturbation by ~1e7 over the 33 steps), so they are compared with the oracle run in the device's storage
+    # format -- float64 arithmetic, every stored vector rounded to fp32, two passes -- which differs from the device
+    # only in the order of its float64 sums: agreement to 1e-3 of what the storage format itself costs (envelope of
+    # |T_fp32storage - T_float64 route|), i.e. the kernels add nothing visible to the rounding of the stored vectors.
+    me = 33
+    b_h = np.concatenate([b_h, [0.0]])          # the Krylov space ends there: the next off-diagonal entry is zero
+    emu = oracle.lanczos(planted_op(w), w.v1, w.m, passes=2, storage=np.float32, breakdown_tol=0.0)
+    cost = np.maximum(np.abs(emu.alpha[:me] - a_h[:me]), np.abs(emu.beta[:me] - b_h[:me]))
+    diff = np.maximum(np.abs(g["alpha"][:me] - emu.alpha[:me]), np.abs(g["beta"][:me] - emu.beta[:me]))
+    print("[workload 1] |T_fp32storage - T_ref|", np.array2string(cost, precision=1, max_line_width=100000))
+    print("[workload 1] |T_gpu - T_fp32storage|", np.array2string(diff, precision=1, max_line_width=100000))
+    assert np.all(diff <= 1e-3 * np.maximum.accumulate(cost))
 
 
 def test_cfg1_orthonormal_basis(cfg1):
