@@ -242,6 +242,25 @@ fosi_status fosi_step(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int
                       const double* evals_host, const float* g_dev, const float* pi_dev,
                       float* mom_dev, float* w_dev, const fosi_step_params* p);
 
+/* The same update for callers that cannot allocate device memory: code running under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  No context is needed and nothing is allocated or freed, on the
+ * device or through any library: the scratch memory of the update's kernels (partial sums, coefficient vectors,
+ * Newton factors) is a static device array of FOSI_NOALLOC_SCRATCH_BYTES (about 2.1 MiB) that every GPU the
+ * library runs on holds until the process ends; its address on a GPU is looked up once, at the first call made
+ * with that GPU current (make that first call outside a capture).  Arguments, layout rules, arithmetic and results
+ * are those of fosi_step (same kernels, bit-identical output); hip_stream is a hipStream_t (NULL: the default
+ * stream) of the CURRENT device, to which all device pointers must belong.  Limits: r_v <= FOSI_NOALLOC_MAX_COLS,
+ * else FOSI_ERR_LIMIT; errors come back as the status alone (there is no context to hold a message).  All calls on
+ * one GPU share that GPU's array and it keeps the last call's contents (what must start from a defined value is
+ * rewritten by a kernel at the start of each call): calls that overlap on one GPU, from several streams or
+ * threads, race.  The divisors travel as a kernel argument, so evals_host is read before the call returns and no
+ * host-to-device copy is enqueued. */
+#define FOSI_NOALLOC_MAX_COLS       64
+#define FOSI_NOALLOC_SCRATCH_BYTES  2133760
+fosi_status fosi_step_noalloc(void* hip_stream, int64_t n, int r_v, const float* V_dev, int64_t ldv,
+                              const double* evals_host, const float* g_dev, const float* pi_dev,
+                              float* mom_dev, float* w_dev, const fosi_step_params* p);
+
 /* Same update with AdamW as the base first-order optimiser (the optimiser of the paper's experiments,
  * Section IV hyper-parameter paragraph).  The optimiser's descent vector is
  *   o = -lr ( m^ / (sqrt(v^) + eps) + weight_decay w ),

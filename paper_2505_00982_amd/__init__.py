@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     GRAPH_ON,
     fosi_ritz,
     fosi_step,
+    fosi_step_noalloc,
     fosi_step_adamw,
     AdamwParams,
     fosi_admm_begin,

@@ -27,7 +27,7 @@ EXPORTS = [
     "fosi_ctx_create", "fosi_ctx_destroy", "fosi_ctx_synchronize", "fosi_last_error", "fosi_status_string",
     "hvp_planted_create", "hvp_diag_create", "hvp_softmax_ggn_create", "hvp_softmax_ggn_bf16_create", "hvp_callback_create", "hvp_apply",
     "hvp_destroy", "fosi_workspace_bytes", "fosi_lanczos", "fosi_lanczos_begin", "fosi_lanczos_end", "fosi_graph_stats", "fosi_lanczos_second_passes",
-    "fosi_lanczos_row_sharded", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_step_adamw", "fosi_admm_begin",
+    "fosi_lanczos_row_sharded", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_step_noalloc", "fosi_step_adamw", "fosi_admm_begin",
     "fosi_admm_end", "fosi_profile_enable", "fosi_profile_reset", "fosi_profile_read",
 ]
 
@@ -97,6 +97,7 @@ def load_library() -> C.CDLL:
     lib.fosi_tridiag_eigh.argtypes = [C.c_int, dp, dp, dp, dp]
     lib.fosi_ritz.argtypes = [vp, i64, C.c_int, vp, i64, dp, dp, C.c_int, C.c_int, vp, i64, dp, dp]
     lib.fosi_step.argtypes = [vp, i64, C.c_int, vp, i64, dp, vp, vp, vp, vp, C.POINTER(_StepParams)]
+    lib.fosi_step_noalloc.argtypes = [vp, i64, C.c_int, vp, i64, dp, vp, vp, vp, vp, C.POINTER(_StepParams)]
     lib.fosi_step_adamw.argtypes = [vp, i64, C.c_int, vp, i64, dp, vp, vp, vp, vp, vp, vp, i64, C.POINTER(_AdamwParams)]
     lib.fosi_admm_begin.argtypes = [vp, i64, C.c_float, vp, vp, vp]
     lib.fosi_admm_end.argtypes = [vp, i64, C.c_float, vp, vp, vp]
@@ -368,6 +369,22 @@ def fosi_step(ctx: Context, V: Optional[ColMajor], r_v: int, evals: Optional[np.
     sp = _StepParams(p.alpha, p.lr, p.momentum, p.sigma, p.curv_mode)
     ctx.check(ctx.lib.fosi_step(ctx.handle, n, r_v, V.ptr if r_v > 0 else None, V.ld if r_v > 0 else 0, _dptr(ev),
                                 _ptr(g), _ptr(pi), _ptr(mom), _ptr(w), C.byref(sp)))
+
+
+def fosi_step_noalloc(stream: Optional[torch.cuda.Stream], V: Optional[ColMajor], r_v: int, evals: Optional[np.ndarray],
+                      g: torch.Tensor, pi: Optional[torch.Tensor], mom: torch.Tensor, w: torch.Tensor, p: StepParams):
+    """fosi_step without a context and without any allocation (static device scratch); r_v <= 64.  `stream` None:
+    torch's current stream on the current device."""
+    lib = load_library()
+    n = w.numel()
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    ev = np.ascontiguousarray(evals, dtype=np.float64) if r_v > 0 else np.zeros(1)
+    sp = _StepParams(p.alpha, p.lr, p.momentum, p.sigma, p.curv_mode)
+    st = lib.fosi_step_noalloc(C.c_void_p(stream.cuda_stream), n, r_v, V.ptr if r_v > 0 else None, V.ld if r_v > 0 else 0,
+                               _dptr(ev), _ptr(g), _ptr(pi), _ptr(mom), _ptr(w), C.byref(sp))
+    if st != 0:
+        raise FosiError(st, lib.fosi_status_string(st).decode())
 
 
 @dataclass

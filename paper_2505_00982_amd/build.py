@@ -10,7 +10,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["fosi_api.hip", "fosi_kernels.hip", "hvp_ggn.hip", "tridiag_eigh.cpp"]
+SOURCES = ["fosi_api.hip", "fosi_kernels.hip", "fosi_noalloc.hip", "hvp_ggn.hip", "tridiag_eigh.cpp"]
 LIB = os.path.join(HERE, "libfosi_hip.so")
 
 
