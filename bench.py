@@ -70,12 +70,17 @@ def device_name(torch) -> str:
     return name
 
 
-def cpu_baseline(cfg_id: int, n_sample: int) -> dict:
-    """The CPU oracle, as it stands, on a reduced-n copy of the same workload."""
+def cpu_baseline(cfg_id: int, n_sample: int, fo=None, reorth: str = "local_full") -> dict:
+    """The CPU oracle, as it stands, on a reduced-n copy of the same workload (host Philox generator) -- and, when
+    the binding is handed in, the HIP path on exactly those host-generated inputs, uploaded, so that one row of the
+    report times both sides on identical data.  Why a reduced n: the oracle's time is linear in n (about 6 us per
+    row for m = 80 on 16 cores: ~10 s at 1.6 M rows, ~155 s and ~32 GB at the full 25.6 M), and the whole bench has
+    to finish within minutes; 1/16 of the block keeps the leg inside the 10-30 s it is given."""
     import numpy as np
 
     import oracle
     import workloads as wl
+    n_sample = min(int(n_sample), wl.CONFIGS[cfg_id]["n"])
     w = wl.planted_workload(cfg_id, n=n_sample)
     op = lambda v: oracle.hvp_planted(w.U, w.lam, float(w.shift), v)
     p = w.params
@@ -95,12 +100,44 @@ def cpu_baseline(cfg_id: int, n_sample: int) -> dict:
         threads = max([d.get("num_threads", 1) for d in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    return {"value": round(gbs, 3), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"numpy fp64 oracle, same workload with n={n_sample} rows (1/{max(1, wl.CONFIGS[cfg_id]['n'] // n_sample)} of the "
-                      f"block), full m={w.m}, one Lanczos+Ritz+update pass, {dt:.1f} s; bytes counted as fp32 "
-                      f"algorithmic traffic of its single-pass variant",
-            "seconds": round(dt, 2),
-            "phase_seconds": {"lanczos": round(t1 - t0, 2), "ritz": round(t2 - t1, 2), "step": round(t3 - t2, 3)}}
+    frac = max(1, wl.CONFIGS[cfg_id]["n"] // n_sample)
+    out = {"value": round(gbs, 3), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+           "sample": f"numpy fp64 oracle, same workload with n={n_sample} rows ("
+                     + (f"1/{frac} of the block: the oracle's time is linear in n and the full block would take ~{frac}x this"
+                        if frac > 1 else "the whole block") + f"), full m={w.m}, one "
+                     f"Lanczos+Ritz+update pass, {dt:.1f} s; bytes counted as fp32 algorithmic traffic of its single-pass variant",
+           "seconds": round(dt, 2),
+           "phase_seconds": {"lanczos": round(t1 - t0, 2), "ritz": round(t2 - t1, 2), "step": round(t3 - t2, 3)}}
+    if fo is not None:
+        import torch
+        ctx = fo.Context(0)
+        ld = wl.padded_ld(w.n)
+        U = fo.ColMajor.from_numpy(w.U, ld)
+        hop = ctx.hvp_planted(U, torch.from_numpy(w.lam).cuda(), float(w.shift))
+        Q, V = fo.ColMajor(w.n, w.m + 1, ld), fo.ColMajor(w.n, w.k + w.l, ld)
+        v1, gd = torch.from_numpy(w.v1).cuda(), torch.from_numpy(g).cuda()
+        sp = fo.StepParams(float(p.alpha), float(p.lr), float(p.momentum), float(p.sigma), 0)
+        times = []
+        for _ in range(4):                                   # first pass warms up; median of the rest
+            wa, mom = torch.from_numpy(w.w0).cuda(), torch.zeros(w.n, device="cuda")
+            Q.col(0).copy_(v1)
+            torch.cuda.synchronize()
+            s0 = time.perf_counter()
+            alpha, beta, m_eff = fo.fosi_lanczos(ctx, hop, Q, w.m, reorth_mode=REORTH_MODES[reorth])
+            evals, _ = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, w.k, w.l, V)
+            fo.fosi_step(ctx, V, w.k + w.l, evals, gd, None, mom, wa, sp)
+            torch.cuda.synchronize()
+            times.append(time.perf_counter() - s0)
+        gpu_s = sorted(times[1:])[1]
+        rel = float(np.max(np.abs(evals - rz.evals) / np.abs(rz.evals)))
+        out["same_inputs"] = {"n": n_sample, "oracle_seconds": round(dt, 2), "gpu_ms": round(gpu_s * 1e3, 3),
+                              "ratio": round(dt / gpu_s, 1),
+                              "max_rel_diff_ritz_values": rel,
+                              "note": "the HIP path on exactly the host-generated inputs the oracle was timed on (uploaded "
+                                      "beforehand); same Lanczos+Ritz+update pass"}
+        hop.close()
+        ctx.close()
+    return out
 
 
 def bench_ggn(args, fo, torch, np) -> int:
@@ -303,6 +340,10 @@ def main() -> int:
                          "block's Lanczos run with fosi_lanczos_begin and collects them with fosi_lanczos_end")
     ap.add_argument("--graph", action="store_true",
                     help="with --blocks: replay each block's Lanczos run from a captured HIP graph (library option graph_mode)")
+    ap.add_argument("--outer", action="store_true",
+                    help="time whole outer iterations of Algorithm 3 instead of single-update steps: curvature refresh, "
+                         "anchor, the workload's number of updates (10) with the dual variable and a fresh gradient each, "
+                         "multiplier rule (workloads 2 and 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=1_600_000)
     ap.add_argument("--pmc-probe", action="store_true",
@@ -341,7 +382,12 @@ def main() -> int:
     mom = torch.zeros_like(wa)
     pi = torch.zeros_like(wa) if w.admm else None
     anchor = torch.zeros_like(wa) if w.admm else None
-    g = w.grad(0)
+    if args.outer and not w.admm:
+        print("bench.py: --outer needs a workload with the ADMM-like rule (--config 2 or 5)", file=sys.stderr)
+        return 2
+    updates = w.steps if args.outer else 1
+    grads = [w.grad(t) for t in range(updates)]     # resident before the timed region, one per update
+    g = grads[0]
     p = w.params
     sp = fo.StepParams(float(p.alpha), float(p.lr), float(p.momentum), float(p.sigma), 0)
     state = {}
@@ -354,7 +400,8 @@ def main() -> int:
         evals, resid = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, w.k, w.l, V)
         if w.admm:
             fo.fosi_admm_begin(ctx, sp.sigma, pi, anchor, wa)
-        fo.fosi_step(ctx, V, r_v, evals, g, pi, mom, wa, sp)
+        for t in range(updates):
+            fo.fosi_step(ctx, V, r_v, evals, grads[t], pi, mom, wa, sp)
         if w.admm:
             fo.fosi_admm_end(ctx, sp.sigma, anchor, wa, pi)
         state.update(m_eff=m_eff, evals=evals, resid=resid)
@@ -394,6 +441,7 @@ def main() -> int:
     vecs = algorithmic_vectors(state["m_eff"], w.r, r_v, args.reorth, w.admm, state["second_passes"])
     if w.admm:
         vecs["total"] += 8
+    vecs["total"] += (updates - 1) * vecs["step"]
     step_bytes = vecs["total"] * vec_bytes
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
@@ -417,6 +465,9 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": "k_combine_columns<false,true,false,false,...> (planted operator, expand sweep)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "traffic_source": (f"profiles/hvp_expand_cfg{args.config}_pmc.txt: FETCH_SIZE and WRITE_SIZE of this kernel from two "
+                                   "rocprofv3 --pmc runs of `bench.py --pmc-probe`, scaled by a 1 GiB copy; not measured in this run")
+                if traffic is not None else None,
                 "avg_launch_ms": round(ms / cnt, 4) if cnt else None,
                 "algorithmic_bytes_per_launch": round(by / cnt) if cnt else None, "launches": cnt}
 
@@ -426,8 +477,10 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"cfg{args.config}: planted spectrum n={w.n}, r={w.r}, Lanczos m={w.m} with "
-                               f"'{args.reorth}' Gram-Schmidt, k={w.k}, l={w.l}, one update"
-                               f"{' with ADMM begin/end' if w.admm else ''}",
+                               f"'{args.reorth}' Gram-Schmidt, k={w.k}, l={w.l}, "
+                               + (f"one outer iteration of Algorithm 3 per step: curvature refresh, anchor, {updates} updates "
+                                  f"with the dual variable and fresh gradients, multiplier rule" if args.outer else
+                                  f"one update{' with ADMM begin/end' if w.admm else ''}"),
                    "accumulation": "f64 products and sums, one rounding per stored fp32 vector",
                    "m_eff": state["m_eff"], "algorithmic_GB_per_step": round(step_bytes / 1e9, 1),
                    **({"second_passes": state["second_passes"], "reorth_eta": args.reorth_eta or round(2 ** -0.5, 4)}
@@ -448,7 +501,13 @@ def main() -> int:
                            "ritz_values": [float(x) for x in state["evals"]],
                            "ritz_residual_estimates": [float(x) for x in state["resid"]]}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_sample_rows)
+        op.close()
+        ctx.close()
+        del U, Q, V, op, ctx
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_sample_rows, fo, args.reorth)
+        print(json.dumps(out))
+        return 0
     print(json.dumps(out))
     op.close()
     ctx.close()

@@ -185,3 +185,59 @@ def synthetic_gram(r: int, n_true: int, seed: int) -> np.ndarray:
     G[:r, r] = G[r, :r] = a
     G[r, r] = a @ a + rng.chisquare(n_true - r)
     return G
+
+
+# ---------------------------------------------------------------------------------------------------
+# Algorithm 3 at sizes the numpy oracle cannot hold: the same equations with library float64 operations on
+# whatever device the tensors live on, V-hat visited in row chunks.  Pinned against the oracle on the CPU
+# (tests/test_oracle_pins.py::test_chunked_float64_state_equals_the_oracle).
+# ---------------------------------------------------------------------------------------------------
+
+class Float64State:
+    """Full-length float64 copies of (w_a, momentum b, multiplier pi, anchor w) advanced by Eq. 14 (heavy ball as the
+    base optimiser, the Newton term in its printed form) and Eq. 11 / Algorithm 3."""
+
+    def __init__(self, w0, chunk: int = 1 << 20):
+        import torch
+        self.torch = torch
+        self.w = w0.double().clone()
+        self.b = torch.zeros_like(self.w)
+        self.pi = torch.zeros_like(self.w)
+        self.anchor = None
+        self.chunk = chunk
+
+    def _vt(self, Vm, x):
+        """V^T x for V given as its transpose Vm (columns of V are rows of Vm, fp32), x float64."""
+        n = x.shape[0]
+        out = self.torch.zeros(Vm.shape[0], dtype=self.torch.float64, device=x.device)
+        for lo in range(0, n, self.chunk):
+            hi = min(n, lo + self.chunk)
+            out += Vm[:, lo:hi].double() @ x[lo:hi]
+        return out
+
+    def begin(self, sigma: float):
+        self.anchor = self.w + self.pi / sigma          # w = w_a + pi / sigma; w_a restarts from it
+        self.w = self.anchor.clone()
+
+    def step(self, Vm, evals, g, alpha: float, lr: float, momentum: float, sigma: float, with_pi: bool = True):
+        torch = self.torch
+        n = self.w.shape[0]
+        gt = g.double() + self.pi if with_pi else g.double()
+        sig = sigma if with_pi else 0.0
+        c = self._vt(Vm, gt)
+        # printed form of the Newton term: V^T applied to the projected gradient V (V^T g~)
+        in_span = torch.empty_like(gt)
+        for lo in range(0, n, self.chunk):
+            hi = min(n, lo + self.chunk)
+            in_span[lo:hi] = Vm[:, lo:hi].double().T @ c
+        c_printed = self._vt(Vm, in_span)
+        newton = alpha * c_printed / (torch.as_tensor(evals, dtype=torch.float64, device=gt.device) + sig)
+        self.b = momentum * self.b + (gt - in_span)
+        o = -lr * self.b
+        e = self._vt(Vm, o)
+        for lo in range(0, n, self.chunk):
+            hi = min(n, lo + self.chunk)
+            self.w[lo:hi] += o[lo:hi] - Vm[:, lo:hi].double().T @ (newton + e)
+
+    def end(self, sigma: float):
+        self.pi = self.pi + sigma * (self.w - self.anchor)

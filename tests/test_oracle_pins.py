@@ -522,3 +522,31 @@ def test_newton_term_printed_and_simplified_forms_agree_on_an_fp32_basis():
     w_s = w0 - alpha * (V @ (c / (ev + sigma))) + o - V @ (V.T @ o)
     assert rel_l2(w_s - w0, w1 - w0) < 1e-6 and rel_l2(b_s, b1) < 1e-6
     assert rel_l2(w_s - w0, w1 - w0) > 0.0                           # ... and they are two different computations
+
+
+def test_chunked_float64_state_equals_the_oracle():
+    """tests/helpers.Float64State (library float64 operations in row chunks, used by the GPU test of the largest
+    workload's whole schedule, where the numpy oracle cannot hold the vectors) against the oracle itself: two outer
+    iterations of Algorithm 3 with three updates each, the basis changing in between."""
+    import torch
+    from tests.helpers import Float64State
+    rng = np.random.default_rng(23)
+    n, r = 7001, 9
+    w0 = rng.standard_normal(n).astype(np.float32)
+    alpha, lr, mu, sigma = 0.1, 0.01, 0.9, 5e-4
+    st = Float64State(torch.from_numpy(w0), chunk=1000)
+    w_ref, b_ref, pi_ref = w0.astype(np.float64), np.zeros(n), np.zeros(n)
+    for outer in range(2):
+        V = np.linalg.qr(rng.standard_normal((n, r)))[0].astype(np.float32)
+        ev = np.concatenate([rng.uniform(1, 50, 6), -rng.uniform(0.5, 5, 3)])
+        Vm = torch.from_numpy(np.ascontiguousarray(V.T))
+        st.begin(sigma)
+        a_ref, w_ref = oracle.admm_begin(w_ref, pi_ref, sigma)
+        for t in range(3):
+            g = (0.03 * rng.standard_normal(n)).astype(np.float32)
+            st.step(Vm, ev, torch.from_numpy(g), alpha, lr, mu, sigma)
+            w_ref, b_ref = oracle.fosi_step(w_ref, g, V, ev, b_ref, alpha, lr, mu, sigma, pi=pi_ref)
+        st.end(sigma)
+        pi_ref = oracle.admm_end(a_ref, w_ref, pi_ref, sigma)
+        assert rel_l2(st.w.numpy(), w_ref) < 1e-13 and rel_l2(st.b.numpy(), b_ref) < 1e-13
+        assert rel_l2(st.pi.numpy(), pi_ref) < 1e-10 and rel_l2(st.anchor.numpy(), a_ref) < 1e-13
