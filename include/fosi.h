@@ -14,10 +14,17 @@
  *     leading dimension ld >= n that is a multiple of 4 floats; matrix and
  *     vector base pointers are 16-byte aligned.  Violations return
  *     FOSI_ERR_BAD_LAYOUT.
- *   - Work is enqueued on the context's HIP stream.  fosi_lanczos blocks until
- *     its tridiagonal has been copied to the host; fosi_ritz is asynchronous
- *     after its (host-side) eigen-solve; everything else is asynchronous.
- *   - No call aborts, throws or prints.  A negative status is an error and
+ *   - Work is enqueued on the context's HIP stream.  fosi_lanczos (and
+ *     fosi_lanczos_end, fosi_lanczos_row_sharded) block until the tridiagonal has
+ *     been copied to the host; fosi_ritz solves the small eigenproblem on the host
+ *     and then only enqueues; every other call only enqueues.  The two small
+ *     host-to-device uploads (the Ritz coefficient block, the Newton factors when
+ *     they change) go through pinned staging buffers owned by the context, so
+ *     neither synchronises the stream; a call that needs a staging buffer again
+ *     while its previous copy is still in flight waits for that copy alone.
+ *     Host arrays passed to a call (alpha, beta, evals) are read before it returns.
+ *   - No call aborts, throws or prints (host allocation failures inside the
+ *     library come back as FOSI_ERR_NOMEM).  A negative status is an error and
  *     fosi_last_error(ctx) describes it.
  *   - Reductions are two-stage with a fixed order: a repeated call on the same
  *     inputs returns the same bits.
@@ -44,7 +51,11 @@ typedef int32_t fosi_status;
 #define FOSI_ERR_LIMIT        (-8)  /* a size exceeds a built-in limit (see FOSI_MAX_COLS)      */
 
 /* Largest number of matrix columns any kernel handles (Lanczos steps + 1,
- * planted rank, k + l). */
+ * planted rank, k + l).  Consequence for the paper's own rule for the number
+ * of Lanczos steps, m = max{4 (k + l), 2 ln n} (fosi_lanczos_steps): m <= 255
+ * means the rule can be followed up to k + l = 63 requested pairs; beyond
+ * that fosi_lanczos returns FOSI_ERR_LIMIT for the rule's m and the caller has
+ * to run fewer steps than the rule asks for. */
 #define FOSI_MAX_COLS 256
 
 typedef struct fosi_ctx fosi_ctx;   /* one GPU + one stream + scratch; not thread-safe */
@@ -64,12 +75,14 @@ typedef struct fosi_hvp fosi_hvp;   /* a curvature operator v -> H v bound to a 
  *                     and grid cap (0: none) of the column-combination kernel
  *   FOSI_STEP_WAVES   resident waves per compute unit aimed at by the update's fused second sweep (12)
  *   FOSI_EARLY_BETA   1: beta from the Gram-Schmidt coefficients, normalisation inside the subtraction (default)
- *   FOSI_RITZ_MFMA    1: Ritz vectors of up to 32 columns on the matrix cores (default) */
+ *   FOSI_RITZ_MFMA    1: Ritz vectors on the matrix cores (default); 0: on the vector ALUs */
 fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream);
-/* Bytes of device memory the context holds for itself (partial sums, coefficient vectors, the tridiagonal,
- * flags): a fixed amount, independent of the problem sizes; every other buffer is the caller's.  Operators
- * created by hvp_softmax_ggn*_create own their work matrices in addition. */
-size_t fosi_workspace_bytes(const fosi_ctx* ctx);
+/* Bytes of device memory a context holds for itself to serve problems of n rows, m Lanczos steps and r_v = k + l
+ * Ritz pairs (partial sums, coefficient vectors, the tridiagonal, flags); every other buffer is the caller's.  The
+ * scratch is laid out for the built-in limits, so the answer is the same (about 9 MiB) for every admissible size;
+ * 0 for sizes beyond the limits.  Host-only, needs no context.  Operators created by hvp_softmax_ggn*_create own
+ * their work matrices in addition (stated there). */
+size_t fosi_workspace_bytes(int64_t n, int m, int r_v);
 fosi_status fosi_ctx_destroy(fosi_ctx* ctx);
 /* Blocks until all work enqueued through this context has finished. */
 fosi_status fosi_ctx_synchronize(fosi_ctx* ctx);

@@ -89,7 +89,7 @@ def load_library() -> C.CDLL:
     lib.fosi_lanczos_end.argtypes = [vp, dp, dp, C.POINTER(i32)]
     lib.fosi_lanczos_row_sharded.argtypes = [vp, vp, i64, C.c_int, C.c_int, vp, i64, dp, dp, C.POINTER(i32),
                                              C.POINTER(_LanczosOpts)]
-    lib.fosi_workspace_bytes.argtypes = [vp]
+    lib.fosi_workspace_bytes.argtypes = [i64, C.c_int, C.c_int]
     lib.fosi_workspace_bytes.restype = C.c_size_t
     lib.fosi_graph_stats.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.fosi_lanczos_second_passes.argtypes = [vp, C.POINTER(C.c_int32)]
@@ -258,8 +258,9 @@ class Context:
         self.check(self.lib.fosi_profile_read(self.handle, cls, C.byref(n), C.byref(ms), C.byref(by)))
         return n.value, ms.value, by.value
 
-    def workspace_bytes(self) -> int:
-        return int(self.lib.fosi_workspace_bytes(self.handle))
+    def workspace_bytes(self, n: int = 1, m: int = 1, r_v: int = 0) -> int:
+        """Device memory a context holds for itself for sizes (n, m, r_v); the same for every admissible size."""
+        return int(self.lib.fosi_workspace_bytes(n, m, r_v))
 
     def graph_stats(self) -> Tuple[int, int]:
         """(captures, replays) of HIP graphs by fosi_lanczos on this context."""

@@ -78,6 +78,29 @@ fosi_status launch_status(fosi_ctx* ctx, const char* what) { return check_hip(ct
 
 const double kVec = 4.0;   // bytes per element of an fp32 vector
 
+// Nothing may throw across the C boundary: host allocations (std::vector, std::string) are the only throwing code
+// in the library, so every exported function that reaches one runs its body through this.
+template <class F>
+fosi_status guarded(fosi_ctx* ctx, F&& body) {
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        if (ctx != nullptr) {
+            try { ctx->last_error = "host allocation failed"; } catch (...) {}
+        }
+        return FOSI_ERR_NOMEM;
+    } catch (...) {
+        return FOSI_ERR_INVALID_ARG;
+    }
+}
+
+// Waits (only) for the previous asynchronous copy out of a pinned staging buffer, if one is still in flight.
+fosi_status stage_acquire(fosi_ctx* ctx, hipEvent_t ev, bool& busy) {
+    if (!busy) return FOSI_OK;
+    busy = false;
+    return check_hip(ctx, hipEventSynchronize(ev), "staging buffer");
+}
+
 }  // namespace
 }  // namespace fosi
 
@@ -142,6 +165,18 @@ fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
         delete ctx;
         return FOSI_ERR_NOMEM;
     }
+    if (hipHostMalloc(reinterpret_cast<void**>(&ctx->stage_S), sizeof(float) * kMaxCols * 64, hipHostMallocDefault) != hipSuccess ||
+        hipHostMalloc(reinterpret_cast<void**>(&ctx->stage_newton), sizeof(double) * kMaxCols, hipHostMallocDefault) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->stage_S_done, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->stage_newton_done, hipEventDisableTiming) != hipSuccess) {
+        if (ctx->stage_S != nullptr) (void)hipHostFree(ctx->stage_S);
+        if (ctx->stage_newton != nullptr) (void)hipHostFree(ctx->stage_newton);
+        if (ctx->stage_S_done != nullptr) (void)hipEventDestroy(ctx->stage_S_done);
+        if (ctx->stage_newton_done != nullptr) (void)hipEventDestroy(ctx->stage_newton_done);
+        (void)hipFree(ctx->scratch_base);
+        delete ctx;
+        return FOSI_ERR_NOMEM;
+    }
     char* b = static_cast<char*>(ctx->scratch_base);
     ctx->s.partials = reinterpret_cast<double*>(b + o_part);
     ctx->s.norm_partials = reinterpret_cast<double*>(b + o_norm);
@@ -163,6 +198,10 @@ fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
     if (hipMemsetAsync(ctx->scratch_base, 0, off, ctx->stream) != hipSuccess ||
         hipMemcpyAsync(ctx->s.scal + 2, ones, sizeof(ones), hipMemcpyHostToDevice, ctx->stream) != hipSuccess ||
         hipStreamSynchronize(ctx->stream) != hipSuccess) {
+        (void)hipHostFree(ctx->stage_S);
+        (void)hipHostFree(ctx->stage_newton);
+        (void)hipEventDestroy(ctx->stage_S_done);
+        (void)hipEventDestroy(ctx->stage_newton_done);
         (void)hipFree(ctx->scratch_base);
         delete ctx;
         return FOSI_ERR_HIP;
@@ -180,12 +219,33 @@ fosi_status fosi_ctx_destroy(fosi_ctx* ctx) {
     }
     for (auto& e : ctx->event_pool) (void)hipEventDestroy(e);
     if (ctx->graph_exec != nullptr) (void)hipGraphExecDestroy(ctx->graph_exec);
+    (void)hipHostFree(ctx->stage_S);
+    (void)hipHostFree(ctx->stage_newton);
+    (void)hipEventDestroy(ctx->stage_S_done);
+    (void)hipEventDestroy(ctx->stage_newton_done);
     (void)hipFree(ctx->scratch_base);
     delete ctx;
     return FOSI_OK;
 }
 
-size_t fosi_workspace_bytes(const fosi_ctx* ctx) { return ctx == nullptr ? 0 : ctx->scratch_bytes; }
+size_t fosi_workspace_bytes(int64_t n, int m, int r_v) {
+    if (n < 1 || m < 1 || r_v < 0 || m + 1 > kMaxCols || r_v > kMaxCols) return 0;
+    // the same layout fosi_ctx_create allocates: sized by the built-in limits, not by (n, m, r_v)
+    const size_t cols1 = kMaxCols + 1;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { off += round256(bytes); };
+    take(sizeof(double) * kMaxDotSlots * cols1);
+    take(sizeof(double) * 3 * kMaxNormSlots);
+    for (int i = 0; i < 4; ++i) take(sizeof(double) * cols1);
+    take(sizeof(double) * 8);
+    take(sizeof(double) * 8);
+    for (int i = 0; i < 4; ++i) take(sizeof(double) * kMaxCols);
+    take(sizeof(float) * kMaxCols * kMaxCols);
+    take(sizeof(int) * 8);
+    take(sizeof(double) * kMaxShards * cols1);
+    take(sizeof(double) * kMaxShards * 3);
+    return off;
+}
 
 fosi_status fosi_ctx_synchronize(fosi_ctx* ctx) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
@@ -210,7 +270,7 @@ static fosi_status new_op(fosi_ctx* ctx, fosi_hvp::Kind kind, int64_t n, fosi_hv
     return FOSI_OK;
 }
 
-fosi_status hvp_planted_create(fosi_ctx* ctx, int64_t n, int r, const float* U_dev, int64_t ldu,
+static fosi_status hvp_planted_create_impl(fosi_ctx* ctx, int64_t n, int r, const float* U_dev, int64_t ldu,
                                const float* lam_dev, float shift, fosi_hvp** out) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
     if (out != nullptr) *out = nullptr;
@@ -227,7 +287,7 @@ fosi_status hvp_planted_create(fosi_ctx* ctx, int64_t n, int r, const float* U_d
     return FOSI_OK;
 }
 
-fosi_status hvp_diag_create(fosi_ctx* ctx, int64_t n, const float* d_dev, fosi_hvp** out) {
+static fosi_status hvp_diag_create_impl(fosi_ctx* ctx, int64_t n, const float* d_dev, fosi_hvp** out) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
     if (out != nullptr) *out = nullptr;
     if (d_dev == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "d_dev is null");
@@ -236,7 +296,7 @@ fosi_status hvp_diag_create(fosi_ctx* ctx, int64_t n, const float* d_dev, fosi_h
     return FOSI_OK;
 }
 
-fosi_status hvp_softmax_ggn_create(fosi_ctx* ctx, int B, int d, int C, const float* X_dev, const float* W_dev,
+static fosi_status hvp_softmax_ggn_create_impl(fosi_ctx* ctx, int B, int d, int C, const float* X_dev, const float* W_dev,
                                    fosi_hvp** out) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
     if (out != nullptr) *out = nullptr;
@@ -259,7 +319,7 @@ fosi_status hvp_softmax_ggn_create(fosi_ctx* ctx, int B, int d, int C, const flo
     return FOSI_OK;
 }
 
-fosi_status hvp_softmax_ggn_bf16_create(fosi_ctx* ctx, int B, int d, int C, const uint16_t* X_bf16_dev,
+static fosi_status hvp_softmax_ggn_bf16_create_impl(fosi_ctx* ctx, int B, int d, int C, const uint16_t* X_bf16_dev,
                                         const float* W_dev, fosi_hvp** out) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
     if (out != nullptr) *out = nullptr;
@@ -284,7 +344,7 @@ fosi_status hvp_softmax_ggn_bf16_create(fosi_ctx* ctx, int B, int d, int C, cons
     return FOSI_OK;
 }
 
-fosi_status hvp_callback_create(fosi_ctx* ctx, int64_t n, fosi_hvp_fn fn, void* user, fosi_hvp** out) {
+static fosi_status hvp_callback_create_impl(fosi_ctx* ctx, int64_t n, fosi_hvp_fn fn, void* user, fosi_hvp** out) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
     if (out != nullptr) *out = nullptr;
     if (fn == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "fn is null");
@@ -345,7 +405,7 @@ static fosi_status apply_operator(fosi_hvp* op, const float* v_dev, float* hv_de
     return launch_status(ctx, "hvp_apply");
 }
 
-fosi_status hvp_apply(fosi_hvp* op, const float* v_dev, float* hv_dev) {
+static fosi_status hvp_apply_impl(fosi_hvp* op, const float* v_dev, float* hv_dev) {
     if (op == nullptr) return FOSI_ERR_INVALID_ARG;
     fosi_ctx* ctx = op->ctx;
     if (fosi_status s = check_vector(ctx, "v_dev", v_dev)) return s;
@@ -356,7 +416,7 @@ fosi_status hvp_apply(fosi_hvp* op, const float* v_dev, float* hv_dev) {
 
 static void drop_graph(fosi_ctx* ctx);
 
-fosi_status hvp_destroy(fosi_hvp* op) {
+static fosi_status hvp_destroy_impl(fosi_hvp* op) {
     if (op == nullptr) return FOSI_ERR_INVALID_ARG;
     if (op->ctx->graph_key.op == op) {      // a captured run refers to this operator's buffers
         (void)hipStreamSynchronize(op->ctx->stream);
@@ -506,7 +566,7 @@ static bool lanczos_by_graph(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, floa
     return true;
 }
 
-fosi_status fosi_lanczos_begin(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q_dev, int64_t ldq,
+static fosi_status fosi_lanczos_begin_impl(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q_dev, int64_t ldq,
                                const fosi_lanczos_opts* opts) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
     if (op == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "null argument");
@@ -551,7 +611,7 @@ fosi_status fosi_lanczos_begin(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, fl
     return FOSI_OK;
 }
 
-fosi_status fosi_lanczos_end(fosi_ctx* ctx, double* alpha_host, double* beta_host, int32_t* m_eff) {
+static fosi_status fosi_lanczos_end_impl(fosi_ctx* ctx, double* alpha_host, double* beta_host, int32_t* m_eff) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
     if (alpha_host == nullptr || beta_host == nullptr || m_eff == nullptr)
         return fail(ctx, FOSI_ERR_INVALID_ARG, "null argument");
@@ -682,7 +742,7 @@ static fosi_status sharded_operator(fosi_hvp* op, const Shards& sh, const float*
     return launch_status(ctx, "sharded hvp");
 }
 
-fosi_status fosi_lanczos_row_sharded(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, int shards, float* Q_dev,
+static fosi_status fosi_lanczos_row_sharded_impl(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, int shards, float* Q_dev,
                                      int64_t ldq, double* alpha_host, double* beta_host, int32_t* m_eff,
                                      const fosi_lanczos_opts* opts) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
@@ -777,7 +837,7 @@ fosi_status fosi_tridiag_eigh(int m, const double* alpha, const double* beta, do
     return tridiag_eigh(m, alpha, beta, evals, evecs) == 0 ? FOSI_OK : FOSI_ERR_NONFINITE;
 }
 
-fosi_status fosi_ritz(fosi_ctx* ctx, int64_t n, int m_eff, const float* Q_dev, int64_t ldq, const double* alpha_host,
+static fosi_status fosi_ritz_impl(fosi_ctx* ctx, int64_t n, int m_eff, const float* Q_dev, int64_t ldq, const double* alpha_host,
                       const double* beta_host, int k, int l, float* V_dev, int64_t ldv, double* evals_host,
                       double* resid_host) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
@@ -801,21 +861,25 @@ fosi_status fosi_ritz(fosi_ctx* ctx, int64_t n, int m_eff, const float* Q_dev, i
         evals_host[j] = u[sel[j]];
         if (resid_host != nullptr) resid_host[j] = blast * std::fabs(Z[(size_t)sel[j] * m_eff + (m_eff - 1)]);
     }
-    // Ritz vectors: up to 32 output columns in one sweep on the matrix cores; more in chunks of at most 40
-    // columns on the vector ALUs (register budget of that kernel)
+    // Ritz vectors on the matrix cores in 16-wide column blocks: up to 48 output columns per sweep of Q (64 when
+    // that finishes the job in one sweep).  For comparison: the vector ALUs in chunks of at most 40 columns.
     const double vec = kVec * (double)n;
-    const bool mfma = ctx->tun.ritz_mfma != 0 && rv <= 32;
-    const int chunk = mfma ? 32 : 40;
+    const bool mfma = ctx->tun.ritz_mfma != 0;
+    const int chunk = mfma ? (rv > 48 && rv <= 64 ? 64 : 48) : 40;
     for (int c0 = 0; c0 < rv; c0 += chunk) {
         const int cw = std::min(chunk, rv - c0);
-        const int pad = mfma ? 32 : cw <= 8 ? 8 : cw <= 16 ? 16 : cw <= 24 ? 24 : cw <= 32 ? 32 : 40;
-        std::vector<float> S((size_t)m_eff * pad, 0.f);
+        const int pad = mfma ? (cw + 15) / 16 * 16 : cw <= 8 ? 8 : cw <= 16 ? 16 : cw <= 24 ? 24 : cw <= 32 ? 32 : 40;
+        // the coefficient block goes through the context's pinned staging buffer: the copy is asynchronous, and
+        // the buffer is rewritten only after the previous copy out of it has finished
+        if (fosi_status s = stage_acquire(ctx, ctx->stage_S_done, ctx->stage_S_busy)) return s;
+        float* S = ctx->stage_S;
         for (int j = 0; j < m_eff; ++j)
-            for (int t = 0; t < cw; ++t) S[(size_t)j * pad + t] = (float)Z[(size_t)sel[c0 + t] * m_eff + j];
-        // pageable source: the runtime stages the copy before returning, so S may go out of scope
-        if (fosi_status s = check_hip(ctx, hipMemcpyAsync(ctx->s.S, S.data(), S.size() * sizeof(float),
+            for (int t = 0; t < pad; ++t)
+                S[(size_t)j * pad + t] = t < cw ? (float)Z[(size_t)sel[c0 + t] * m_eff + j] : 0.f;
+        if (fosi_status s = check_hip(ctx, hipMemcpyAsync(ctx->s.S, S, sizeof(float) * (size_t)m_eff * pad,
                                                           hipMemcpyHostToDevice, ctx->stream), "upload S")) return s;
-        if (fosi_status s = check_hip(ctx, hipStreamSynchronize(ctx->stream), "upload S sync")) return s;
+        if (fosi_status s = check_hip(ctx, hipEventRecord(ctx->stage_S_done, ctx->stream), "upload S")) return s;
+        ctx->stage_S_busy = true;
         ProfScope ps(ctx, FOSI_PROF_RITZ_VECTORS, (m_eff + cw) * vec);
         if (mfma)
             launch_ritz_vectors_mfma(ctx, Q_dev, ldq, m_eff, ctx->s.S, cw, V_dev + (int64_t)c0 * ldv, ldv, n);
@@ -832,7 +896,7 @@ fosi_status fosi_ritz(fosi_ctx* ctx, int64_t n, int m_eff, const float* Q_dev, i
 static fosi_status upload_newton(fosi_ctx* ctx, int r_v, const double* evals_host, int curv_mode, double sigma,
                                  double alpha) {
     if (r_v <= 0) return FOSI_OK;
-    std::vector<double> newton(r_v);
+    double newton[kMaxCols];
     for (int j = 0; j < r_v; ++j) {
         const double a = curv_mode == FOSI_CURV_ABS ? std::fabs(evals_host[j]) : evals_host[j];
         const double den = a + sigma;
@@ -840,17 +904,22 @@ static fosi_status upload_newton(fosi_ctx* ctx, int r_v, const double* evals_hos
             return fail(ctx, FOSI_ERR_NONFINITE, "Newton divisor a_j + sigma is zero or non-finite");
         newton[j] = alpha / den;
     }
-    if (newton != ctx->newton_cache) {
-        if (fosi_status s = check_hip(ctx, hipMemcpyAsync(ctx->s.newton, newton.data(), sizeof(double) * r_v,
+    if (ctx->newton_cached != r_v || std::memcmp(newton, ctx->newton_cache, sizeof(double) * r_v) != 0) {
+        // through the pinned staging buffer: no stream synchronisation, see fosi_ritz
+        if (fosi_status s = stage_acquire(ctx, ctx->stage_newton_done, ctx->stage_newton_busy)) return s;
+        std::memcpy(ctx->stage_newton, newton, sizeof(double) * r_v);
+        if (fosi_status s = check_hip(ctx, hipMemcpyAsync(ctx->s.newton, ctx->stage_newton, sizeof(double) * r_v,
                                                           hipMemcpyHostToDevice, ctx->stream), "upload divisors"))
             return s;
-        if (fosi_status s = check_hip(ctx, hipStreamSynchronize(ctx->stream), "upload divisors sync")) return s;
-        ctx->newton_cache = newton;
+        if (fosi_status s = check_hip(ctx, hipEventRecord(ctx->stage_newton_done, ctx->stream), "upload divisors")) return s;
+        ctx->stage_newton_busy = true;
+        std::memcpy(ctx->newton_cache, newton, sizeof(double) * r_v);
+        ctx->newton_cached = r_v;
     }
     return FOSI_OK;
 }
 
-fosi_status fosi_step(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int64_t ldv, const double* evals_host,
+static fosi_status fosi_step_impl(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int64_t ldv, const double* evals_host,
                       const float* g_dev, const float* pi_dev, float* mom_dev, float* w_dev, const fosi_step_params* p) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
     if (p == nullptr) return fail(ctx, FOSI_ERR_INVALID_ARG, "params is null");
@@ -892,7 +961,7 @@ fosi_status fosi_step(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int
     return launch_status(ctx, "fosi_step");
 }
 
-fosi_status fosi_step_adamw(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int64_t ldv,
+static fosi_status fosi_step_adamw_impl(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int64_t ldv,
                             const double* evals_host, const float* g_dev, const float* pi_dev, float* exp_avg_dev,
                             float* exp_avg_sq_dev, float* work_dev, float* w_dev, int64_t step_index,
                             const fosi_adamw_params* p) {
@@ -937,7 +1006,7 @@ fosi_status fosi_step_adamw(fosi_ctx* ctx, int64_t n, int r_v, const float* V_de
 
 /* ------------------------------------------------------ Algorithm 3 / Eq. 11 */
 
-fosi_status fosi_admm_begin(fosi_ctx* ctx, int64_t n, float sigma, const float* pi_dev, float* w_anchor_dev,
+static fosi_status fosi_admm_begin_impl(fosi_ctx* ctx, int64_t n, float sigma, const float* pi_dev, float* w_anchor_dev,
                             float* wa_dev) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
     if (n < 1 || !(sigma > 0.f)) return fail(ctx, FOSI_ERR_INVALID_ARG, "n and sigma must be positive");
@@ -948,7 +1017,7 @@ fosi_status fosi_admm_begin(fosi_ctx* ctx, int64_t n, float sigma, const float* 
     return launch_status(ctx, "admm_begin");
 }
 
-fosi_status fosi_admm_end(fosi_ctx* ctx, int64_t n, float sigma, const float* w_anchor_dev, const float* wa_dev,
+static fosi_status fosi_admm_end_impl(fosi_ctx* ctx, int64_t n, float sigma, const float* w_anchor_dev, const float* wa_dev,
                           float* pi_dev) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
     if (n < 1 || !(sigma > 0.f)) return fail(ctx, FOSI_ERR_INVALID_ARG, "n and sigma must be positive");
@@ -961,7 +1030,7 @@ fosi_status fosi_admm_end(fosi_ctx* ctx, int64_t n, float sigma, const float* w_
 
 /* ------------------------------------------------------------------ timers */
 
-fosi_status fosi_profile_enable(fosi_ctx* ctx, int on) {
+static fosi_status fosi_profile_enable_impl(fosi_ctx* ctx, int on) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
     if (on < 0) return fail(ctx, FOSI_ERR_INVALID_ARG, "bad profile selection");
     ctx->prof_on = on != 0;
@@ -969,7 +1038,7 @@ fosi_status fosi_profile_enable(fosi_ctx* ctx, int on) {
     return FOSI_OK;
 }
 
-fosi_status fosi_profile_reset(fosi_ctx* ctx) {
+static fosi_status fosi_profile_reset_impl(fosi_ctx* ctx) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
     if (fosi_status s = check_hip(ctx, hipStreamSynchronize(ctx->stream), "profile reset")) return s;
     for (auto& r : ctx->prof) {
@@ -980,7 +1049,7 @@ fosi_status fosi_profile_reset(fosi_ctx* ctx) {
     return FOSI_OK;
 }
 
-fosi_status fosi_profile_read(fosi_ctx* ctx, int kernel_class, int64_t* launches, double* total_ms,
+static fosi_status fosi_profile_read_impl(fosi_ctx* ctx, int kernel_class, int64_t* launches, double* total_ms,
                               double* algorithmic_bytes) {
     if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
     if (kernel_class < 0 || kernel_class >= FOSI_PROF_NUM || launches == nullptr || total_ms == nullptr ||
@@ -1001,6 +1070,78 @@ fosi_status fosi_profile_read(fosi_ctx* ctx, int kernel_class, int64_t* launches
     *total_ms = ms;
     *algorithmic_bytes = bytes;
     return FOSI_OK;
+}
+
+
+/* ---- the exported names: each runs its body behind the exception guard ---- */
+fosi_status hvp_planted_create(fosi_ctx* ctx, int64_t n, int r, const float* U_dev, int64_t ldu,
+                               const float* lam_dev, float shift, fosi_hvp** out) {
+    return guarded(ctx, [&] { return hvp_planted_create_impl(ctx, n, r, U_dev, ldu, lam_dev, shift, out); });
+}
+fosi_status hvp_diag_create(fosi_ctx* ctx, int64_t n, const float* d_dev, fosi_hvp** out) {
+    return guarded(ctx, [&] { return hvp_diag_create_impl(ctx, n, d_dev, out); });
+}
+fosi_status hvp_softmax_ggn_create(fosi_ctx* ctx, int B, int d, int C, const float* X_dev, const float* W_dev,
+                                   fosi_hvp** out) {
+    return guarded(ctx, [&] { return hvp_softmax_ggn_create_impl(ctx, B, d, C, X_dev, W_dev, out); });
+}
+fosi_status hvp_softmax_ggn_bf16_create(fosi_ctx* ctx, int B, int d, int C, const uint16_t* X_bf16_dev,
+                                        const float* W_dev, fosi_hvp** out) {
+    return guarded(ctx, [&] { return hvp_softmax_ggn_bf16_create_impl(ctx, B, d, C, X_bf16_dev, W_dev, out); });
+}
+fosi_status hvp_callback_create(fosi_ctx* ctx, int64_t n, fosi_hvp_fn fn, void* user, fosi_hvp** out) {
+    return guarded(ctx, [&] { return hvp_callback_create_impl(ctx, n, fn, user, out); });
+}
+fosi_status hvp_apply(fosi_hvp* op, const float* v_dev, float* hv_dev) {
+    return guarded(op != nullptr ? op->ctx : nullptr, [&] { return hvp_apply_impl(op, v_dev, hv_dev); });
+}
+fosi_status hvp_destroy(fosi_hvp* op) {
+    return guarded(op != nullptr ? op->ctx : nullptr, [&] { return hvp_destroy_impl(op); });
+}
+fosi_status fosi_lanczos_begin(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, float* Q_dev, int64_t ldq,
+                               const fosi_lanczos_opts* opts) {
+    return guarded(ctx, [&] { return fosi_lanczos_begin_impl(ctx, op, n, m, Q_dev, ldq, opts); });
+}
+fosi_status fosi_lanczos_end(fosi_ctx* ctx, double* alpha_host, double* beta_host, int32_t* m_eff) {
+    return guarded(ctx, [&] { return fosi_lanczos_end_impl(ctx, alpha_host, beta_host, m_eff); });
+}
+fosi_status fosi_lanczos_row_sharded(fosi_ctx* ctx, fosi_hvp* op, int64_t n, int m, int shards, float* Q_dev,
+                                     int64_t ldq, double* alpha_host, double* beta_host, int32_t* m_eff,
+                                     const fosi_lanczos_opts* opts) {
+    return guarded(ctx, [&] { return fosi_lanczos_row_sharded_impl(ctx, op, n, m, shards, Q_dev, ldq, alpha_host, beta_host, m_eff, opts); });
+}
+fosi_status fosi_ritz(fosi_ctx* ctx, int64_t n, int m_eff, const float* Q_dev, int64_t ldq, const double* alpha_host,
+                      const double* beta_host, int k, int l, float* V_dev, int64_t ldv, double* evals_host,
+                      double* resid_host) {
+    return guarded(ctx, [&] { return fosi_ritz_impl(ctx, n, m_eff, Q_dev, ldq, alpha_host, beta_host, k, l, V_dev, ldv, evals_host, resid_host); });
+}
+fosi_status fosi_step(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int64_t ldv, const double* evals_host,
+                      const float* g_dev, const float* pi_dev, float* mom_dev, float* w_dev, const fosi_step_params* p) {
+    return guarded(ctx, [&] { return fosi_step_impl(ctx, n, r_v, V_dev, ldv, evals_host, g_dev, pi_dev, mom_dev, w_dev, p); });
+}
+fosi_status fosi_step_adamw(fosi_ctx* ctx, int64_t n, int r_v, const float* V_dev, int64_t ldv,
+                            const double* evals_host, const float* g_dev, const float* pi_dev, float* exp_avg_dev,
+                            float* exp_avg_sq_dev, float* work_dev, float* w_dev, int64_t step_index,
+                            const fosi_adamw_params* p) {
+    return guarded(ctx, [&] { return fosi_step_adamw_impl(ctx, n, r_v, V_dev, ldv, evals_host, g_dev, pi_dev, exp_avg_dev, exp_avg_sq_dev, work_dev, w_dev, step_index, p); });
+}
+fosi_status fosi_admm_begin(fosi_ctx* ctx, int64_t n, float sigma, const float* pi_dev, float* w_anchor_dev,
+                            float* wa_dev) {
+    return guarded(ctx, [&] { return fosi_admm_begin_impl(ctx, n, sigma, pi_dev, w_anchor_dev, wa_dev); });
+}
+fosi_status fosi_admm_end(fosi_ctx* ctx, int64_t n, float sigma, const float* w_anchor_dev, const float* wa_dev,
+                          float* pi_dev) {
+    return guarded(ctx, [&] { return fosi_admm_end_impl(ctx, n, sigma, w_anchor_dev, wa_dev, pi_dev); });
+}
+fosi_status fosi_profile_enable(fosi_ctx* ctx, int on) {
+    return guarded(ctx, [&] { return fosi_profile_enable_impl(ctx, on); });
+}
+fosi_status fosi_profile_reset(fosi_ctx* ctx) {
+    return guarded(ctx, [&] { return fosi_profile_reset_impl(ctx); });
+}
+fosi_status fosi_profile_read(fosi_ctx* ctx, int kernel_class, int64_t* launches, double* total_ms,
+                              double* algorithmic_bytes) {
+    return guarded(ctx, [&] { return fosi_profile_read_impl(ctx, kernel_class, launches, total_ms, algorithmic_bytes); });
 }
 
 }  // extern "C"

@@ -31,7 +31,7 @@ struct Tunables {
     int comb_cols_unroll;     // CU: columns loaded together in that kernel
     int comb_max_blocks;      // cap on that kernel's grid (it grid-strides over row tiles); 0 = no cap
     int early_beta;           // 1 (default): 'local_full' runs take beta from the coefficients and normalise inside the subtraction
-    int ritz_mfma;            // 1: Ritz vectors of up to 32 columns on the matrix cores (default), 0: vector ALUs
+    int ritz_mfma;            // 1 (default): Ritz vectors on the matrix cores in 16-wide column blocks; 0: vector ALUs
     int step_waves_per_cu;    // resident wavefronts per CU aimed at by the fused second sweep of the update
 };
 
@@ -71,7 +71,14 @@ struct fosi_ctx {
     bool prof_open = false;             // the last prof_begin recorded a start event
     std::vector<fosi::ProfRecord> prof;
     std::vector<hipEvent_t> event_pool;
-    std::vector<double> newton_cache;   // host copy of what `s.newton` holds
+    // pinned host staging for the two small uploads (Ritz coefficient block S, Newton factors): an asynchronous copy
+    // from it needs no stream synchronisation; the event tells when the buffer may be rewritten
+    float* stage_S = nullptr;           // kMaxCols x 64 floats
+    double* stage_newton = nullptr;     // kMaxCols doubles
+    hipEvent_t stage_S_done = nullptr, stage_newton_done = nullptr;
+    bool stage_S_busy = false, stage_newton_busy = false;
+    double newton_cache[FOSI_MAX_COLS] = {0};   // host copy of what `s.newton` holds
+    int newton_cached = 0;              // number of valid entries in newton_cache
     // HIP graph of the last captured Lanczos run and what it was captured for
     struct GraphKey {
         const void* op = nullptr;
@@ -189,7 +196,7 @@ void launch_scale(fosi_ctx* ctx, float* x, const double* factor, int64_t n, cons
 void launch_diag_apply(fosi_ctx* ctx, const float* d, const float* v, float* out, int64_t n);
 void launch_ritz_vectors(fosi_ctx* ctx, const float* Q, int64_t ldq, int m, const float* S_dev, int rv_pad,
                          int rv, float* V, int64_t ldv, int64_t n);
-// matrix-core variant for rv <= 32; S_dev is m x 32 row-major, zero padded
+// matrix-core variant, 16-wide column blocks, rv <= 64; S_dev is m x (16 ceil(rv / 16)) row-major, zero padded
 void launch_ritz_vectors_mfma(fosi_ctx* ctx, const float* Q, int64_t ldq, int m, const float* S_dev, int rv, float* V,
                               int64_t ldv, int64_t n);
 void launch_step_coefficients(fosi_ctx* ctx, int rv, double lr);

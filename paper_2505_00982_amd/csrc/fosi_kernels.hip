@@ -919,89 +919,120 @@ __global__ __launch_bounds__(kThreads) void k_ritz_vectors(
     }
 }
 
-// The same product on the matrix cores, for at most 32 output columns.  It is a dense contraction at
-// ~11 flop per byte, above what the vector ALUs sustain at HBM speed without packed fp32 (the kernel
-// above reaches ~60 % of the HBM rate), but within reach of v_mfma_f32_32x32x2_f32.  The product is
-// taken transposed, V^T tile (32 output columns x 32 rows) = S^T (32 x 2) . Q^T (2 x 32 rows) per
-// instruction, so that a lane ends up with all output columns of its own rows: lane l feeds the S entry
-// of output column l % 32 and Lanczos column k0 + l / 32 (from LDS) and, as the other operand, one of
-// the four rows of its float4 load of that Lanczos column (rows 4 (l % 32) + c, c = 0..3: four
-// instructions share one 16-byte load), and the four accumulators give float4 stores of 4 consecutive
-// rows per output column: 512 contiguous bytes per half wave, no transpose.
-// S: m x 32 row-major, zero padded.  A wave owns tiles of 128 rows; U column pairs are loaded together.
-typedef float floatx16 __attribute__((ext_vector_type(16)));
+// The same product on the matrix cores, for up to CB * 16 output columns (CB = 1..4).  It is a dense contraction
+// at 11-14 flop per byte, above what the vector ALUs sustain at HBM speed without packed fp32 (the kernel above
+// reaches ~60 % of the HBM rate), but within reach of v_mfma_f32_16x16x4_f32: 16-wide column blocks pad 30 columns
+// to 32 and 40 to 48 (2 n m 48 flop at n = 125 M, m = 100 is 7.6 ms of matrix work against a memory floor of
+// 8.8 ms; 32-wide tiles would pad 40 to 64 and be bound by the matrix cores).  The product is taken transposed, so
+// that a lane ends up with float4 stores of consecutive rows and no transpose is needed.
+// Per instruction: V^T tile (16 output columns x 16 rows) += S^T (16 x 4) . Q^T (4 x 16 rows).
+// Lane l = 16 g + i feeds S[k0 + g][16 cb + i] (from LDS) and, as the other operand, one of the four rows of its
+// 16-byte load of Lanczos column k0 + g (rows 4 i + c, c = 0..3 of a 64-row group: four instructions share one
+// load; a load instruction covers 4 columns x 256 contiguous bytes); accumulator register v of the instruction
+// for row c is output column 16 cb + 4 g + v, so the four instructions of one (cb, row group) give float4 stores of
+// 4 consecutive rows per output column.  A wave owns RG row groups of 64 rows; U k-steps (of 4 columns) per
+// register set, two sets, so that 2 U RG loads per lane are in flight while the matrix instructions run.
+// S: m x (16 CB) row-major, zero padded.  LDS rows are pitched so that the four 16-lane groups of a read hit
+// distinct banks.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-template <int U>
-__global__ __launch_bounds__(kThreads) void k_ritz_vectors_mfma(
+template <int CB>
+constexpr int ritz16_pitch() { return CB <= 3 ? 48 : 80; }      // = 16 mod 64 banks
+
+template <int CB, int RG, int U>
+__global__ __launch_bounds__(kThreads) void k_ritz_vectors_mfma16(
     const float* __restrict__ Q, int64_t ldq, int m, const float* __restrict__ S, int rv,
     float* __restrict__ V, int64_t ldv, int64_t n) {
-    extern __shared__ float Ssh[];                 // (m rounded up to even) x 32, the extra row zero
+    constexpr int SP = ritz16_pitch<CB>();
+    extern __shared__ float Ssh[];                 // (m rounded up to 4) x SP, rows beyond m and padding columns zero
     const int tid = threadIdx.x;
-    const int mp = (m + 1) & ~1;
-    for (int i = tid; i < mp * 32; i += kThreads) Ssh[i] = i < m * 32 ? S[i] : 0.f;
+    const int mp = (m + 3) & ~3;
+    for (int i = tid; i < mp * SP; i += kThreads) {
+        const int row = i / SP, col = i - row * SP;
+        Ssh[i] = (row < m && col < CB * 16) ? S[row * (CB * 16) + col] : 0.f;
+    }
     __syncthreads();
-    const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int lane = tid & 63, i16 = lane & 15, g = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane((int)(tid >> 6));
     const int64_t n4 = n >> 2;
-    const int64_t ntiles = (n4 + 31) >> 5;
+    const int64_t ntiles = (n4 + RG * 16 - 1) / (RG * 16);
     for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < ntiles; tile += (int64_t)gridDim.x * 4) {
-        const int64_t rg = (tile << 5) + l32;      // this lane's float4 row group
-        const bool ok = rg < n4;
-        const float* qp = Q + ((ok ? rg : n4 - 1) << 2);
-        floatx16 acc[4];
+        int64_t rgi[RG];
+        bool ok[RG];
+        const float* qp[RG];
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
+        for (int r = 0; r < RG; ++r) {
+            rgi[r] = (tile * RG + r) * 16 + i16;   // this lane's float4 row group in sub-tile r
+            ok[r] = rgi[r] < n4;
+            qp[r] = Q + ((ok[r] ? rgi[r] : n4 - 1) << 2);
+        }
+        floatx4 acc[CB][RG][4];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
-        // two register sets: the loads of the next U column pairs are in flight while the matrix
-        // instructions of the current ones run (the fences keep the compiler from serialising the two)
-        auto issue = [&](int kb, float4* q) {
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int r = 0; r < RG; ++r)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[cb][r][c] = floatx4{0.f, 0.f, 0.f, 0.f};
+        auto issue = [&](int kb, float4 (*q)[RG]) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (kb + 2 * u < mp) {             // uniform
-                    const int k = min(kb + 2 * u + half, m - 1);   // odd m: the padding column re-reads the last one, times 0
-                    q[u] = load_stream4(qp + (int64_t)k * ldq);
+                if (kb + 4 * u < mp) {             // uniform
+                    const int k = min(kb + 4 * u + g, m - 1);   // padding columns re-read the last one, times 0
+#pragma unroll
+                    for (int r = 0; r < RG; ++r) q[u][r] = load_stream4(qp[r] + (int64_t)k * ldq);
                 }
             }
         };
-        auto multiply = [&](int kb, const float4* q) {
+        auto multiply = [&](int kb, const float4 (*q)[RG]) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                if (kb + 2 * u < mp) {
-                    const float a = Ssh[(kb + 2 * u + half) * 32 + l32];
-                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, q[u].x, acc[0], 0, 0, 0);
-                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, q[u].y, acc[1], 0, 0, 0);
-                    acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, q[u].z, acc[2], 0, 0, 0);
-                    acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, q[u].w, acc[3], 0, 0, 0);
+                if (kb + 4 * u < mp) {
+                    float a[CB];
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb) a[cb] = Ssh[(kb + 4 * u + g) * SP + cb * 16 + i16];
+#pragma unroll
+                    for (int r = 0; r < RG; ++r)
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb) {
+                            acc[cb][r][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[cb], q[u][r].x, acc[cb][r][0], 0, 0, 0);
+                            acc[cb][r][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[cb], q[u][r].y, acc[cb][r][1], 0, 0, 0);
+                            acc[cb][r][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[cb], q[u][r].z, acc[cb][r][2], 0, 0, 0);
+                            acc[cb][r][3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[cb], q[u][r].w, acc[cb][r][3], 0, 0, 0);
+                        }
                 }
             }
         };
-        float4 qa[U], qb[U];
+        float4 qa[U][RG], qb[U][RG];
         issue(0, qa);
-        for (int k0 = 0; k0 < mp; k0 += 4 * U) {
-            issue(k0 + 2 * U, qb);
+        for (int k0 = 0; k0 < mp; k0 += 8 * U) {
+            issue(k0 + 4 * U, qb);
             __builtin_amdgcn_sched_barrier(0);
             multiply(k0, qa);
             __builtin_amdgcn_sched_barrier(0);
-            issue(k0 + 4 * U, qa);
+            issue(k0 + 8 * U, qa);
             __builtin_amdgcn_sched_barrier(0);
-            multiply(k0 + 2 * U, qb);
+            multiply(k0 + 4 * U, qb);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (ok) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int col = 8 * (v >> 2) + 4 * half + (v & 3);
-                if (col < rv)
-                    store_stream4(V + (int64_t)col * ldv + (rg << 2), make_float4(acc[0][v], acc[1][v], acc[2][v], acc[3][v]));
-            }
+        for (int r = 0; r < RG; ++r) {
+            if (!ok[r]) continue;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int col = cb * 16 + 4 * g + v;
+                    if (col < rv)
+                        store_stream4(V + (int64_t)col * ldv + (rgi[r] << 2),
+                                      make_float4(acc[cb][r][0][v], acc[cb][r][1][v], acc[cb][r][2][v], acc[cb][r][3][v]));
+                }
         }
     }
     const int64_t tail_row = (n4 << 2) + tid;
     if (blockIdx.x == 0 && tid < 3 && tail_row < n) {
         for (int t = 0; t < rv; ++t) {
             float s = 0.f;
-            for (int j = 0; j < m; ++j) s = fmaf(Q[(int64_t)j * ldq + tail_row], Ssh[j * 32 + t], s);
+            for (int j = 0; j < m; ++j) s = fmaf(Q[(int64_t)j * ldq + tail_row], Ssh[j * SP + t], s);
             V[(int64_t)t * ldv + tail_row] = s;
         }
     }
@@ -1247,16 +1278,36 @@ void launch_diag_apply(fosi_ctx* ctx, const float* d, const float* v, float* out
     hipLaunchKernelGGL(k_diag_apply, dim3(elementwise_grid(n)), dim3(kThreads), 0, ctx->stream, d, v, out, n);
 }
 
-void launch_ritz_vectors_mfma(fosi_ctx* ctx, const float* Q, int64_t ldq, int m, const float* S_dev, int rv, float* V,
-                              int64_t ldv, int64_t n) {
-    const int64_t ntiles = ((n >> 2) + 31) >> 5;
+namespace {
+// One row group of 64 rows per wave, four k-steps per register set (8 loads of 16 bytes per lane in flight), two
+// workgroups per compute unit.  Measured on MI355X with 1, 2, 4 row groups, 1-4 k-steps per set and 1-4 workgroups per
+// unit: everything with at least 8 loads in flight and two workgroups per unit lands within 2 % (n = 25.6 M, m = 80,
+// 30 columns: 2.17-2.27 ms; n = 125 M, m = 100, 40 columns: 13.7-14.0 ms), because the kernel then runs at the rate
+// the memory system gives this mix of reads and writes: a kernel with the same loads and stores and no arithmetic at
+// all takes 1.9-2.2 ms on the first shape, whatever the store policy or the tile size.
+template <int CB>
+void ritz16_launch(fosi_ctx* ctx, const float* Q, int64_t ldq, int m, const float* S_dev, int rv, float* V, int64_t ldv,
+                   int64_t n) {
+    constexpr int RG = 1, U = 4;
+    const int64_t ntiles = ((n >> 2) + RG * 16 - 1) / (RG * 16);
     int64_t grid = (ntiles + 3) / 4;
-    const int64_t cap = (int64_t)ctx->sm_count * 8;     // resident workgroups; the kernel grid-strides over row tiles
+    const int64_t cap = (int64_t)ctx->sm_count * 2;      // resident workgroups; the kernel grid-strides over row tiles
     if (grid > cap) grid = cap;
     if (grid < 1) grid = 1;
-    const size_t lds = sizeof(float) * 32 * ((m + 1) & ~1);
-    hipLaunchKernelGGL((k_ritz_vectors_mfma<8>), dim3((unsigned)grid), dim3(kThreads), lds, ctx->stream, Q, ldq, m, S_dev, rv,
-                       V, ldv, n);
+    const size_t lds = sizeof(float) * ritz16_pitch<CB>() * ((m + 3) & ~3);
+    hipLaunchKernelGGL((k_ritz_vectors_mfma16<CB, RG, U>), dim3((unsigned)grid), dim3(kThreads), lds, ctx->stream, Q, ldq, m,
+                       S_dev, rv, V, ldv, n);
+}
+}  // namespace
+
+// S_dev: m x (16 cb) row-major, zero padded, cb = ceil(rv / 16) <= 4
+void launch_ritz_vectors_mfma(fosi_ctx* ctx, const float* Q, int64_t ldq, int m, const float* S_dev, int rv, float* V,
+                              int64_t ldv, int64_t n) {
+    const int cb = (rv + 15) / 16;
+    if (cb <= 1) ritz16_launch<1>(ctx, Q, ldq, m, S_dev, rv, V, ldv, n);
+    else if (cb == 2) ritz16_launch<2>(ctx, Q, ldq, m, S_dev, rv, V, ldv, n);
+    else if (cb == 3) ritz16_launch<3>(ctx, Q, ldq, m, S_dev, rv, V, ldv, n);
+    else ritz16_launch<4>(ctx, Q, ldq, m, S_dev, rv, V, ldv, n);
 }
 
 void launch_ritz_vectors(fosi_ctx* ctx, const float* Q, int64_t ldq, int m, const float* S_dev, int rv_pad, int rv,

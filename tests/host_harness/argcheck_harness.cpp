@@ -1,0 +1,94 @@
+// Host harness for the argument-checking paths of the C boundary, linked against a build of the library whose host
+// code carries AddressSanitizer and UndefinedBehaviorSanitizer (tests/test_host_sanitizers.py).  Every call below
+// must be refused, or answered, on the host before any GPU work: null contexts and operators, null outputs,
+// host-only helpers with bad and good arguments.  With a GPU present it also walks the size / layout / limit checks
+// of a real context (nothing is launched: every one of these calls fails its checks first).
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "fosi.h"
+
+#define EXPECT(cond) do { if (!(cond)) { std::printf("FAILED line %d: %s\n", __LINE__, #cond); return 1; } } while (0)
+
+int main() {
+    double a[4] = {1.0, 2.0, 3.0, 4.0}, b[4] = {0.5, 0.5, 0.5, 0.0}, u[4], Z[16];
+    int32_t m_eff = -1, count = 0;
+    int64_t i64 = 0;
+    double d0 = 0.0, d1 = 0.0;
+    fosi_hvp* op = nullptr;
+    fosi_lanczos_opts opts;
+    std::memset(&opts, 0, sizeof opts);
+    fosi_step_params sp = {0.1f, 0.01f, 0.9f, 5e-4f, FOSI_CURV_SIGNED};
+    fosi_adamw_params ap = {0.1f, 1e-3f, 0.9f, 0.999f, 1e-8f, 0.05f, 5e-4f, FOSI_CURV_SIGNED};
+    float dummy[8] = {0};
+
+    // host-only helpers
+    EXPECT(fosi_tridiag_eigh(4, a, b, u, Z) == FOSI_OK && u[0] <= u[1] && u[2] <= u[3]);
+    EXPECT(fosi_tridiag_eigh(0, a, b, u, Z) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_tridiag_eigh(4, nullptr, b, u, Z) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_tridiag_eigh(4, a, nullptr, u, Z) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_tridiag_eigh(1, a, nullptr, u, nullptr) == FOSI_OK && u[0] == 1.0);
+    a[2] = NAN;
+    EXPECT(fosi_tridiag_eigh(4, a, b, u, Z) == FOSI_ERR_NONFINITE);
+    a[2] = 3.0;
+    EXPECT(fosi_lanczos_steps(25600000, 20, 10) == 120 && fosi_lanczos_steps(4096, 1, 0) == 17);
+    EXPECT(fosi_lanczos_steps(0, 1, 1) == 0 && fosi_lanczos_steps(10, 0, 0) == 0 && fosi_lanczos_steps(10, -1, 3) == 0);
+    EXPECT(fosi_workspace_bytes(1000, 80, 30) > 0 && fosi_workspace_bytes(1000, 80, 30) == fosi_workspace_bytes(5, 1, 0));
+    EXPECT(fosi_workspace_bytes(0, 80, 30) == 0 && fosi_workspace_bytes(1000, 256, 30) == 0 &&
+           fosi_workspace_bytes(1000, 80, 257) == 0);
+    EXPECT(std::strcmp(fosi_status_string(FOSI_OK), "ok") == 0 && std::strcmp(fosi_status_string(-99), "unknown status") == 0);
+    EXPECT(std::strcmp(fosi_last_error(nullptr), "null context") == 0);
+
+    // null context / operator: refused before anything else
+    EXPECT(fosi_ctx_create(nullptr, 0, nullptr) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_ctx_destroy(nullptr) == FOSI_ERR_INVALID_ARG && fosi_ctx_synchronize(nullptr) == FOSI_ERR_INVALID_ARG);
+    EXPECT(hvp_planted_create(nullptr, 8, 1, dummy, 8, dummy, 0.f, &op) == FOSI_ERR_INVALID_ARG);
+    EXPECT(hvp_diag_create(nullptr, 8, dummy, &op) == FOSI_ERR_INVALID_ARG);
+    EXPECT(hvp_softmax_ggn_create(nullptr, 1, 1, 1, dummy, dummy, &op) == FOSI_ERR_INVALID_ARG);
+    EXPECT(hvp_softmax_ggn_bf16_create(nullptr, 1, 1, 1, nullptr, dummy, &op) == FOSI_ERR_INVALID_ARG);
+    EXPECT(hvp_callback_create(nullptr, 8, nullptr, nullptr, &op) == FOSI_ERR_INVALID_ARG);
+    EXPECT(hvp_apply(nullptr, dummy, dummy) == FOSI_ERR_INVALID_ARG && hvp_destroy(nullptr) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_lanczos(nullptr, nullptr, 8, 2, dummy, 8, a, b, &m_eff, &opts) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_lanczos_begin(nullptr, nullptr, 8, 2, dummy, 8, &opts) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_lanczos_end(nullptr, a, b, &m_eff) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_lanczos_row_sharded(nullptr, nullptr, 8, 2, 2, dummy, 8, a, b, &m_eff, &opts) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_graph_stats(nullptr, &i64, &i64) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_lanczos_second_passes(nullptr, &count) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_ritz(nullptr, 8, 2, dummy, 8, a, b, 1, 0, dummy, 8, u, nullptr) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_step(nullptr, 8, 1, dummy, 8, a, dummy, nullptr, dummy, dummy, &sp) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_step_adamw(nullptr, 8, 1, dummy, 8, a, dummy, nullptr, dummy, dummy, dummy, dummy, 1, &ap) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_admm_begin(nullptr, 8, 1.f, dummy, dummy, dummy) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_admm_end(nullptr, 8, 1.f, dummy, dummy, dummy) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_profile_enable(nullptr, 1) == FOSI_ERR_INVALID_ARG && fosi_profile_reset(nullptr) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_profile_read(nullptr, 0, &i64, &d0, &d1) == FOSI_ERR_INVALID_ARG);
+    // the entry point without a context checks its arguments before it looks for a device
+    EXPECT(fosi_step_noalloc(nullptr, 8, 1, dummy, 8, a, nullptr, nullptr, dummy, dummy, &sp) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_step_noalloc(nullptr, 8, FOSI_NOALLOC_MAX_COLS + 1, dummy, 8, a, dummy, nullptr, dummy, dummy, &sp) == FOSI_ERR_LIMIT);
+    EXPECT(fosi_step_noalloc(nullptr, 0, 1, dummy, 8, a, dummy, nullptr, dummy, dummy, &sp) == FOSI_ERR_INVALID_ARG);
+
+    // a context: without a GPU its creation must fail cleanly; with one, walk the checks that need it
+    fosi_ctx* ctx = nullptr;
+    const fosi_status cs = fosi_ctx_create(&ctx, 0, nullptr);
+    if (cs != FOSI_OK) {
+        EXPECT(ctx == nullptr && (cs == FOSI_ERR_HIP || cs == FOSI_ERR_INVALID_ARG));
+        std::printf("argcheck harness ok (no GPU: context checks skipped)\n");
+        return 0;
+    }
+    EXPECT(hvp_planted_create(ctx, 0, 1, dummy, 8, dummy, 0.f, &op) == FOSI_ERR_INVALID_ARG && op == nullptr);
+    EXPECT(hvp_planted_create(ctx, 8, FOSI_MAX_COLS + 1, dummy, 8, dummy, 0.f, &op) == FOSI_ERR_LIMIT);
+    EXPECT(hvp_planted_create(ctx, 8, 1, dummy, 6, dummy, 0.f, &op) == FOSI_ERR_BAD_LAYOUT);
+    EXPECT(hvp_planted_create(ctx, 8, 1, nullptr, 8, dummy, 0.f, &op) == FOSI_ERR_INVALID_ARG);
+    EXPECT(std::strlen(fosi_last_error(ctx)) > 0);
+    EXPECT(fosi_ritz(ctx, 8, 2, dummy, 8, a, b, 2, 1, dummy, 8, u, nullptr) == FOSI_ERR_RANK);
+    EXPECT(fosi_ritz(ctx, 8, FOSI_MAX_COLS + 1, dummy, 8, a, b, 1, 0, dummy, 8, u, nullptr) == FOSI_ERR_LIMIT);
+    EXPECT(fosi_step(ctx, 8, 1, dummy, 8, a, dummy, nullptr, dummy, dummy, nullptr) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_lanczos_end(ctx, a, b, &m_eff) == FOSI_ERR_INVALID_ARG);          // nothing pending
+    EXPECT(fosi_profile_enable(ctx, -1) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_profile_read(ctx, FOSI_PROF_NUM, &i64, &d0, &d1) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_admm_begin(ctx, 8, 0.f, dummy, dummy, dummy) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_ctx_destroy(ctx) == FOSI_OK);
+    std::printf("argcheck harness ok\n");
+    return 0;
+}

@@ -183,3 +183,11 @@ def test_header_is_plain_c_and_links_from_c(fo, tmp_path):
     assert r.returncode == 0, r.stderr
     r = subprocess.run([str(exe)], capture_output=True, text=True)
     assert r.returncode == 0, (r.returncode, r.stderr)
+
+
+def test_workspace_query_is_host_only_and_size_independent(fo):
+    lib = fo.load_library()
+    w = lib.fosi_workspace_bytes(25_600_000, 80, 30)
+    assert 8 << 20 < w < 16 << 20
+    assert lib.fosi_workspace_bytes(4096, 1, 0) == w
+    assert lib.fosi_workspace_bytes(0, 80, 30) == 0 and lib.fosi_workspace_bytes(4096, 256, 0) == 0
