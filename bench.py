@@ -456,6 +456,17 @@ def main() -> int:
         if c_:
             phases[name] = {"launches": c_, "ms_total": round(m_, 3), "avg_ms": round(m_ / c_, 4),
                             "GBps": round(b_ / (m_ * 1e-3) / 1e9, 1) if m_ > 0 else None}
+    # the three sweeps of the update one by one (one more untimed update; the whole-update bracket above and these
+    # three are alternatives inside the library)
+    ctx.profile_enable(["step_project", "step_complement", "step_apply"])
+    ctx.profile_reset()
+    fo.fosi_step(ctx, V, r_v, state["evals"], g, pi, mom, wa, sp)
+    for name in ("step_project", "step_complement", "step_apply"):
+        c_, m_, b_ = ctx.profile_read(name)
+        if c_:
+            phases[name] = {"launches": c_, "ms_total": round(m_, 3), "avg_ms": round(m_ / c_, 4),
+                            "GBps": round(b_ / (m_ * 1e-3) / 1e9, 1) if m_ > 0 else None}
+    ctx.profile_enable(False)
     traffic = None
     tfile = os.path.join(ROOT, "profiles", f"hvp_expand_cfg{args.config}_pmc.txt")
     if os.path.exists(tfile) and args.n is None:

@@ -73,7 +73,8 @@ typedef struct fosi_hvp fosi_hvp;   /* a curvature operator v -> H v bound to a 
  *   FOSI_COMB_ROWS / FOSI_COMB_COLS / FOSI_COMB_BLOCKS   row groups per thread and columns loaded together (one of
  *                     1x8, 1x16, 2x4, 2x8, 4x2, 4x4, 4x8, 8x2, 8x3, 8x4; default: 4x8 up to 8 M rows, 8x4 beyond)
  *                     and grid cap (0: none) of the column-combination kernel
- *   FOSI_STEP_WAVES   resident waves per compute unit aimed at by the update's fused second sweep (12)
+ *   FOSI_STEP_WAVES   resident waves per compute unit aimed at by the update's fused second sweep (8)
+ *   FOSI_STEP_COLS    columns of V-hat per wave in that sweep: 16, 24 or 32 (default 0: 16 up to 32 columns, else 24)
  *   FOSI_EARLY_BETA   1: beta from the Gram-Schmidt coefficients, normalisation inside the subtraction (default)
  *   FOSI_RITZ_MFMA    1: Ritz vectors on the matrix cores (default); 0: on the vector ALUs */
 fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream);
@@ -317,7 +318,12 @@ fosi_status fosi_admm_end(fosi_ctx* ctx, int64_t n, float sigma, const float* w_
 #define FOSI_PROF_HVP_GGN       8   /* softmax-GGN operator, whole apply; the "bytes"   */
                                     /* field returns its GEMM flops (4 B d C) instead  */
 #define FOSI_PROF_HVP_OTHER     9   /* diagonal / callback operators                   */
-#define FOSI_PROF_NUM          10
+/* The three sweeps of fosi_step one by one.  Recorded only when the whole-step class is NOT selected (select them
+ * with FOSI_PROF_ONLY): the step's kernels carry either the one bracket or these three. */
+#define FOSI_PROF_STEP_PROJECT 10   /* c = V^T (g + pi)                                */
+#define FOSI_PROF_STEP_COMPLEMENT 11 /* b <- mu b + (g + pi) - V c, e = V^T b (fused)   */
+#define FOSI_PROF_STEP_APPLY   12   /* w <- w - lr b - V d                             */
+#define FOSI_PROF_NUM          13
 /* on = 0: off; 1: every class; FOSI_PROF_ONLY(c) [| FOSI_PROF_ONLY(c2) ...]: only those classes.  Two events
  * around a kernel cost about 5 us of stream time each on MI355X (the stream drains at every event), so a
  * timed run that must not be disturbed selects the one class it needs. */

@@ -21,7 +21,7 @@ _lib = None
 STATUS = {0: "OK", -1: "INVALID_ARG", -2: "BAD_LAYOUT", -3: "RANK", -4: "NONFINITE", -5: "HIP", -6: "NOMEM",
           -7: "CALLBACK", -8: "LIMIT"}
 PROF = {"hvp_project": 0, "hvp_expand": 1, "reorth_dot": 2, "reorth_sub": 3, "normalise": 4, "ritz_vectors": 5,
-        "step": 6, "admm": 7, "hvp_ggn": 8, "hvp_other": 9}
+        "step": 6, "admm": 7, "hvp_ggn": 8, "hvp_other": 9, "step_project": 10, "step_complement": 11, "step_apply": 12}
 
 EXPORTS = [
     "fosi_ctx_create", "fosi_ctx_destroy", "fosi_ctx_synchronize", "fosi_last_error", "fosi_status_string",

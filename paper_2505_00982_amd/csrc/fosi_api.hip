@@ -143,7 +143,8 @@ fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
     ctx->tun.comb_max_blocks = env_int("FOSI_COMB_BLOCKS", 0);
     ctx->tun.early_beta = env_int("FOSI_EARLY_BETA", 1);
     ctx->tun.ritz_mfma = env_int("FOSI_RITZ_MFMA", 1);
-    ctx->tun.step_waves_per_cu = env_int("FOSI_STEP_WAVES", 12);
+    ctx->tun.step_waves_per_cu = env_int("FOSI_STEP_WAVES", 8);
+    ctx->tun.step_cols_per_wave = env_int("FOSI_STEP_COLS", 0);
     if (ctx->tun.step_waves_per_cu < 1) ctx->tun.step_waves_per_cu = 1;
 
     const size_t cols1 = kMaxCols + 1;
@@ -939,25 +940,31 @@ static fosi_status fosi_step_impl(fosi_ctx* ctx, int64_t n, int r_v, const float
     if (fosi_status st = upload_newton(ctx, r_v, evals_host, p->curv_mode, sigma, alpha)) return st;
     const double vec = kVec * (double)n;
     const int extra = pi_dev != nullptr ? 1 : 0;
-    // three sweeps of V: r_v + 1 (+1), r_v + 3 (+1), r_v + 3 vectors
-    ProfScope ps(ctx, FOSI_PROF_STEP, r_v > 0 ? (3.0 * r_v + 7 + 2 * extra) * vec : (6.0 + extra) * vec);
+    // three sweeps of V: r_v + 1 (+1), r_v + 3 (+1), r_v + 3 vectors.  Timers: one bracket around the whole update, or
+    // (when that class is not selected) one per sweep.
+    const bool whole = ctx->prof_on && (ctx->prof_mask == 1 || ((ctx->prof_mask >> (FOSI_PROF_STEP + 1)) & 1) != 0);
+    const int c1 = whole ? -1 : FOSI_PROF_STEP_PROJECT, c2 = whole ? -1 : FOSI_PROF_STEP_COMPLEMENT,
+              c3 = whole ? -1 : FOSI_PROF_STEP_APPLY;
+    if (whole) prof_begin(ctx, FOSI_PROF_STEP, r_v > 0 ? (3.0 * r_v + 7 + 2 * extra) * vec : (6.0 + extra) * vec);
     if (r_v > 0) {
         // c = V^T (g + pi)
         launch_dot_columns(ctx, V_dev, ldv, r_v, g_dev, pi_dev, nullptr, nullptr, n, ctx->s.coef_a, nullptr, 0, 1.0,
-                           nullptr, nullptr, -1, 0.0);
+                           nullptr, nullptr, c1, (r_v + 1 + extra) * vec);
         // b <- momentum b + (g + pi) - V c ;  e = V^T b
         launch_complement_reproject(ctx, 0, V_dev, ldv, r_v, ctx->s.coef_a, g_dev, pi_dev, nullptr, mom_dev, nullptr,
-                                    nullptr, n, mu, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, ctx->s.coef_b);
+                                    nullptr, n, mu, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, ctx->s.coef_b, c2,
+                                    (r_v + 3 + extra) * vec);
         // d = newton . c - lr e
         launch_step_coefficients(ctx, r_v, lr);
     } else {
         // b <- momentum b + (g + pi)
         launch_combine_columns(ctx, V_dev, ldv, 0, ctx->s.coef_a, mom_dev, mu, g_dev, 1.0, pi_dev, 1.0, nullptr, false,
-                               -1.0, mom_dev, n, false, nullptr, -1, 0.0);
+                               -1.0, mom_dev, n, false, nullptr, c2, (3.0 + extra) * vec);
     }
     // w <- w - lr b - V d   ( = w + Delta_1 + Delta_2 )
     launch_combine_columns(ctx, V_dev, ldv, r_v, ctx->s.coef_c, w_dev, 1.0, mom_dev, -lr, nullptr, 0.0, nullptr, false,
-                           -1.0, w_dev, n, false, nullptr, -1, 0.0);
+                           -1.0, w_dev, n, false, nullptr, c3, (r_v + 3) * vec);
+    if (whole) prof_end(ctx);
     return launch_status(ctx, "fosi_step");
 }
 

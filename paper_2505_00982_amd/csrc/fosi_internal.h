@@ -33,6 +33,7 @@ struct Tunables {
     int early_beta;           // 1 (default): 'local_full' runs take beta from the coefficients and normalise inside the subtraction
     int ritz_mfma;            // 1 (default): Ritz vectors on the matrix cores in 16-wide column blocks; 0: vector ALUs
     int step_waves_per_cu;    // resident wavefronts per CU aimed at by the fused second sweep of the update
+    int step_cols_per_wave;   // columns of V-hat a wave of that sweep keeps in registers: 16, 24 or 32; 0 = chosen by width
 };
 
 // Device scratch layout (one allocation per context).
@@ -206,7 +207,7 @@ void launch_step_coefficients(fosi_ctx* ctx, int rv, double lr);
 void launch_complement_reproject(fosi_ctx* ctx, int opt, const float* V, int64_t ldv, int rv, const double* c,
                                  const float* g, const float* pi, const float* w, float* m, float* v, float* o_out,
                                  int64_t n, double mu, double b1, double b2, double inv_bc1, double inv_bc2, double eps,
-                                 double lr, double wd, double* e_out);
+                                 double lr, double wd, double* e_out, int prof_cls = -1, double prof_bytes = 0.0);
 // d = newton . c + e for the last sweep of the AdamW variant
 void launch_step_coefficients_plus(fosi_ctx* ctx, int rv);
 void launch_admm_begin(fosi_ctx* ctx, int64_t n, double inv_sigma, const float* pi, float* anchor, float* wa);

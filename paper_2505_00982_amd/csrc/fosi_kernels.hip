@@ -1345,20 +1345,28 @@ void launch_admm_end(fosi_ctx* ctx, int64_t n, double sigma, const float* anchor
 void launch_complement_reproject(fosi_ctx* ctx, int opt, const float* V, int64_t ldv, int rv, const double* c,
                                  const float* g, const float* pi, const float* w, float* m, float* v, float* o_out,
                                  int64_t n, double mu, double b1, double b2, double inv_bc1, double inv_bc2, double eps,
-                                 double lr, double wd, double* e_out) {
-    // columns per wave: at most 16 up to 128 columns, at most 32 beyond; no empty wave
-    int S = (rv + 15) / 16;
+                                 double lr, double wd, double* e_out, int prof_cls, double prof_bytes) {
+    // columns per wave: at most 16 up to 32 columns, 24 up to 192 (a 40-column basis then splits 20 + 20 over two
+    // waves instead of 14 + 14 + 12 over three: one exchange partner less per tile), 32 beyond; no empty wave
+    int per_wave = ctx->tun.step_cols_per_wave;
+    if (per_wave != 16 && per_wave != 24 && per_wave != 32) per_wave = rv <= 32 ? 16 : rv <= 192 ? 24 : 32;
+    int S = (rv + per_wave - 1) / per_wave;
     if (S < 1) S = 1;
     if (S > 8) S = 8;
     const int cw = rv > 0 ? (rv + S - 1) / S : 1;
     S = rv > 0 ? (rv + cw - 1) / cw : 1;
     const int64_t ntiles = ((n >> 2) + 63) >> 6;
-    int64_t blocks = (int64_t)ctx->sm_count * ctx->tun.step_waves_per_cu / S;
+    // a whole number of blocks per compute unit: the blocks stride over the tiles in lockstep, so a unit that holds
+    // one block more than its neighbours finishes that much later
+    int64_t per_cu = ctx->tun.step_waves_per_cu / S;
+    if (per_cu < 1) per_cu = 1;
+    int64_t blocks = (int64_t)ctx->sm_count * per_cu;
     if (blocks > kMaxDotSlots) blocks = kMaxDotSlots;
     if (blocks > ntiles) blocks = ntiles;
     if (blocks < 1) blocks = 1;
     const size_t lds = S > 1 ? sizeof(double) * 2 * S * 4 * 64 : 0;
     OptScalars p{mu, b1, b2, inv_bc1, inv_bc2, eps, lr, wd};
+    if (prof_cls >= 0) prof_begin(ctx, prof_cls, prof_bytes);
 #define FOSI_CR(NCOL)                                                                                              \
     do {                                                                                                           \
         if (opt == 0)                                                                                              \
@@ -1375,6 +1383,7 @@ void launch_complement_reproject(fosi_ctx* ctx, int opt, const float* V, int64_t
     else if (cw <= 24) FOSI_CR(24);
     else FOSI_CR(32);
 #undef FOSI_CR
+    if (prof_cls >= 0) prof_end(ctx);
     if (rv > 0)
         hipLaunchKernelGGL(k_reduce_columns, dim3(rv + 1), dim3(64), 0, ctx->stream, ctx->s.partials, (int)blocks, (int64_t)1,
                            (int64_t)blocks, e_out, (const float*)nullptr, 0, 1.0, rv, (const double*)nullptr,

@@ -115,7 +115,8 @@ extern "C" fosi_status fosi_step_noalloc(void* hip_stream, int64_t n, int r_v, c
     local.tun = Tunables{};
     local.tun.early_beta = 1;
     local.tun.ritz_mfma = 1;
-    local.tun.step_waves_per_cu = 12;
+    local.tun.step_waves_per_cu = 8;
+    local.tun.step_cols_per_wave = 0;
     local.s = Scratch{};
     local.s.partials = reinterpret_cast<double*>(base + kOffPartials);
     local.s.norm_partials = local.s.partials;                      // not used by the update (no norm is requested)

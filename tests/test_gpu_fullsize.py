@@ -16,6 +16,7 @@ import torch
 
 import oracle
 import workloads as wl
+from oracle.hvp import hvp_planted_chunked
 from oracle.lanczos import tridiagonal
 from tests.helpers import (reduced_ritz_coefficients, reduced_tridiagonal_from_gram, rel_l2,
                            sin_principal_angles, storage_emulation)
@@ -384,6 +385,37 @@ def test_workload4_other_schemes_full_size(fo, ctx, mode_name):
         gram += blk @ blk.T
     dev_ = float((gram - torch.eye(m, dtype=torch.float64, device="cuda")).abs().max())
     assert dev_ < (1e-5 if mode_name == "single" else 1e-7), dev_
+    op.close()
+
+
+@pytest.mark.parametrize("mode_name", ["single", "twice"])
+def test_in_place_rewrites_at_three_million_rows(fo, ctx, mode_name):
+    """The schemes whose subtraction sweep rewrites the vector in place with the hand-written write-through store and
+    then goes on computing with the stored values (sum of squares), at a size where thousands of workgroups are in
+    flight and the rows are ragged (3 * 2^20 + 1): EVERY element of the first ten Lanczos vectors against the
+    oracle.  (That store once lost elements under memory pressure -- its data registers were overwritten inside
+    the hardware's wait states -- and only the 8 GB full-size runs noticed.)"""
+    n, m = 3 * (1 << 20) + 1, 10
+    w = wl.planted_workload(2, n=n)
+    ld = wl.padded_ld(n)
+    U = fo.ColMajor.from_numpy(w.U, ld)
+    op = ctx.hvp_planted(U, dev(w.lam), float(w.shift))
+    Q = fo.ColMajor(n, m + 1, ld)
+    Q.col(0).copy_(dev(w.v1))
+    mode = {"single": fo.REORTH_SINGLE, "twice": fo.REORTH_TWICE}[mode_name]
+    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, m, reorth_mode=mode)
+    ctx.synchronize()
+    assert m_eff == m
+    res = oracle.lanczos(lambda v: hvp_planted_chunked(w.U, w.lam, float(w.shift), v), w.v1, m,
+                         passes=1 if mode_name == "single" else 2)
+    Qg = Q.to_numpy(m + 1).astype(np.float64)
+    assert np.all(np.isfinite(Qg))
+    for j in range(m + 1):
+        tol = 1e-4 * np.abs(res.Q[:, j]).max()
+        bad = np.flatnonzero(np.abs(Qg[:, j] - res.Q[:, j]) > tol)
+        assert bad.size == 0, (mode_name, j, bad[:8], bad.size)
+    scale = np.abs(w.lam).max()
+    assert np.max(np.abs(alpha - res.alpha)) < 1e-6 * scale and np.max(np.abs(beta - res.beta)) < 1e-6 * scale
     op.close()
 
 

@@ -684,7 +684,7 @@ def test_maximum_lanczos_length_and_planted_rank(fo, ctx):
     {"FOSI_COMB_ROWS": "1", "FOSI_COMB_COLS": "16"}, {"FOSI_COMB_ROWS": "2", "FOSI_COMB_COLS": "4"},
     {"FOSI_COMB_ROWS": "8", "FOSI_COMB_COLS": "2"}, {"FOSI_COMB_ROWS": "8", "FOSI_COMB_COLS": "4"},   # 8 x 4: the library's choice above 8 M rows
     {"FOSI_COMB_ROWS": "8", "FOSI_COMB_COLS": "3"}, {"FOSI_COMB_BLOCKS": "3"},
-    {"FOSI_STEP_WAVES": "1"},
+    {"FOSI_STEP_WAVES": "1"}, {"FOSI_STEP_COLS": "24"}, {"FOSI_STEP_COLS": "32"},
 ], ids=lambda e: ",".join(f"{k[5:]}={v}" for k, v in e.items()))
 def test_launch_shape_knobs_keep_the_results(fo, env, monkeypatch):
     """The environment knobs read at context creation select other compiled variants and launch shapes of the
