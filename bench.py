@@ -349,6 +349,10 @@ def main() -> int:
     ap.add_argument("--pmc-probe", action="store_true",
                     help="short run for hardware-counter collection: 3 plain copies of 1 GiB (calibration), then a "
                          "Lanczos run of 6 steps, Ritz vectors and one update on the chosen workload; no timing")
+    ap.add_argument("--traffic-model", action="store_true",
+                    help="instead of the timed steps: the library's memory-only sweep (fosi_traffic_model) on the chosen "
+                         "workload's column counts -- Ritz vectors (m read, k + l written), an update sweep (k + l + 2 "
+                         "read, 1 written), read-only and write-only -- beside the real kernels of one step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -417,6 +421,39 @@ def main() -> int:
         fo.fosi_step(ctx, V, r_v, np.linspace(10.0, 1.0, r_v), g, pi, mom, wa, sp)
         ctx.synchronize()
         print(json.dumps({"pmc_probe": "done", "n": w.n, "r": w.r, "copy_bytes_each_way": 4 << 28}))
+        return 0
+
+    if args.traffic_model:
+        def phase(names):
+            out = {}
+            for name in names:
+                c_, m_, b_ = ctx.profile_read(name)
+                if c_:
+                    out[name] = {"launches": c_, "avg_ms": round(m_ / c_, 4), "GBps": round(b_ / (m_ * 1e-3) / 1e9, 1)}
+            return out
+        one_step()                                           # warm-up, and real Ritz pairs for the update
+        ctx.profile_enable(["ritz_vectors", "step_project", "step_complement", "step_apply"])
+        ctx.profile_reset()
+        one_step()
+        kernels = phase(["ritz_vectors", "step_project", "step_complement", "step_apply"])
+        ctx.profile_enable("traffic_model")
+        m_e = state["m_eff"]
+        cases = [("ritz_vectors: m read, k+l written", Q, m_e, V, r_v), ("update sweep: k+l+2 read, 1 written", Q, r_v + 2, V, 1),
+                 ("read only, m columns", Q, m_e, None, 0), ("read only, r columns", U, w.r, None, 0),
+                 ("write only, k+l columns", None, 0, V, r_v)]
+        model = {}
+        for label, A_, ci, B_, co in cases:
+            for _ in range(2):
+                fo.fosi_traffic_model(ctx, A_, ci, B_, co, w.n)
+            ctx.profile_reset()
+            for _ in range(5):
+                fo.fosi_traffic_model(ctx, A_, ci, B_, co, w.n)
+            c_, m_, b_ = ctx.profile_read("traffic_model")
+            model[label] = {"cols_in": ci, "cols_out": co, "avg_ms": round(m_ / c_, 4), "GBps": round(b_ / (m_ * 1e-3) / 1e9, 1),
+                            "frac_of_hbm_peak": round(b_ / (m_ * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        ctx.profile_enable(False)
+        print(json.dumps({"traffic_model": model, "kernels_of_one_step": kernels, "unit": "algorithmic GB/s",
+                          "workload": f"cfg{args.config}: n={w.n}, m={w.m}, k+l={r_v}, r={w.r}"}))
         return 0
 
     for _ in range(args.warmup):

@@ -302,6 +302,19 @@ fosi_status fosi_admm_begin(fosi_ctx* ctx, int64_t n, float sigma, const float* 
 fosi_status fosi_admm_end(fosi_ctx* ctx, int64_t n, float sigma, const float* w_anchor_dev,
                           const float* wa_dev, float* pi_dev);
 
+/* ---- measurement aid ---------------------------------------------------------
+ * Not a step of the method (no passage of the paper defines it): a memory-only model of a sweep.
+ * Reads cols_in columns of A (device, fp32 column-major, lda) and writes cols_out columns of B (device, ldb) with
+ * the streaming loads, streaming stores and workgroup tiling of the library's own sweeps and no arithmetic beyond
+ * one add per loaded value; column w of B receives (w + 1) * (sum of the columns of A), or zeros when cols_in == 0
+ * (write-only), and nothing is written when cols_out == 0 (read-only; B_dev may then be NULL).  Timed through the
+ * FOSI_PROF_TRAFFIC_MODEL class it states what the device's memory system gives to a given mix of read and
+ * written columns (bench.py --traffic-model): the yardstick for the kernels whose traffic is that mix -- the Ritz
+ * vectors (m read, k + l written) and the update's sweeps (k + l + 2 read, 1 written).
+ * n: rows, a positive multiple of 4.  Only enqueues.  FOSI_ERR_INVALID_ARG / FOSI_ERR_BAD_LAYOUT as elsewhere. */
+fosi_status fosi_traffic_model(fosi_ctx* ctx, int64_t n, const float* A_dev, int64_t lda, int cols_in, float* B_dev,
+                               int64_t ldb, int cols_out);
+
 /* ---- per-kernel timing (opt-in) --------------------------------------------
  * When enabled, every launch of the kernels listed below is bracketed by HIP
  * events on the context's stream.  fosi_profile_read synchronises and returns
@@ -323,7 +336,8 @@ fosi_status fosi_admm_end(fosi_ctx* ctx, int64_t n, float sigma, const float* w_
 #define FOSI_PROF_STEP_PROJECT 10   /* c = V^T (g + pi)                                */
 #define FOSI_PROF_STEP_COMPLEMENT 11 /* b <- mu b + (g + pi) - V c, e = V^T b (fused)   */
 #define FOSI_PROF_STEP_APPLY   12   /* w <- w - lr b - V d                             */
-#define FOSI_PROF_NUM          13
+#define FOSI_PROF_TRAFFIC_MODEL 13  /* fosi_traffic_model                              */
+#define FOSI_PROF_NUM          14
 /* on = 0: off; 1: every class; FOSI_PROF_ONLY(c) [| FOSI_PROF_ONLY(c2) ...]: only those classes.  Two events
  * around a kernel cost about 5 us of stream time each on MI355X (the stream drains at every event), so a
  * timed run that must not be disturbed selects the one class it needs. */

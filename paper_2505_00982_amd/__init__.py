@@ -29,6 +29,7 @@ from .binding import (  # noqa: F401
     AdamwParams,
     fosi_admm_begin,
     fosi_admm_end,
+    fosi_traffic_model,
     fosi_tridiag_eigh,
     library_path,
     load_library,

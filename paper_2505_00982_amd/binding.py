@@ -21,14 +21,15 @@ _lib = None
 STATUS = {0: "OK", -1: "INVALID_ARG", -2: "BAD_LAYOUT", -3: "RANK", -4: "NONFINITE", -5: "HIP", -6: "NOMEM",
           -7: "CALLBACK", -8: "LIMIT"}
 PROF = {"hvp_project": 0, "hvp_expand": 1, "reorth_dot": 2, "reorth_sub": 3, "normalise": 4, "ritz_vectors": 5,
-        "step": 6, "admm": 7, "hvp_ggn": 8, "hvp_other": 9, "step_project": 10, "step_complement": 11, "step_apply": 12}
+        "step": 6, "admm": 7, "hvp_ggn": 8, "hvp_other": 9, "step_project": 10, "step_complement": 11, "step_apply": 12,
+        "traffic_model": 13}
 
 EXPORTS = [
     "fosi_ctx_create", "fosi_ctx_destroy", "fosi_ctx_synchronize", "fosi_last_error", "fosi_status_string",
     "hvp_planted_create", "hvp_diag_create", "hvp_softmax_ggn_create", "hvp_softmax_ggn_bf16_create", "hvp_callback_create", "hvp_apply",
     "hvp_destroy", "fosi_workspace_bytes", "fosi_lanczos", "fosi_lanczos_begin", "fosi_lanczos_end", "fosi_graph_stats", "fosi_lanczos_second_passes",
     "fosi_lanczos_row_sharded", "fosi_lanczos_steps", "fosi_tridiag_eigh", "fosi_ritz", "fosi_step", "fosi_step_noalloc", "fosi_step_adamw", "fosi_admm_begin",
-    "fosi_admm_end", "fosi_profile_enable", "fosi_profile_reset", "fosi_profile_read",
+    "fosi_admm_end", "fosi_traffic_model", "fosi_profile_enable", "fosi_profile_reset", "fosi_profile_read",
 ]
 
 
@@ -101,6 +102,7 @@ def load_library() -> C.CDLL:
     lib.fosi_step_adamw.argtypes = [vp, i64, C.c_int, vp, i64, dp, vp, vp, vp, vp, vp, vp, i64, C.POINTER(_AdamwParams)]
     lib.fosi_admm_begin.argtypes = [vp, i64, C.c_float, vp, vp, vp]
     lib.fosi_admm_end.argtypes = [vp, i64, C.c_float, vp, vp, vp]
+    lib.fosi_traffic_model.argtypes = [vp, i64, vp, i64, C.c_int, vp, i64, C.c_int]
     lib.fosi_profile_enable.argtypes = [vp, C.c_int]
     lib.fosi_profile_reset.argtypes = [vp]
     lib.fosi_profile_read.argtypes = [vp, C.c_int, C.POINTER(i64), dp, dp]
@@ -417,3 +419,10 @@ def fosi_admm_begin(ctx: Context, sigma: float, pi: torch.Tensor, w_anchor: torc
 
 def fosi_admm_end(ctx: Context, sigma: float, w_anchor: torch.Tensor, wa: torch.Tensor, pi: torch.Tensor):
     ctx.check(ctx.lib.fosi_admm_end(ctx.handle, wa.numel(), float(sigma), _ptr(w_anchor), _ptr(wa), _ptr(pi)))
+
+
+def fosi_traffic_model(ctx: Context, A: Optional[ColMajor], cols_in: int, B: Optional[ColMajor], cols_out: int, n: int):
+    """Memory-only model of a sweep (measurement aid): cols_in columns of A read, cols_out columns of B written."""
+    ctx.check(ctx.lib.fosi_traffic_model(ctx.handle, int(n), A.ptr if A is not None else None, A.ld if A is not None else 0,
+                                         int(cols_in), B.ptr if B is not None else None, B.ld if B is not None else 0,
+                                         int(cols_out)))

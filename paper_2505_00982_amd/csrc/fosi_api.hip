@@ -1035,6 +1035,20 @@ static fosi_status fosi_admm_end_impl(fosi_ctx* ctx, int64_t n, float sigma, con
     return launch_status(ctx, "admm_end");
 }
 
+/* ------------------------------------------- measurement aid: memory-only sweep */
+
+static fosi_status fosi_traffic_model_impl(fosi_ctx* ctx, int64_t n, const float* A_dev, int64_t lda, int cols_in,
+                                           float* B_dev, int64_t ldb, int cols_out) {
+    if (ctx == nullptr) return FOSI_ERR_INVALID_ARG;
+    if (n < 4 || (n & 3) != 0) return fail(ctx, FOSI_ERR_INVALID_ARG, "n must be a positive multiple of 4");
+    if (cols_in < 0 || cols_out < 0 || cols_in + cols_out < 1) return fail(ctx, FOSI_ERR_INVALID_ARG, "bad column counts");
+    if (fosi_status s = check_matrix(ctx, "A_dev", A_dev, n, lda, cols_in)) return s;
+    if (fosi_status s = check_matrix(ctx, "B_dev", B_dev, n, ldb, cols_out)) return s;
+    ProfScope ps(ctx, FOSI_PROF_TRAFFIC_MODEL, kVec * (double)n * (cols_in + cols_out));
+    launch_traffic_model(ctx, A_dev, lda, cols_in, B_dev, ldb, cols_out, n, n > ((int64_t)8 << 20));
+    return launch_status(ctx, "traffic model");
+}
+
 /* ------------------------------------------------------------------ timers */
 
 static fosi_status fosi_profile_enable_impl(fosi_ctx* ctx, int on) {
@@ -1139,6 +1153,10 @@ fosi_status fosi_admm_begin(fosi_ctx* ctx, int64_t n, float sigma, const float* 
 fosi_status fosi_admm_end(fosi_ctx* ctx, int64_t n, float sigma, const float* w_anchor_dev, const float* wa_dev,
                           float* pi_dev) {
     return guarded(ctx, [&] { return fosi_admm_end_impl(ctx, n, sigma, w_anchor_dev, wa_dev, pi_dev); });
+}
+fosi_status fosi_traffic_model(fosi_ctx* ctx, int64_t n, const float* A_dev, int64_t lda, int cols_in, float* B_dev,
+                               int64_t ldb, int cols_out) {
+    return guarded(ctx, [&] { return fosi_traffic_model_impl(ctx, n, A_dev, lda, cols_in, B_dev, ldb, cols_out); });
 }
 fosi_status fosi_profile_enable(fosi_ctx* ctx, int on) {
     return guarded(ctx, [&] { return fosi_profile_enable_impl(ctx, on); });

@@ -198,6 +198,8 @@ void launch_diag_apply(fosi_ctx* ctx, const float* d, const float* v, float* out
 void launch_ritz_vectors(fosi_ctx* ctx, const float* Q, int64_t ldq, int m, const float* S_dev, int rv_pad,
                          int rv, float* V, int64_t ldv, int64_t n);
 // matrix-core variant, 16-wide column blocks, rv <= 64; S_dev is m x (16 ceil(rv / 16)) row-major, zero padded
+void launch_traffic_model(fosi_ctx* ctx, const float* A, int64_t lda, int cols_in, float* Bm, int64_t ldb, int cols_out,
+                          int64_t n, bool large_tiles);
 void launch_ritz_vectors_mfma(fosi_ctx* ctx, const float* Q, int64_t ldq, int m, const float* S_dev, int rv, float* V,
                               int64_t ldv, int64_t n);
 void launch_step_coefficients(fosi_ctx* ctx, int rv, double lr);

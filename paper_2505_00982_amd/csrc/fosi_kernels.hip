@@ -1396,4 +1396,74 @@ void launch_step_coefficients_plus(fosi_ctx* ctx, int rv) {
                        ctx->s.coef_b, ctx->s.newton, rv, ctx->s.coef_c);
 }
 
+/* --------------------------------------------------------------- memory-only model of a sweep (measurement aid) */
+namespace {
+
+// Reads cols_in columns of A and writes cols_out columns of B with the loads, the stores and the tiling of the
+// sweeps above (a workgroup owns RPT * 1024 consecutive rows, CU columns of loads in flight per thread) and no
+// arithmetic beyond one add per loaded value: what it reaches is what the memory system gives to that mix of
+// reads and writes.  Column w of B receives (w + 1) * (sum of the columns of A); with cols_in == 0 the sum is 0.
+template <int RPT, int CU>
+__global__ __launch_bounds__(kThreads) void k_traffic_model(const float* __restrict__ A, int64_t lda, int cols_in,
+                                                            float* __restrict__ Bm, int64_t ldb, int cols_out,
+                                                            int64_t n4) {
+    const int tid = threadIdx.x;
+    const int64_t base = (int64_t)blockIdx.x * (RPT * kThreads);
+    int64_t r4[RPT];                      // float4 row group of each slot; slots past the end repeat the last group
+#pragma unroll
+    for (int q = 0; q < RPT; ++q) {
+        r4[q] = base + q * kThreads + tid;
+        if (r4[q] >= n4) r4[q] = n4 - 1;
+    }
+    float4 s[RPT];
+#pragma unroll
+    for (int q = 0; q < RPT; ++q) s[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    int j = 0;
+    for (; j + CU <= cols_in; j += CU) {
+        float4 a[CU][RPT];
+#pragma unroll
+        for (int u = 0; u < CU; ++u)
+#pragma unroll
+            for (int q = 0; q < RPT; ++q) a[u][q] = load_stream4(A + (int64_t)(j + u) * lda + (r4[q] << 2));
+#pragma unroll
+        for (int u = 0; u < CU; ++u)
+#pragma unroll
+            for (int q = 0; q < RPT; ++q) {
+                s[q].x += a[u][q].x; s[q].y += a[u][q].y; s[q].z += a[u][q].z; s[q].w += a[u][q].w;
+            }
+    }
+    for (; j < cols_in; ++j)
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            const float4 a = load_stream4(A + (int64_t)j * lda + (r4[q] << 2));
+            s[q].x += a.x; s[q].y += a.y; s[q].z += a.z; s[q].w += a.w;
+        }
+    for (int w = 0; w < cols_out; ++w) {
+        const float f = (float)(w + 1);
+#pragma unroll
+        for (int q = 0; q < RPT; ++q)
+            store_stream4(Bm + (int64_t)w * ldb + (r4[q] << 2), make_float4(f * s[q].x, f * s[q].y, f * s[q].z, f * s[q].w));
+    }
+    // keeps the loads alive when nothing is stored (the condition never holds for finite data)
+    if (cols_out == 0 && s[0].x != s[0].x && Bm != nullptr) Bm[0] = s[0].x;
+}
+
+}  // namespace
+
+// n is a multiple of 4 (whole 16-byte row groups); large_tiles selects the launch shape the library uses above 8 M rows
+void launch_traffic_model(fosi_ctx* ctx, const float* A, int64_t lda, int cols_in, float* Bm, int64_t ldb, int cols_out,
+                          int64_t n, bool large_tiles) {
+    const int64_t n4 = n >> 2;
+    if (large_tiles) {
+        const int64_t tiles = (n4 + 8 * kThreads - 1) / (8 * kThreads);
+        hipLaunchKernelGGL((k_traffic_model<8, 4>), dim3((unsigned)tiles), dim3(kThreads), 0, ctx->stream, A, lda, cols_in,
+                           Bm, ldb, cols_out, n4);
+    } else {
+        const int64_t tiles = (n4 + 4 * kThreads - 1) / (4 * kThreads);
+        hipLaunchKernelGGL((k_traffic_model<4, 8>), dim3((unsigned)tiles), dim3(kThreads), 0, ctx->stream, A, lda, cols_in,
+                           Bm, ldb, cols_out, n4);
+    }
+}
+
+
 }  // namespace fosi

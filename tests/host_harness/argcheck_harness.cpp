@@ -61,6 +61,7 @@ int main() {
     EXPECT(fosi_step_adamw(nullptr, 8, 1, dummy, 8, a, dummy, nullptr, dummy, dummy, dummy, dummy, 1, &ap) == FOSI_ERR_INVALID_ARG);
     EXPECT(fosi_admm_begin(nullptr, 8, 1.f, dummy, dummy, dummy) == FOSI_ERR_INVALID_ARG);
     EXPECT(fosi_admm_end(nullptr, 8, 1.f, dummy, dummy, dummy) == FOSI_ERR_INVALID_ARG);
+    EXPECT(fosi_traffic_model(nullptr, 8, dummy, 8, 1, dummy, 8, 1) == FOSI_ERR_INVALID_ARG);
     EXPECT(fosi_profile_enable(nullptr, 1) == FOSI_ERR_INVALID_ARG && fosi_profile_reset(nullptr) == FOSI_ERR_INVALID_ARG);
     EXPECT(fosi_profile_read(nullptr, 0, &i64, &d0, &d1) == FOSI_ERR_INVALID_ARG);
     // the entry point without a context checks its arguments before it looks for a device
