@@ -1350,6 +1350,8 @@ void launch_complement_reproject(fosi_ctx* ctx, int opt, const float* V, int64_t
     // waves instead of 14 + 14 + 12 over three: one exchange partner less per tile), 32 beyond; no empty wave
     int per_wave = ctx->tun.step_cols_per_wave;
     if (per_wave != 16 && per_wave != 24 && per_wave != 32) per_wave = rv <= 32 ? 16 : rv <= 192 ? 24 : 32;
+    // the AdamW variant carries two more state vectors per row and does not fit 24 columns in registers
+    if (opt == 1 && ctx->tun.step_cols_per_wave == 0 && rv <= 128) per_wave = 16;
     int S = (rv + per_wave - 1) / per_wave;
     if (S < 1) S = 1;
     if (S > 8) S = 8;
