@@ -41,17 +41,24 @@ __device__ __forceinline__ void store_stream4(float* p, const float4 v) {
 // as dirty streaming data.  Used where a kernel rewrites a vector in place and a long read-only sweep follows
 // (the Gram-Schmidt subtraction before the operator's project sweep): with the plain streaming store that next
 // sweep runs ~1.5 % slower while the L2s still write back (1.949 -> 1.921 ms on the 128-column project sweep of the
-// n = 25.6 M workload; for the expand sweep's own output the two policies measure the same).  No builtin
-// selects this combination of cache bits for a 16-byte store, hence the assembly.  The s_nop belongs to it: on
-// gfx940-class hardware a vector instruction must not overwrite the data registers of a store of more than 8 bytes
-// within two wait states of it; the compiler pads its own stores but cannot see into an asm statement, and in the
-// kernels that go on computing with the stored value (sum of squares, local dot products) it did schedule such a
-// write right behind the store -- corrupted vector elements under memory pressure, non-finite recurrences at
-// n = 25.6 M -- until the padding was added here.
-__device__ __forceinline__ void store_through4(float* p, const float4 v) {
+// n = 25.6 M workload; for the expand sweep's own output the two policies measure the same).  No builtin selects
+// this combination of cache bits for a 16-byte store through a plain pointer, but the raw buffer store takes the
+// bits as an operand: the store goes through a buffer descriptor (wave-uniform base and extent, per-lane byte
+// offset) and stays an instruction the compiler schedules itself -- it, not this file, keeps the hardware's rule
+// that the data registers of a store wider than 8 bytes are not overwritten within two wait states.  (An
+// earlier version issued global_store_dwordx4 from an asm statement; the compiler could not see into it and
+// scheduled such a write right behind it: corrupted elements at n = 25.6 M until padding was added by hand.)
+// Stores beyond the descriptor's extent are dropped by the hardware.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kBufferStoreSc1Nt = 16 | 2;     // cache-policy operand of the raw buffer store: sc1 (bit 4), nt (bit 1)
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t store_window(float* base, int64_t bytes) {
+    // untyped 32-bit elements, no swizzle; the extent saturates below 4 GiB (callers pass at most one tile)
+    return __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)(bytes < 0x7fffffff ? bytes : 0x7fffffff), 0x00020000);
+}
+__device__ __forceinline__ void store_through4(__amdgpu_buffer_rsrc_t window, uint32_t byte_offset, const float4 v) {
     f32x4 t;
     t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
-    asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(t) : "memory");
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, t), window, (int)byte_offset, 0, kBufferStoreSc1Nt);
 }
 
 __device__ __forceinline__ double wave_sum(double v) {
@@ -455,6 +462,9 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
         }
         double s[RPT][4];
         accumulate_columns<RPT, CU>(A, lda, ncols, d, rc, s);
+        // this tile's part of the output as a store window (uniform: t is the same in every lane)
+        const int64_t tile_groups = n4 - t * tile < tile ? n4 - t * tile : tile;
+        const __amdgpu_buffer_rsrc_t window = store_window(out + ((t * tile) << 2), tile_groups << 4);
 #pragma unroll
         for (int q = 0; q < RPT; ++q) {
             if (r4[q] >= n4) continue;
@@ -477,7 +487,7 @@ __global__ __launch_bounds__(kThreads) void k_combine_columns(
             }
             if (oscale != nullptr) { o0 *= osc; o1 *= osc; o2 *= osc; o3 *= osc; }
             const float4 o = make_float4((float)o0, (float)o1, (float)o2, (float)o3);
-            if (HAS_Y) store_through4(out + (r4[q] << 2), o);     // in-place rewrite, a read sweep follows
+            if (HAS_Y) store_through4(window, (uint32_t)((q * kThreads + tid) << 4), o);   // in-place rewrite, a read sweep follows
             else store_stream4(out + (r4[q] << 2), o);
             if (NORM || LDOT) nrm = fma((double)o.x, (double)o.x, fma((double)o.y, (double)o.y,
                                     fma((double)o.z, (double)o.z, fma((double)o.w, (double)o.w, nrm))));
