@@ -1392,6 +1392,7 @@ void launch_complement_reproject(fosi_ctx* ctx, int opt, const float* V, int64_t
     else if (cw <= 8) FOSI_CR(8);
     else if (cw <= 12) FOSI_CR(12);
     else if (cw <= 16) FOSI_CR(16);
+    else if (cw <= 20) FOSI_CR(20);
     else if (cw <= 24) FOSI_CR(24);
     else FOSI_CR(32);
 #undef FOSI_CR
