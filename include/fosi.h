@@ -105,8 +105,10 @@ fosi_status hvp_diag_create(fosi_ctx* ctx, int64_t n, const float* d_dev, fosi_h
 /* Generalised Gauss-Newton matrix of the mean softmax cross-entropy of a linear
  * classifier, logits = X W:  H v = X^T[(diag(p_b) - p_b p_b^T)(X V)_b]_b / B with
  * V = v viewed as d x C row-major, n = d*C.  X_dev: B x d row-major, W_dev:
- * d x C row-major.  The operator caches P = softmax(X W) and two B x C work
- * matrices in device memory it allocates (freed by hvp_destroy). */
+ * d x C row-major.  The operator caches P = softmax(X W), up to eight B x C
+ * matrices of partial products and a transposed copy of X in device memory it
+ * allocates (freed by hvp_destroy); X_dev is read at creation and at every apply
+ * and must not change while the operator lives. */
 fosi_status hvp_softmax_ggn_create(fosi_ctx* ctx, int B, int d, int C, const float* X_dev,
                                    const float* W_dev, fosi_hvp** out);
 /* The same operator for a data matrix stored in bf16 (X_bf16_dev: B x d row-major, raw 16-bit

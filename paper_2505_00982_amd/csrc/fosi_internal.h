@@ -119,6 +119,8 @@ struct fosi_hvp {
     const float* W = nullptr;
     float* P = nullptr;     // B x C softmax probabilities
     float* Z = nullptr;     // B x C work
+    float* XT = nullptr;    // fp32 path: d x ldxt transposed copy of X (owned), so that both products stage k-major tiles
+    int ldxt = 0;
     bool bf16 = false;      // data matrix given in bf16: split-operand bf16 matrix-core path
     const unsigned short* Xb = nullptr;   // B x d bf16 (caller's)
     unsigned short* XTb = nullptr;        // d x B bf16 (transposed copy, owned)

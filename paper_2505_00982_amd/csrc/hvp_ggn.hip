@@ -5,7 +5,10 @@
 // softmax-Jacobian.  The shapes are small (B x d x C = 512 x 2048 x 1000 in the
 // reference workload: 2 x 2.1 GFLOP), so the first GEMM is split along K to
 // give every CU a tile; the partial products are summed inside the
-// softmax-Jacobian kernel, in a fixed order.
+// softmax-Jacobian kernel, in a fixed order.  Both products take their A operand
+// k-major (K x M): the second one reads X as it is (k = batch index), the first
+// one a transposed copy of X made once per operator, so that every tile goes
+// into LDS with 16-byte writes.
 #include "fosi_internal.h"
 
 namespace fosi {
@@ -44,10 +47,10 @@ constexpr int TK = 16;                     // K-step of the generic kernel
 constexpr int FK = 32;                     // K-step of the aligned-shape kernel (plans use multiples of FK)
 constexpr int LDT = TM + 4;
 
-// C[z] (M x N, row-major, ldc) = scale * A[:, kz] * B[kz, :]   over the K range of split z.
-// A is M x K row-major (A_KM == false) or given transposed as K x M row-major (A_KM == true).
-// B is K x N row-major.  VEC: every row start and every 4-column group is 16-byte aligned.
-template <bool A_KM, bool VEC>
+// C[z] (M x N, row-major, ldc) = scale * A^T[:, kz] * B[kz, :]   over the K range of split z.
+// A is given k-major (K x M row-major, lda), B is K x N row-major.  VEC: every row start and every 4-column
+// group is 16-byte aligned.
+template <bool VEC>
 __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, int lda, const float* __restrict__ Bm,
                                                   int ldb, float* __restrict__ Cout, int ldc, int M, int N, int K,
                                                   int klen, int nsplit, int64_t cstride, float scale) {
@@ -62,8 +65,7 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, i
     const int kend = min(K, kbeg + klen);
 
     // this thread's slots in the two tiles
-    const int bk = tid >> 4, bn4 = (tid & 15) * 4;          // B tile (and A tile when A_KM): row k, 4 columns
-    const int am = tid >> 2, ak4 = (tid & 3) * 4;           // A tile when stored M x K: row m, 4 k-values
+    const int bk = tid >> 4, bn4 = (tid & 15) * 4;          // both tiles: row k, 4 columns
     float ra[4], rb[4];
 
     auto load = [&](int k0) {
@@ -78,7 +80,7 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, i
                 for (int i = 0; i < 4; ++i) rb[i] = (k < kend && n + i < N) ? p[i] : 0.f;
             }
         }
-        if (A_KM) {
+        {   // A tile
             const int k = k0 + bk, m = m0 + bn4;
             const float* p = A + (int64_t)k * lda + m;
             if (VEC && k < kend && m + 3 < M) {
@@ -88,28 +90,13 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, i
 #pragma unroll
                 for (int i = 0; i < 4; ++i) ra[i] = (k < kend && m + i < M) ? p[i] : 0.f;
             }
-        } else {
-            const int m = m0 + am, k = k0 + ak4;
-            const float* p = A + (int64_t)m * lda + k;
-            if (VEC && m < M && k + 3 < kend) {
-                const float4 v = *reinterpret_cast<const float4*>(p);
-                ra[0] = v.x; ra[1] = v.y; ra[2] = v.z; ra[3] = v.w;
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) ra[i] = (m < M && k + i < kend) ? p[i] : 0.f;
-            }
         }
     };
     auto store = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) Bs[buf][bk][bn4 + i] = rb[i];
-        if (A_KM) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) As[buf][bk][bn4 + i] = ra[i];
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) As[buf][ak4 + i][am] = ra[i];
-        }
+        for (int i = 0; i < 4; ++i) As[buf][bk][bn4 + i] = ra[i];
     };
 
     floatx16 acc;
@@ -163,7 +150,7 @@ __device__ __forceinline__ float4 mask4(const float4 v, const unsigned int keep)
 // FULLK: K and the split length are multiples of FK, so every K-step of a split is whole: the addresses then
 // advance by a constant per K-step and the bounds masks do not depend on k (computed once); otherwise every load
 // clamps its k index and every LDS write masks it, ~40 more vector instructions per K-step.
-template <bool A_KM, bool FULLK>
+template <bool FULLK>
 __global__ __launch_bounds__(256) void k_gemm_f32_aligned(const float* __restrict__ A, int lda,
                                                           const float* __restrict__ Bm, int ldb,
                                                           float* __restrict__ Cout, int ldc, int M, int N, int K,
@@ -179,21 +166,16 @@ __global__ __launch_bounds__(256) void k_gemm_f32_aligned(const float* __restric
     const int kend = min(K, kbeg + klen);
     const int nk = (kend - kbeg + FK - 1) / FK;
 
-    // k-major tiles (B always, A when it is stored K x M): rows kr and kr + 16, four columns from c4
+    // both tiles are k-major: rows kr and kr + 16, four columns from c4
     const int kr = tid >> 4, c4 = (tid & 15) * 4;
-    // A stored M x K: rows am and am + 32 of the tile, four k values from ak4
-    const int am = tid >> 3, ak4 = (tid & 7) * 4;
     float4 ra[FPF][2], rb[FPF][2];
 
     // k-independent parts: clamped column / row offsets and the masks of the m and n bounds
     const int nb = n0 + c4, ma = m0 + c4;
     const unsigned int keep_n = nb < N ? 0xffffffffu : 0u;
-    const unsigned int keep_mk = ma < M ? 0xffffffffu : 0u;                       // A stored K x M
-    const unsigned int keep_m0 = m0 + am < M ? 0xffffffffu : 0u, keep_m1 = m0 + am + 32 < M ? 0xffffffffu : 0u;
+    const unsigned int keep_mk = ma < M ? 0xffffffffu : 0u;
     const float* pB = Bm + (nb < N ? nb : 0);
-    const float* pAk = A + (ma < M ? ma : 0);                                      // A stored K x M: + k * lda
-    const float* pAm0 = A + (int64_t)(m0 + am < M ? m0 + am : 0) * lda;            // A stored M x K: + k
-    const float* pAm1 = A + (int64_t)(m0 + am + 32 < M ? m0 + am + 32 : 0) * lda;
+    const float* pAk = A + (ma < M ? ma : 0);                                      // + k * lda
 
     auto load = [&](int kt, float4* qa, float4* qb) {
         if (FULLK) {
@@ -202,8 +184,7 @@ __global__ __launch_bounds__(256) void k_gemm_f32_aligned(const float* __restric
             for (int j = 0; j < 2; ++j) {
                 const int k = k0 + kr + 16 * j;
                 qb[j] = *reinterpret_cast<const float4*>(pB + (int64_t)k * ldb);
-                if (A_KM) qa[j] = *reinterpret_cast<const float4*>(pAk + (int64_t)k * lda);
-                else qa[j] = *reinterpret_cast<const float4*>((j == 0 ? pAm0 : pAm1) + k0 + ak4);
+                qa[j] = *reinterpret_cast<const float4*>(pAk + (int64_t)k * lda);
             }
         } else {
             const int k0 = kbeg + kt * FK;
@@ -212,12 +193,7 @@ __global__ __launch_bounds__(256) void k_gemm_f32_aligned(const float* __restric
                 const int k = k0 + kr + 16 * j;
                 const int kc = k < kend ? k : 0;
                 qb[j] = *reinterpret_cast<const float4*>(pB + (int64_t)kc * ldb);
-                if (A_KM) {
-                    qa[j] = *reinterpret_cast<const float4*>(pAk + (int64_t)kc * lda);
-                } else {
-                    const int ka = k0 + ak4;
-                    qa[j] = *reinterpret_cast<const float4*>((j == 0 ? pAm0 : pAm1) + (ka < kend ? ka : 0));
-                }
+                qa[j] = *reinterpret_cast<const float4*>(pAk + (int64_t)kc * lda);
             }
         }
     };
@@ -230,16 +206,7 @@ __global__ __launch_bounds__(256) void k_gemm_f32_aligned(const float* __restric
             const int k = k0 + kr + 16 * j;
             const unsigned int keep_k = FULLK ? in_range : (k < kend ? 0xffffffffu : 0u);
             *reinterpret_cast<float4*>(&Bs[buf][kr + 16 * j][c4]) = mask4(qb[j], keep_k & keep_n);
-            if (A_KM) {
-                *reinterpret_cast<float4*>(&As[buf][kr + 16 * j][c4]) = mask4(qa[j], keep_k & keep_mk);
-            } else {
-                const unsigned int keep_ka = FULLK ? in_range : (k0 + ak4 < kend ? 0xffffffffu : 0u);
-                const float4 v = mask4(qa[j], keep_ka & (j == 0 ? keep_m0 : keep_m1));
-                As[buf][ak4 + 0][am + 32 * j] = v.x;
-                As[buf][ak4 + 1][am + 32 * j] = v.y;
-                As[buf][ak4 + 2][am + 32 * j] = v.z;
-                As[buf][ak4 + 3][am + 32 * j] = v.w;
-            }
+            *reinterpret_cast<float4*>(&As[buf][kr + 16 * j][c4]) = mask4(qa[j], keep_k & keep_mk);
         }
     };
 
@@ -609,6 +576,19 @@ __global__ __launch_bounds__(256) void k_transpose_u16(const unsigned short* __r
         if (c0 + i < cols && r0 + tx < rows) XT[(int64_t)(c0 + i) * rows + r0 + tx] = tile[tx][i];
 }
 
+// XT[j, i] = X[i, j] for an fp32 matrix (rows x cols row-major -> cols x ldt row-major, ldt >= rows), once per operator.
+__global__ __launch_bounds__(256) void k_transpose_f32(const float* __restrict__ X, int rows, int cols,
+                                                       float* __restrict__ XT, int ldt) {
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+    const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+    for (int i = ty; i < 32; i += 8)
+        if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = X[(int64_t)(r0 + i) * cols + c0 + tx];
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8)
+        if (c0 + i < cols && r0 + tx < rows) XT[(int64_t)(c0 + i) * ldt + r0 + tx] = tile[tx][i];
+}
+
 // out[i] = scale * sum_s parts[s][i]  (fixed order)
 __global__ __launch_bounds__(256) void k_sum_splits(const float* __restrict__ parts, int nsplit, int64_t pstride,
                                                     int64_t count, float scale, float* __restrict__ out) {
@@ -635,7 +615,6 @@ GemmPlan plan_split(int M, int N, int K, int sm_count) {
     return {s, klen};
 }
 
-template <bool A_KM>
 void launch_gemm(fosi_ctx* ctx, const float* A, int lda, const float* Bm, int ldb, float* Cout, int ldc, int M, int N,
                  int K, GemmPlan plan, int64_t cstride, float scale) {
     const int tiles = ((N + TN - 1) / TN) * ((M + TM - 1) / TM) * plan.nsplit;
@@ -643,18 +622,18 @@ void launch_gemm(fosi_ctx* ctx, const float* A, int lda, const float* Bm, int ld
     const bool vec = (lda % 4 == 0) && (ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(A) & 15) == 0) &&
                      ((reinterpret_cast<uintptr_t>(Bm) & 15) == 0);
     // whole 16-byte groups only: N (columns of B) and the contiguous extent of A (M if stored K x M, else K)
-    const bool aligned = vec && N % 4 == 0 && (A_KM ? M : K) % 4 == 0 && plan.klen % FK == 0;
+    const bool aligned = vec && N % 4 == 0 && M % 4 == 0 && plan.klen % FK == 0;
     if (aligned && K % FK == 0)
-        hipLaunchKernelGGL((k_gemm_f32_aligned<A_KM, true>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M,
+        hipLaunchKernelGGL((k_gemm_f32_aligned<true>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M,
                            N, K, plan.klen, plan.nsplit, cstride, scale);
     else if (aligned)
-        hipLaunchKernelGGL((k_gemm_f32_aligned<A_KM, false>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M,
+        hipLaunchKernelGGL((k_gemm_f32_aligned<false>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M,
                            N, K, plan.klen, plan.nsplit, cstride, scale);
     else if (vec)
-        hipLaunchKernelGGL((k_gemm_f32<A_KM, true>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N, K,
+        hipLaunchKernelGGL((k_gemm_f32<true>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N, K,
                            plan.klen, plan.nsplit, cstride, scale);
     else
-        hipLaunchKernelGGL((k_gemm_f32<A_KM, false>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N, K,
+        hipLaunchKernelGGL((k_gemm_f32<false>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N, K,
                            plan.klen, plan.nsplit, cstride, scale);
 }
 
@@ -719,11 +698,19 @@ fosi_status ggn_prepare(fosi_hvp* op) {
         return check_hip(ctx, hipGetLastError(), "softmax-GGN prepare");
     }
     const GemmPlan plan = plan_split(B, C, d, ctx->sm_count);
+    op->ldxt = (B + 3) / 4 * 4;
     if (hipMalloc(reinterpret_cast<void**>(&op->P), bc * sizeof(float)) != hipSuccess ||
-        hipMalloc(reinterpret_cast<void**>(&op->Z), bc * sizeof(float) * plan.nsplit) != hipSuccess)
+        hipMalloc(reinterpret_cast<void**>(&op->Z), bc * sizeof(float) * plan.nsplit) != hipSuccess ||
+        hipMalloc(reinterpret_cast<void**>(&op->XT), (size_t)d * op->ldxt * sizeof(float)) != hipSuccess)
         return fail(ctx, FOSI_ERR_NOMEM, "softmax-GGN work buffers");
+    // X is constant over the operator's life: a transposed copy lets the first product stage its A tiles k-major
+    // with 16-byte LDS writes like the second one (with X itself the tile has to be transposed on the way into
+    // LDS, four scalar writes per 16 bytes with four-way bank conflicts)
+    if (op->ldxt != B) (void)hipMemsetAsync(op->XT, 0, (size_t)d * op->ldxt * sizeof(float), ctx->stream);
+    hipLaunchKernelGGL(k_transpose_f32, dim3((d + 31) / 32, (B + 31) / 32), dim3(256), 0, ctx->stream, op->X, B, d, op->XT,
+                       op->ldxt);
     // P = softmax(X W)
-    launch_gemm<false>(ctx, op->X, d, op->W, C, op->Z, C, B, C, d, plan, (int64_t)bc, 1.f);
+    launch_gemm(ctx, op->XT, op->ldxt, op->W, C, op->Z, C, B, C, d, plan, (int64_t)bc, 1.f);
     hipLaunchKernelGGL(k_row_softmax, dim3(B), dim3(256), 0, ctx->stream, op->Z, plan.nsplit, (int64_t)bc, C, op->P);
     return check_hip(ctx, hipGetLastError(), "softmax-GGN prepare");
 }
@@ -755,9 +742,9 @@ fosi_status ggn_apply(fosi_hvp* op, const float* v, float* hv) {
     }
     const GemmPlan plan = plan_split(B, C, d, ctx->sm_count);
     // Z = X V (split along d), Y = softmax-Jacobian rows of Z, hv = X^T Y / B
-    launch_gemm<false>(ctx, op->X, d, v, C, op->Z, C, B, C, d, plan, bc, 1.f);
+    launch_gemm(ctx, op->XT, op->ldxt, v, C, op->Z, C, B, C, d, plan, bc, 1.f);
     launch_softmax_jacobian(ctx, op->Z, plan.nsplit, bc, B, C, op->P);
-    launch_gemm<true>(ctx, op->X, d, op->Z, C, hv, C, d, C, B, GemmPlan{1, (B + FK - 1) / FK * FK}, 0,
+    launch_gemm(ctx, op->X, d, op->Z, C, hv, C, d, C, B, GemmPlan{1, (B + FK - 1) / FK * FK}, 0,
                       1.f / (float)B);
     return FOSI_OK;
 }
@@ -766,6 +753,8 @@ void ggn_release(fosi_hvp* op) {
     if (op->P != nullptr) (void)hipFree(op->P);
     if (op->Z != nullptr) (void)hipFree(op->Z);
     if (op->XTb != nullptr) (void)hipFree(op->XTb);
+    if (op->XT != nullptr) (void)hipFree(op->XT);
+    op->XT = nullptr;
     if (op->Y2 != nullptr) (void)hipFree(op->Y2);
     if (op->S1 != nullptr) (void)hipFree(op->S1);
     if (op->S2 != nullptr) (void)hipFree(op->S2);
