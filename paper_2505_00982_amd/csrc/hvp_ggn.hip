@@ -150,28 +150,35 @@ __device__ __forceinline__ float4 mask4(const float4 v, const unsigned int keep)
 // FULLK: K and the split length are multiples of FK, so every K-step of a split is whole: the addresses then
 // advance by a constant per K-step and the bounds masks do not depend on k (computed once); otherwise every load
 // clamps its k index and every LDS write masks it, ~40 more vector instructions per K-step.
-template <bool FULLK>
-__global__ __launch_bounds__(256) void k_gemm_f32_aligned(const float* __restrict__ A, int lda,
-                                                          const float* __restrict__ Bm, int ldb,
-                                                          float* __restrict__ Cout, int ldc, int M, int N, int K,
-                                                          int klen, int nsplit, int64_t cstride, float scale) {
-    __shared__ __attribute__((aligned(16))) float As[2][FK][LDT];   // [k][m]
-    __shared__ __attribute__((aligned(16))) float Bs[2][FK][LDT];   // [k][n]
+// WM: the workgroup tile is 64 WM rows x 64 columns, computed by 4 WM waves (32 x 32 each).  WM = 2 (512 threads, one
+// workgroup per CU) shares each B tile among twice as many rows: a quarter less operand traffic through the L1 per
+// flop, which is what these products wait for.
+template <bool FULLK, int WM>
+__global__ __launch_bounds__(256 * WM) void k_gemm_f32_aligned(const float* __restrict__ A, int lda,
+                                                               const float* __restrict__ Bm, int ldb,
+                                                               float* __restrict__ Cout, int ldc, int M, int N, int K,
+                                                               int klen, int nsplit, int64_t cstride, float scale) {
+    constexpr int TMV = TM * WM;                                    // rows of the workgroup tile
+    constexpr int NB = 2 / WM;                                      // 16-byte loads per thread and K-step: B tile (A: 2)
+    __shared__ __attribute__((aligned(16))) float As[2][FK][TMV + 4];   // [k][m]
+    __shared__ __attribute__((aligned(16))) float Bs[2][FK][LDT];       // [k][n]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32;
     int tn, tm, tz;
-    if (!xcd_tile((N + TN - 1) / TN, (M + TM - 1) / TM, nsplit, tn, tm, tz)) return;
-    const int m0 = tm * TM, n0 = tn * TN;
+    if (!xcd_tile((N + TN - 1) / TN, (M + TMV - 1) / TMV, nsplit, tn, tm, tz)) return;
+    const int m0 = tm * TMV, n0 = tn * TN;
     const int kbeg = tz * klen;
     const int kend = min(K, kbeg + klen);
     const int nk = (kend - kbeg + FK - 1) / FK;
 
-    // both tiles are k-major: rows kr and kr + 16, four columns from c4
+    // both tiles are k-major.  B: rows kr + 16 WM j (j < NB), four columns from c4; A: rows kra + 16 j (j < 2),
+    // four columns from c4a
     const int kr = tid >> 4, c4 = (tid & 15) * 4;
-    float4 ra[FPF][2], rb[FPF][2];
+    const int kra = tid / (16 * WM), c4a = (tid % (16 * WM)) * 4;
+    float4 ra[FPF][2], rb[FPF][NB];
 
     // k-independent parts: clamped column / row offsets and the masks of the m and n bounds
-    const int nb = n0 + c4, ma = m0 + c4;
+    const int nb = n0 + c4, ma = m0 + c4a;
     const unsigned int keep_n = nb < N ? 0xffffffffu : 0u;
     const unsigned int keep_mk = ma < M ? 0xffffffffu : 0u;
     const float* pB = Bm + (nb < N ? nb : 0);
@@ -181,19 +188,20 @@ __global__ __launch_bounds__(256) void k_gemm_f32_aligned(const float* __restric
         if (FULLK) {
             const int k0 = kbeg + min(kt, nk - 1) * FK;      // past the end: the last K-step again (never stored)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int k = k0 + kr + 16 * j;
-                qb[j] = *reinterpret_cast<const float4*>(pB + (int64_t)k * ldb);
-                qa[j] = *reinterpret_cast<const float4*>(pAk + (int64_t)k * lda);
-            }
+            for (int j = 0; j < NB; ++j) qb[j] = *reinterpret_cast<const float4*>(pB + (int64_t)(k0 + kr + 16 * WM * j) * ldb);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) qa[j] = *reinterpret_cast<const float4*>(pAk + (int64_t)(k0 + kra + 16 * j) * lda);
         } else {
             const int k0 = kbeg + kt * FK;
 #pragma unroll
+            for (int j = 0; j < NB; ++j) {
+                const int k = k0 + kr + 16 * WM * j;
+                qb[j] = *reinterpret_cast<const float4*>(pB + (int64_t)(k < kend ? k : 0) * ldb);
+            }
+#pragma unroll
             for (int j = 0; j < 2; ++j) {
-                const int k = k0 + kr + 16 * j;
-                const int kc = k < kend ? k : 0;
-                qb[j] = *reinterpret_cast<const float4*>(pB + (int64_t)kc * ldb);
-                qa[j] = *reinterpret_cast<const float4*>(pAk + (int64_t)kc * lda);
+                const int k = k0 + kra + 16 * j;
+                qa[j] = *reinterpret_cast<const float4*>(pAk + (int64_t)(k < kend ? k : 0) * lda);
             }
         }
     };
@@ -202,11 +210,16 @@ __global__ __launch_bounds__(256) void k_gemm_f32_aligned(const float* __restric
         // (FULLK: a K-step past the range, reached only through the rounded-up trip count, must store zeros too)
         const unsigned int in_range = kt < nk ? 0xffffffffu : 0u;
 #pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int kl = kr + 16 * WM * j;
+            const unsigned int keep_k = FULLK ? in_range : (k0 + kl < kend ? 0xffffffffu : 0u);
+            *reinterpret_cast<float4*>(&Bs[buf][kl][c4]) = mask4(qb[j], keep_k & keep_n);
+        }
+#pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const int k = k0 + kr + 16 * j;
-            const unsigned int keep_k = FULLK ? in_range : (k < kend ? 0xffffffffu : 0u);
-            *reinterpret_cast<float4*>(&Bs[buf][kr + 16 * j][c4]) = mask4(qb[j], keep_k & keep_n);
-            *reinterpret_cast<float4*>(&As[buf][kr + 16 * j][c4]) = mask4(qa[j], keep_k & keep_mk);
+            const int kl = kra + 16 * j;
+            const unsigned int keep_k = FULLK ? in_range : (k0 + kl < kend ? 0xffffffffu : 0u);
+            *reinterpret_cast<float4*>(&As[buf][kl][c4a]) = mask4(qa[j], keep_k & keep_mk);
         }
     };
 
@@ -602,32 +615,43 @@ __global__ __launch_bounds__(256) void k_sum_splits(const float* __restrict__ pa
 
 struct GemmPlan {
     int nsplit, klen;
+    int wm = 1;          // row-tile multiple of the aligned kernel (1: 64 rows, two workgroups per CU; 2: 128 rows, one)
 };
 
 GemmPlan plan_split(int M, int N, int K, int sm_count) {
-    const int tiles = ((M + TM - 1) / TM) * ((N + TN - 1) / TN);
-    int s = (2 * sm_count) / (tiles > 0 ? tiles : 1);
+    // the tall tile where the output has the rows for it; the target is then one workgroup of 512 threads per CU
+    const int wm = M >= 2 * TM ? 2 : 1;
+    const int tiles = ((M + TM * wm - 1) / (TM * wm)) * ((N + TN - 1) / TN);
+    int s = (2 / wm * sm_count) / (tiles > 0 ? tiles : 1);
     if (s < 1) s = 1;
     if (s > 8) s = 8;
     int klen = ((K + s - 1) / s + FK - 1) / FK * FK;
     if (klen < FK) klen = FK;
     s = (K + klen - 1) / klen;
-    return {s, klen};
+    return {s, klen, wm};
 }
 
 void launch_gemm(fosi_ctx* ctx, const float* A, int lda, const float* Bm, int ldb, float* Cout, int ldc, int M, int N,
                  int K, GemmPlan plan, int64_t cstride, float scale) {
     const int tiles = ((N + TN - 1) / TN) * ((M + TM - 1) / TM) * plan.nsplit;
     const dim3 grid((tiles + 7) / 8 * 8);
+    const int tiles_tall = ((N + TN - 1) / TN) * ((M + 2 * TM - 1) / (2 * TM)) * plan.nsplit;
+    const dim3 grid_tall((tiles_tall + 7) / 8 * 8);
     const bool vec = (lda % 4 == 0) && (ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(A) & 15) == 0) &&
                      ((reinterpret_cast<uintptr_t>(Bm) & 15) == 0);
     // whole 16-byte groups only: N (columns of B) and the contiguous extent of A (M if stored K x M, else K)
     const bool aligned = vec && N % 4 == 0 && M % 4 == 0 && plan.klen % FK == 0;
-    if (aligned && K % FK == 0)
-        hipLaunchKernelGGL((k_gemm_f32_aligned<true>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M,
+    if (aligned && K % FK == 0 && plan.wm == 2)
+        hipLaunchKernelGGL((k_gemm_f32_aligned<true, 2>), grid_tall, dim3(512), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc,
+                           M, N, K, plan.klen, plan.nsplit, cstride, scale);
+    else if (aligned && plan.wm == 2)
+        hipLaunchKernelGGL((k_gemm_f32_aligned<false, 2>), grid_tall, dim3(512), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc,
+                           M, N, K, plan.klen, plan.nsplit, cstride, scale);
+    else if (aligned && K % FK == 0)
+        hipLaunchKernelGGL((k_gemm_f32_aligned<true, 1>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M,
                            N, K, plan.klen, plan.nsplit, cstride, scale);
     else if (aligned)
-        hipLaunchKernelGGL((k_gemm_f32_aligned<false>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M,
+        hipLaunchKernelGGL((k_gemm_f32_aligned<false, 1>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M,
                            N, K, plan.klen, plan.nsplit, cstride, scale);
     else if (vec)
         hipLaunchKernelGGL((k_gemm_f32<true>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc, M, N, K,
@@ -744,7 +768,7 @@ fosi_status ggn_apply(fosi_hvp* op, const float* v, float* hv) {
     // Z = X V (split along d), Y = softmax-Jacobian rows of Z, hv = X^T Y / B
     launch_gemm(ctx, op->XT, op->ldxt, v, C, op->Z, C, B, C, d, plan, bc, 1.f);
     launch_softmax_jacobian(ctx, op->Z, plan.nsplit, bc, B, C, op->P);
-    launch_gemm(ctx, op->X, d, op->Z, C, hv, C, d, C, B, GemmPlan{1, (B + FK - 1) / FK * FK}, 0,
+    launch_gemm(ctx, op->X, d, op->Z, C, hv, C, d, C, B, GemmPlan{1, (B + FK - 1) / FK * FK, d >= 2 * TM ? 2 : 1}, 0,
                       1.f / (float)B);
     return FOSI_OK;
 }
