@@ -76,7 +76,9 @@ typedef struct fosi_hvp fosi_hvp;   /* a curvature operator v -> H v bound to a 
  *   FOSI_STEP_WAVES   resident waves per compute unit aimed at by the update's fused second sweep (8)
  *   FOSI_STEP_COLS    columns of V-hat per wave in that sweep: 16, 24 or 32 (default 0: 16 up to 32 columns, else 24)
  *   FOSI_EARLY_BETA   1: beta from the Gram-Schmidt coefficients, normalisation inside the subtraction (default)
- *   FOSI_RITZ_MFMA    1: Ritz vectors on the matrix cores (default); 0: on the vector ALUs */
+ *   FOSI_RITZ_MFMA    1: Ritz vectors on the matrix cores (default); 0: on the vector ALUs
+ *   FOSI_GGN_DIRECT   1: the softmax-GGN products load their operand tiles straight into LDS where the shape allows
+ *                     (default); 0: always stage them through registers */
 fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream);
 /* Bytes of device memory a context holds for itself to serve problems of n rows, m Lanczos steps and r_v = k + l
  * Ritz pairs (partial sums, coefficient vectors, the tridiagonal, flags); every other buffer is the caller's.  The

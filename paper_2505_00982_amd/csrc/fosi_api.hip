@@ -145,6 +145,7 @@ fosi_status fosi_ctx_create(fosi_ctx** out, int device, void* hip_stream) {
     ctx->tun.ritz_mfma = env_int("FOSI_RITZ_MFMA", 1);
     ctx->tun.step_waves_per_cu = env_int("FOSI_STEP_WAVES", 8);
     ctx->tun.step_cols_per_wave = env_int("FOSI_STEP_COLS", 0);
+    ctx->tun.ggn_direct = env_int("FOSI_GGN_DIRECT", 1);
     if (ctx->tun.step_waves_per_cu < 1) ctx->tun.step_waves_per_cu = 1;
 
     const size_t cols1 = kMaxCols + 1;

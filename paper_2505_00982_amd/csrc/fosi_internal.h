@@ -34,6 +34,7 @@ struct Tunables {
     int ritz_mfma;            // 1 (default): Ritz vectors on the matrix cores in 16-wide column blocks; 0: vector ALUs
     int step_waves_per_cu;    // resident wavefronts per CU aimed at by the fused second sweep of the update
     int step_cols_per_wave;   // columns of V-hat a wave of that sweep keeps in registers: 16, 24 or 32; 0 = chosen by width
+    int ggn_direct = 1;              // softmax-GGN products: operand tiles loaded straight into LDS (0: staged through registers)
 };
 
 // Device scratch layout (one allocation per context).

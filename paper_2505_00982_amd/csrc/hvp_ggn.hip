@@ -45,7 +45,7 @@ __device__ __forceinline__ void lds_barrier() {
 constexpr int TM = 64, TN = 64;            // workgroup tile; each of the 4 waves owns a 32 x 32 quadrant
 constexpr int TK = 16;                     // K-step of the generic kernel
 constexpr int FK = 32;                     // K-step of the aligned-shape kernel (plans use multiples of FK)
-constexpr int LDT = TM + 4;
+constexpr int LDT = TM;                    // LDS rows are written and read as whole 16-byte groups: no padding needed
 
 // C[z] (M x N, row-major, ldc) = scale * A^T[:, kz] * B[kz, :]   over the K range of split z.
 // A is given k-major (K x M row-major, lda), B is K x N row-major.  VEC: every row start and every 4-column
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(256 * WM) void k_gemm_f32_aligned(const float* __re
                                                                int klen, int nsplit, int64_t cstride, float scale) {
     constexpr int TMV = TM * WM;                                    // rows of the workgroup tile
     constexpr int NB = 2 / WM;                                      // 16-byte loads per thread and K-step: B tile (A: 2)
-    __shared__ __attribute__((aligned(16))) float As[2][FK][TMV + 4];   // [k][m]
+    __shared__ __attribute__((aligned(16))) float As[2][FK][TMV];       // [k][m]
     __shared__ __attribute__((aligned(16))) float Bs[2][FK][LDT];       // [k][n]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32;
@@ -259,6 +259,109 @@ __global__ __launch_bounds__(256 * WM) void k_gemm_f32_aligned(const float* __re
             }
         }
     }
+    float* Cz = Cout + (int64_t)tz * cstride;
+    const int col = n0 + wn + l32;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm + 8 * (v >> 2) + 4 * half + (v & 3);
+        if (row < M && col < N) Cz[(int64_t)row * ldc + col] = acc[v] * scale;
+    }
+}
+
+// The same product with the operand tiles loaded from global memory straight into LDS (global_load_lds_dwordx4:
+// lane l of a wave deposits its 16 bytes at the wave's LDS base + 16 l, so a wave instruction fills 1 KiB of
+// contiguous LDS -- two rows of a 128-wide tile, four rows of a 64-wide one -- and the rows are stored without
+// padding).  No registers and no LDS-write instructions are spent on staging, which is what the register-staged
+// kernel above waits for.  Three tiles per operand: during K-step t a wave multiplies tile t while tiles t + 1
+// and t + 2 are in flight; the loads of tile t + 2 are issued behind the barrier that opens K-step t, when every
+// wave has finished with tile t - 1, whose buffer they overwrite.  Only for whole K-steps (K and the split length
+// multiples of FK): data lands in LDS unmasked, which is harmless along m and n (a column of A past M or of B past
+// N only reaches outputs that are not stored; its address is clamped to a valid one) but not along k.
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* glb_ptr_t;
+
+template <int WM>
+__global__ __launch_bounds__(256 * WM) void k_gemm_f32_direct(const float* __restrict__ A, int lda,
+                                                              const float* __restrict__ Bm, int ldb,
+                                                              float* __restrict__ Cout, int ldc, int M, int N, int K,
+                                                              int klen, int nsplit, int64_t cstride, float scale) {
+    constexpr int TMV = TM * WM, NW = 4 * WM;
+    constexpr int A_RPI = 256 / TMV, B_RPI = 256 / TN;              // tile rows filled by one wave instruction (1 KiB)
+    constexpr int A_IPW = FK / A_RPI / NW, B_IPW = FK / B_RPI / NW; // instructions per wave and tile
+    __shared__ __attribute__((aligned(16))) float As0[FK][TMV], As1[FK][TMV], As2[FK][TMV];   // [k][m]
+    __shared__ __attribute__((aligned(16))) float Bs0[FK][TN], Bs1[FK][TN], Bs2[FK][TN];      // [k][n]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32;
+    int tn, tm, tz;
+    if (!xcd_tile((N + TN - 1) / TN, (M + TMV - 1) / TMV, nsplit, tn, tm, tz)) return;
+    const int m0 = tm * TMV, n0 = tn * TN;
+    const int kbeg = tz * klen;
+    const int nk = (min(K, kbeg + klen) - kbeg) / FK;
+
+    // this lane's source of every load: row offset inside a wave instruction and clamped column
+    const int a_row = lane / (TMV / 4), a_col = m0 + (lane % (TMV / 4)) * 4;
+    const int b_row = lane / (TN / 4), b_col = n0 + (lane % (TN / 4)) * 4;
+    const int64_t oA = (a_col < M ? a_col : 0) + (int64_t)(kbeg + a_row) * lda;      // float offsets of this lane
+    const int64_t oB = (b_col < N ? b_col : 0) + (int64_t)(kbeg + b_row) * ldb;
+
+    auto issue = [&](int kt, float (*As)[TMV], float (*Bs)[TN]) {
+#pragma unroll
+        for (int i = 0; i < A_IPW; ++i) {
+            const int r = (wave + NW * i) * A_RPI;                  // first tile row of this instruction (uniform)
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(A + oA + (int64_t)(kt * FK + r) * lda), (lds_ptr_t)&As[r][0], 16, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < B_IPW; ++i) {
+            const int r = (wave + NW * i) * B_RPI;
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(Bm + oB + (int64_t)(kt * FK + r) * ldb), (lds_ptr_t)&Bs[r][0], 16, 0, 0);
+        }
+    };
+
+    floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    const int half = lane >> 5, l32 = lane & 31;
+    float av[FK / 2], bv[FK / 2];                                   // a K-step's operands of this lane
+    auto fetch = [&](const float (*As)[TMV], const float (*Bs)[TN]) {
+#pragma unroll
+        for (int i = 0; i < FK / 2; ++i) {
+            av[i] = As[2 * i + half][wm + l32];
+            bv[i] = Bs[2 * i + half][wn + l32];
+        }
+    };
+    auto multiply = [&]() {
+#pragma unroll
+        for (int i = 0; i < FK / 2; ++i) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[i], acc, 0, 0, 0);
+    };
+    // vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the other counters left at their maxima)
+    constexpr int LPT = A_IPW + B_IPW;                              // loads per wave and tile
+    constexpr int kWaitOneTileLeft = 0x0F70 | LPT, kWaitAll = 0x0F70;
+
+    issue(0, As0, Bs0);
+    if (nk > 1) issue(1, As1, Bs1);
+    // one K-step: wait for this wave's part of tile kt (the younger tile may stay in flight), meet the other waves
+    // (their parts have landed too, and they are done with tile kt - 1), request this lane's operands from LDS,
+    // refill tile kt - 1's buffer, multiply.  The LDS reads are issued before the refill on purpose: the compiler
+    // makes an LDS read wait for every direct-to-LDS load it cannot tell apart from the read's own tile, and that is
+    // harmless here, where the only loads in flight are at least a K-step old.
+#define FOSI_KSTEP(kt, Ac, Bc, Ar, Br)                                                       \
+    do {                                                                                     \
+        if ((kt) + 1 < nk) __builtin_amdgcn_s_waitcnt(kWaitOneTileLeft);                     \
+        else __builtin_amdgcn_s_waitcnt(kWaitAll);                                           \
+        __builtin_amdgcn_s_barrier();                                                        \
+        fetch(Ac, Bc);                                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                   \
+        if ((kt) + 2 < nk) issue((kt) + 2, Ar, Br);                                          \
+        __builtin_amdgcn_sched_barrier(0);                                                   \
+        multiply();                                                                          \
+    } while (0)
+    for (int kt = 0; kt < nk; kt += 3) {
+        FOSI_KSTEP(kt, As0, Bs0, As2, Bs2);
+        if (kt + 1 < nk) FOSI_KSTEP(kt + 1, As1, Bs1, As0, Bs0);
+        if (kt + 2 < nk) FOSI_KSTEP(kt + 2, As2, Bs2, As1, Bs1);
+    }
+#undef FOSI_KSTEP
     float* Cz = Cout + (int64_t)tz * cstride;
     const int col = n0 + wn + l32;
 #pragma unroll
@@ -618,9 +721,18 @@ struct GemmPlan {
     int wm = 1;          // row-tile multiple of the aligned kernel (1: 64 rows, two workgroups per CU; 2: 128 rows, one)
 };
 
+// Row-tile multiple: the tall tile shares each B tile among twice the rows (a quarter less operand traffic per flop) but
+// runs as one workgroup of eight waves per CU, whose waves meet at the same barriers; two 64 x 64 workgroups per CU
+// drift apart and cover each other's barriers and LDS latencies.  Measured on d x C = 2048 x 1000 (whole operator):
+// batch 512: 57.9 us with 64 x 64 tiles against 59.0 us; 2048: 164 against 173 us; 8192: 673 against 656 us -- the tall
+// tile pays once there are several rounds of workgroups per CU.
+int tile_rows_multiple(int M, int N, int sm_count) {
+    const int tiles64 = ((M + TM - 1) / TM) * ((N + TN - 1) / TN);
+    return (M >= 2 * TM && tiles64 >= 8 * sm_count) ? 2 : 1;
+}
+
 GemmPlan plan_split(int M, int N, int K, int sm_count) {
-    // the tall tile where the output has the rows for it; the target is then one workgroup of 512 threads per CU
-    const int wm = M >= 2 * TM ? 2 : 1;
+    const int wm = tile_rows_multiple(M, N, sm_count);
     const int tiles = ((M + TM * wm - 1) / (TM * wm)) * ((N + TN - 1) / TN);
     int s = (2 / wm * sm_count) / (tiles > 0 ? tiles : 1);
     if (s < 1) s = 1;
@@ -641,7 +753,13 @@ void launch_gemm(fosi_ctx* ctx, const float* A, int lda, const float* Bm, int ld
                      ((reinterpret_cast<uintptr_t>(Bm) & 15) == 0);
     // whole 16-byte groups only: N (columns of B) and the contiguous extent of A (M if stored K x M, else K)
     const bool aligned = vec && N % 4 == 0 && M % 4 == 0 && plan.klen % FK == 0;
-    if (aligned && K % FK == 0 && plan.wm == 2)
+    if (aligned && K % FK == 0 && plan.wm == 2 && ctx->tun.ggn_direct)
+        hipLaunchKernelGGL((k_gemm_f32_direct<2>), grid_tall, dim3(512), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc,
+                           M, N, K, plan.klen, plan.nsplit, cstride, scale);
+    else if (aligned && K % FK == 0 && plan.wm == 1 && ctx->tun.ggn_direct)
+        hipLaunchKernelGGL((k_gemm_f32_direct<1>), grid, dim3(256), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc,
+                           M, N, K, plan.klen, plan.nsplit, cstride, scale);
+    else if (aligned && K % FK == 0 && plan.wm == 2)
         hipLaunchKernelGGL((k_gemm_f32_aligned<true, 2>), grid_tall, dim3(512), 0, ctx->stream, A, lda, Bm, ldb, Cout, ldc,
                            M, N, K, plan.klen, plan.nsplit, cstride, scale);
     else if (aligned && plan.wm == 2)
@@ -768,7 +886,7 @@ fosi_status ggn_apply(fosi_hvp* op, const float* v, float* hv) {
     // Z = X V (split along d), Y = softmax-Jacobian rows of Z, hv = X^T Y / B
     launch_gemm(ctx, op->XT, op->ldxt, v, C, op->Z, C, B, C, d, plan, bc, 1.f);
     launch_softmax_jacobian(ctx, op->Z, plan.nsplit, bc, B, C, op->P);
-    launch_gemm(ctx, op->X, d, op->Z, C, hv, C, d, C, B, GemmPlan{1, (B + FK - 1) / FK * FK, d >= 2 * TM ? 2 : 1}, 0,
+    launch_gemm(ctx, op->X, d, op->Z, C, hv, C, d, C, B, GemmPlan{1, (B + FK - 1) / FK * FK, tile_rows_multiple(d, C, ctx->sm_count)}, 0,
                       1.f / (float)B);
     return FOSI_OK;
 }

@@ -40,8 +40,11 @@ def dev(a):
 # C = 1500, 2500: the softmax-Jacobian row kept in 8 registers per thread / too long for registers (two-pass kernel);
 # (96, 64, 36), (32, 32, 4): both contraction lengths multiples of 32 (whole K-steps: the variant with constant address
 # increments), ragged in M and N
+# (8192, 64, 1000), (64, 8192, 1000): 2048 output tiles of 64 x 64 in the first / the second product, which then takes
+# the 128-row tile; (8192, 72, 1000): the same with a contraction length that is not a whole number of K-steps
 @pytest.mark.parametrize("B,d,C", [(16, 8, 5), (1, 1, 1), (70, 200, 132), (130, 260, 100), (4, 4, 4), (100, 301, 130),
-                                   (65, 17, 64), (9, 12, 1500), (9, 12, 2500), (96, 64, 36), (32, 32, 4), (512, 2048, 1000)])
+                                   (65, 17, 64), (9, 12, 1500), (9, 12, 2500), (96, 64, 36), (32, 32, 4), (512, 2048, 1000),
+                                   (8192, 64, 1000), (64, 8192, 1000), (8192, 72, 1000)])
 def test_ggn_operator_matches_oracle(fo, ctx, B, d, C):
     g = wl.ggn_workload(B=B, d=d, C=C)
     op = ctx.hvp_softmax_ggn(dev(g.X), dev(g.W))
@@ -53,6 +56,25 @@ def test_ggn_operator_matches_oracle(fo, ctx, B, d, C):
         ref = oracle.hvp_softmax_ggn(g.X, g.W, v)
         assert rel_l2(out.cpu().numpy(), ref) <= GGN_RTOL
     op.close()
+
+
+@pytest.mark.parametrize("B,d,C", [(96, 64, 36), (512, 2048, 1000), (8192, 64, 1000), (64, 8192, 1000)])
+def test_ggn_operator_register_staged_kernels(fo, B, d, C, monkeypatch):
+    """FOSI_GGN_DIRECT=0 at context creation sends the shapes that normally load their tiles straight into LDS
+    through the register-staged kernels (the path of contraction lengths that are not whole K-steps)."""
+    monkeypatch.setenv("FOSI_GGN_DIRECT", "0")
+    c = fo.Context(0)
+    try:
+        g = wl.ggn_workload(B=B, d=d, C=C)
+        op = c.hvp_softmax_ggn(dev(g.X), dev(g.W))
+        v = wl.normal_vector(3, 63, g.n)
+        out = torch.zeros(g.n, device="cuda")
+        op.apply(dev(v), out)
+        c.synchronize()
+        assert rel_l2(out.cpu().numpy(), oracle.hvp_softmax_ggn(g.X, g.W, v)) <= GGN_RTOL
+        op.close()
+    finally:
+        c.close()
 
 
 def test_ggn_operator_properties(fo, ctx):
