@@ -611,6 +611,38 @@ def test_degenerate_inputs(fo, ctx):
     op.close()
 
 
+@pytest.mark.parametrize("n", [2, 3, 5, 7])
+def test_whole_path_on_a_handful_of_rows(fo, ctx, n):
+    """Fewer rows than a 16-byte row group, or barely more: no kernel has a full tile, everything runs through
+    the per-row tails.  Lanczos to exhaustion (m = n), every Ritz pair, one update with a dual variable."""
+    rng = np.random.default_rng(400 + n)
+    d = np.linspace(1.0, 2.0 + n, n).astype(np.float32)
+    v1 = rng.standard_normal(n).astype(np.float32)
+    op = ctx.hvp_diag(dev(d))
+    Q = fo.ColMajor(n, n + 1)
+    Q.col(0).copy_(dev(v1))
+    alpha, beta, m_eff = fo.fosi_lanczos(ctx, op, Q, n)
+    res = oracle.lanczos(lambda v: oracle.hvp_diag(d, v), v1, n)
+    assert m_eff == res.m_eff == n
+    k, l = (n + 1) // 2, n // 2
+    V = fo.ColMajor(n, n)
+    evals, _ = fo.fosi_ritz(ctx, Q, m_eff, alpha, beta, k, l, V)
+    rz = oracle.ritz(res.Q, res.alpha, res.beta, res.m_eff, k, l)
+    assert np.max(np.abs(evals - rz.evals) / np.abs(rz.evals)) <= EVAL_RTOL
+    assert np.max(np.abs(np.sort(evals) - np.sort(d.astype(np.float64)))) <= 1e-5 * d.max()   # m = n: the whole spectrum
+    Vg = V.to_numpy().astype(np.float64)
+    assert np.abs(Vg.T @ Vg - np.eye(n)).max() < 1e-5
+    w0, g, pi = (rng.standard_normal(n).astype(np.float32) for _ in range(3))
+    wd, md = dev(w0), torch.zeros(n, device="cuda")
+    sp = fo.StepParams(0.1, 0.01, 0.9, 5e-4, 0)
+    fo.fosi_step(ctx, V, n, evals, dev(g), dev(pi), md, wd, sp)
+    ctx.synchronize()
+    w_ref, b_ref = oracle.fosi_step(w0, g, Vg, evals, np.zeros(n), 0.1, 0.01, 0.9, sigma=5e-4, pi=pi.astype(np.float64))
+    assert rel_l2(wd.cpu().numpy().astype(np.float64) - w0, w_ref - w0) <= 5e-5
+    assert rel_l2(md.cpu().numpy(), b_ref) <= 5e-5 or np.linalg.norm(b_ref) < 1e-6
+    op.close()
+
+
 def test_callback_operator_matches_builtin(fo, ctx):
     n = 3000
     d = dev(np.linspace(0.5, 9.0, n))
