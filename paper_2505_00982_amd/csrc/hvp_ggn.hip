@@ -7,8 +7,11 @@
 // give every CU a tile; the partial products are summed inside the
 // softmax-Jacobian kernel, in a fixed order.  Both products take their A operand
 // k-major (K x M): the second one reads X as it is (k = batch index), the first
-// one a transposed copy of X made once per operator, so that every tile goes
-// into LDS with 16-byte writes.
+// one a transposed copy of X made once per operator, so that every tile is a set
+// of whole 16-byte groups along its rows.  Three kernels for the products: tiles
+// loaded from global memory straight into LDS (k_gemm_f32_direct; whole K-steps),
+// tiles staged through registers with masks (k_gemm_f32_aligned; any K), and a
+// scalar one for shapes that are not multiples of 4 (k_gemm_f32).
 #include "fosi_internal.h"
 
 namespace fosi {
