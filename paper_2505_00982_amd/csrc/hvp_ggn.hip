@@ -283,6 +283,15 @@ __global__ __launch_bounds__(256 * WM) void k_gemm_f32_aligned(const float* __re
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
+// Rendezvous of the workgroup with LDS-only ordering: the bare barrier intrinsic carries no memory semantics, so
+// nothing would forbid the compiler to move the LDS reads of the new tile above it; the two fences do (workgroup
+// scope, LDS address space only: they cost a wait for this wave's own LDS traffic, not for global memory).
+__device__ __forceinline__ void tile_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 template <int WM>
 __global__ __launch_bounds__(256 * WM) void k_gemm_f32_direct(const float* __restrict__ A, int lda,
                                                               const float* __restrict__ Bm, int ldb,
@@ -343,16 +352,18 @@ __global__ __launch_bounds__(256 * WM) void k_gemm_f32_direct(const float* __res
 
     issue(0, As0, Bs0);
     if (nk > 1) issue(1, As1, Bs1);
-    // one K-step: wait for this wave's part of tile kt (the younger tile may stay in flight), meet the other waves
-    // (their parts have landed too, and they are done with tile kt - 1), request this lane's operands from LDS,
-    // refill tile kt - 1's buffer, multiply.  The LDS reads are issued before the refill on purpose: the compiler
-    // makes an LDS read wait for every direct-to-LDS load it cannot tell apart from the read's own tile, and that is
-    // harmless here, where the only loads in flight are at least a K-step old.
+    // one K-step: wait for this wave's part of tile kt (the explicit count is what correctness needs: the younger
+    // tile may stay in flight; today's compiler, which knows that these loads write LDS, makes the release fence of
+    // the barrier wait for all of them, which measures the same), meet the other waves (their parts have landed
+    // too, and they are done with tile kt - 1), request this lane's operands from LDS, refill tile kt - 1's buffer,
+    // multiply.  The LDS reads are issued before the refill on purpose: the compiler makes an LDS read wait for
+    // every direct-to-LDS load it cannot tell apart from the read's own tile, and that is harmless here, where the
+    // only loads in flight are at least a K-step old.
 #define FOSI_KSTEP(kt, Ac, Bc, Ar, Br)                                                       \
     do {                                                                                     \
         if ((kt) + 1 < nk) __builtin_amdgcn_s_waitcnt(kWaitOneTileLeft);                     \
         else __builtin_amdgcn_s_waitcnt(kWaitAll);                                           \
-        __builtin_amdgcn_s_barrier();                                                        \
+        tile_barrier();                                                                      \
         fetch(Ac, Bc);                                                                       \
         __builtin_amdgcn_sched_barrier(0);                                                   \
         if ((kt) + 2 < nk) issue((kt) + 2, Ar, Br);                                          \
